@@ -1,0 +1,152 @@
+/*
+ * mixkv.h -- C ABI of libmixkv: MixKV's prefill-time KV-cache compression step
+ * on one MI355X (gfx950).
+ *
+ * For every layer l and KV head h the library scores each cached key, mixes an
+ * importance score with a diversity score according to the head's redundancy,
+ * keeps the top-B entries and gathers the kept K/V rows into a compacted cache
+ * (paper: Sec. 3.1 "KV Cache Compression" for the operator; Sec. 3.2 for the
+ * importance and diversity scores; Sec. 3.3, Eq. 3-5 for the redundancy and the
+ * head-wise mix; Appendix Algorithm 1 for the whole loop).
+ *
+ * Conventions
+ *   Pointers   Members of mixkv_layer_in / mixkv_layer_out and `workspace` are
+ *              DEVICE pointers owned by the caller.  The params struct and the
+ *              arrays of layer structs are HOST memory, read during the call only.
+ *   Ownership  The library allocates no device memory and keeps no state between
+ *              calls.  Two calls may run concurrently on different streams if they
+ *              use different workspaces and outputs.
+ *   Ordering   All work is enqueued on `hip_stream` (a hipStream_t, NULL = the
+ *              default stream).  Calls return without synchronising; outputs are
+ *              valid once the stream has been synchronised.
+ *   Errors     Every entry point returns a mixkv_status.  Arguments are validated
+ *              on the host before anything is launched; on an argument error no
+ *              output is touched.  HIP launch failures map to MIXKV_ERR_HIP.
+ *   Notation   N cached tokens (the paper's T), D head dim, W window length,
+ *              B budget per head (window included), B' = B - W (Algorithm 1),
+ *              Nc = N - W candidates, G = n_q_heads / n_kv_heads.
+ *   Layout     K, V: [batch, n_kv_heads, N, D], D contiguous, strides in elements.
+ *              Qwin: [batch, n_q_heads, W, D] contiguous; query head g serves KV
+ *              head g / G.  Row starts must be 16-byte aligned.
+ */
+#ifndef MIXKV_H
+#define MIXKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MIXKV_VERSION 1
+#define MIXKV_MAX_LAYERS 128      /* layers per call */
+#define MIXKV_MAX_WINDOW 64
+#define MIXKV_MAX_GROUP_ROWS 512  /* G * W */
+
+typedef enum {
+  MIXKV_OK = 0,
+  MIXKV_ERR_INVALID_ARG = 1,
+  MIXKV_ERR_UNSUPPORTED = 2,
+  MIXKV_ERR_WORKSPACE_TOO_SMALL = 3,
+  MIXKV_ERR_HIP = 4
+} mixkv_status;
+
+typedef enum { MIXKV_F32 = 0, MIXKV_BF16 = 1 } mixkv_dtype;
+typedef enum { MIXKV_POOL_NONE = 0, MIXKV_POOL_AVG = 1, MIXKV_POOL_MAX = 2 } mixkv_pool;
+typedef enum { MIXKV_BUDGET_FIXED = 0, MIXKV_BUDGET_HEAD_ADAPTIVE = 1 } mixkv_budget_mode;
+typedef enum { MIXKV_INTRINSIC_NONE = 0, MIXKV_INTRINSIC_VNORM = 1 } mixkv_intrinsic;
+typedef enum { MIXKV_MIX_HEAD_ADAPTIVE = 0 } mixkv_mix;
+
+typedef struct {
+  mixkv_dtype dtype;         /* element type of K, V, Qwin and of K_out, V_out */
+  int32_t batch;
+  int32_t n_q_heads;         /* multiple of n_kv_heads */
+  int32_t n_kv_heads;
+  int32_t head_dim;          /* D: 64 or 128 */
+  int32_t seq_len;           /* N >= 2, window included */
+  int32_t window;            /* 1 <= W <= MIXKV_MAX_WINDOW and W < N; the queries are the last W positions */
+  int32_t budget;            /* W <= B <= N rows kept per head (fixed mode) / on average (adaptive mode) */
+  mixkv_pool pool;           /* 1-D pooling of the window attention over candidates */
+  int32_t pool_kernel;       /* odd, 1..63; ignored for MIXKV_POOL_NONE */
+  int32_t causal_window;     /* 1: window query w (position Nc+w) attends to keys 0..Nc+w; 0: to all N keys */
+  float softmax_scale;       /* multiplies Q.K before the softmax; the library never rescales Q itself */
+  float eps;                 /* the epsilon of the paper's min-max and mean-matching formulas, > 0 */
+  mixkv_intrinsic intrinsic; /* VNORM: importance = attention + scaled value norm (Sec. 3.2, Eq. 2) */
+  mixkv_mix mix;             /* HEAD_ADAPTIVE: (1 - r) * importance + r * diversity (Sec. 3.3, Eq. 5) */
+  mixkv_budget_mode budget_mode;
+  int32_t budget_floor;      /* adaptive mode: minimum non-window rows per head, 0 <= floor <= B - W */
+} mixkv_params;
+
+/* One layer of the cache to compress. */
+typedef struct {
+  const void *K;             /* [batch, n_kv_heads, N, D] */
+  const void *V;             /* same shape and strides as K */
+  int64_t kv_stride_b, kv_stride_h, kv_stride_n;   /* in elements; kv_stride_n >= D */
+  const void *Qwin;          /* [batch, n_q_heads, W, D] contiguous, post-RoPE observation-window queries */
+} mixkv_layer_in;
+
+/* Outputs for one layer.  Which members are required is stated per entry point. */
+typedef struct {
+  float *scores;             /* [batch, n_kv_heads, N]: the mixed score s_comp at candidates, +inf at the W window slots */
+  float *redundancy;         /* [batch, n_kv_heads]: the head's redundancy r (Eq. 4) */
+  int32_t *indices;          /* kept positions, ascending per head, the W window positions last.
+                                fixed: [batch, n_kv_heads, B]; adaptive: [batch, n_kv_heads * B], heads packed back to back */
+  int32_t *counts;           /* [batch, n_kv_heads] rows kept per head (B in fixed mode) */
+  int32_t *offsets;          /* adaptive: [batch, n_kv_heads + 1] exclusive prefix sums of counts; may be NULL in fixed mode */
+  void *K_out, *V_out;       /* rows of K / V at `indices`, copied bit for bit, D contiguous.
+                                fixed: [batch, n_kv_heads, B, D]; adaptive: [batch, n_kv_heads * B, D] packed like indices */
+} mixkv_layer_out;
+
+/*
+ * Bytes of device workspace any of the three entry points needs for `n_layers`
+ * layers of this shape.  Host only; touches no GPU.  The workspace needs no
+ * initialisation and 256-byte alignment.
+ */
+mixkv_status mixkv_workspace_size(const mixkv_params *params, int32_t n_layers, size_t *bytes);
+
+/*
+ * Score every cached key (Algorithm 1, step 1 and the mixing half of step 2).
+ * Per (layer, batch item, KV head):
+ *   s_ex   mean over the G*W window queries of softmax attention on key i (Sec. 3.2,
+ *          extrinsic importance), pooled over candidates;
+ *   s_imp  s_ex + min-max normalised value norm scaled to mean(s_ex) (Sec. 3.2, Eq. 2);
+ *   s_div  -Khat_i . mean_j Khat_j with Khat the L2-normalised keys, all N keys in the mean
+ *          (Sec. 3.2, diversity metrics), min-max normalised and scaled to mean(s_imp) (Sec. 3.3);
+ *   r      (N^2 |mean Khat|^2 - N) / (N (N-1))   (Sec. 3.3, Eq. 3-4);
+ *   s_comp (1 - r) s_imp + r s_div_scaled         (Sec. 3.3, Eq. 5).
+ * All minima, maxima and means are over the Nc candidates.
+ * Writes out[l].scores (required) and out[l].redundancy (optional, may be NULL).
+ */
+mixkv_status mixkv_score(const mixkv_params *params, const mixkv_layer_in *in, mixkv_layer_out *out,
+                         int32_t n_layers, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * TopB on caller-provided scores (Sec. 3.1; Algorithm 1, TopB step with B' = B - W and the
+ * window excluded from ranking and always kept).  Reads out[l].scores (only the Nc candidate
+ * slots are read); writes out[l].indices, out[l].counts and, if non-NULL, out[l].offsets
+ * (required in adaptive mode).  Ties go to the smaller position.  NaN scores are not supported.
+ * Fixed mode: each head keeps its B' best candidates.  Head-adaptive mode, per (layer, batch
+ * item): every head keeps its budget_floor best candidates, then the remaining
+ * n_kv_heads * (B' - budget_floor) slots go to the best remaining candidates of all heads
+ * together (ties: smaller head, then smaller position).
+ */
+mixkv_status mixkv_select(const mixkv_params *params, mixkv_layer_out *out, int32_t n_layers,
+                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * The whole step (Algorithm 1): score, select, and gather the kept K/V rows (Sec. 3.1,
+ * Khat, Vhat = TopB(K, V, {s_i})).  Writes indices, counts, K_out, V_out (all required),
+ * offsets (required in adaptive mode), and scores / redundancy when non-NULL.
+ * K_out / V_out must not overlap K / V.
+ */
+mixkv_status mixkv_compress(const mixkv_params *params, const mixkv_layer_in *in, mixkv_layer_out *out,
+                            int32_t n_layers, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+const char *mixkv_status_string(mixkv_status status);
+int32_t mixkv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MIXKV_H */

@@ -1,0 +1,207 @@
+"""ctypes binding of libmixkv (see include/mixkv.h).  Argument marshalling only.
+
+Every function here has the name of the C entry point it calls and does nothing
+but build the C structs from torch tensors (device memory and the current HIP
+stream come from torch) and check the returned status.  There is no fallback:
+if the shared library has not been built, `lib()` raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmixkv.so")
+
+MIXKV_OK, MIXKV_ERR_INVALID_ARG, MIXKV_ERR_UNSUPPORTED, MIXKV_ERR_WORKSPACE_TOO_SMALL, MIXKV_ERR_HIP = range(5)
+DTYPE = {"f32": 0, "bf16": 1}
+POOL = {"none": 0, "avg": 1, "max": 2}
+BUDGET_MODE = {"fixed": 0, "adaptive": 1}
+INTRINSIC = {"none": 0, "vnorm": 1}
+TORCH_DTYPE = {0: torch.float32, 1: torch.bfloat16}
+
+
+class MixkvParams(C.Structure):
+    _fields_ = [
+        ("dtype", C.c_int), ("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+        ("head_dim", C.c_int32), ("seq_len", C.c_int32), ("window", C.c_int32), ("budget", C.c_int32),
+        ("pool", C.c_int), ("pool_kernel", C.c_int32), ("causal_window", C.c_int32),
+        ("softmax_scale", C.c_float), ("eps", C.c_float), ("intrinsic", C.c_int), ("mix", C.c_int),
+        ("budget_mode", C.c_int), ("budget_floor", C.c_int32),
+    ]
+
+
+class MixkvLayerIn(C.Structure):
+    _fields_ = [("K", C.c_void_p), ("V", C.c_void_p), ("kv_stride_b", C.c_int64), ("kv_stride_h", C.c_int64),
+                ("kv_stride_n", C.c_int64), ("Qwin", C.c_void_p)]
+
+
+class MixkvLayerOut(C.Structure):
+    _fields_ = [("scores", C.c_void_p), ("redundancy", C.c_void_p), ("indices", C.c_void_p), ("counts", C.c_void_p),
+                ("offsets", C.c_void_p), ("K_out", C.c_void_p), ("V_out", C.c_void_p)]
+
+
+class MixkvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libmixkv.so (built by `python -m paper_2510_20707_amd.build`)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2510_20707_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        pp, pin, pout = C.POINTER(MixkvParams), C.POINTER(MixkvLayerIn), C.POINTER(MixkvLayerOut)
+        L.mixkv_workspace_size.argtypes = [pp, C.c_int32, C.POINTER(C.c_size_t)]
+        L.mixkv_workspace_size.restype = C.c_int
+        L.mixkv_score.argtypes = [pp, pin, pout, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.mixkv_score.restype = C.c_int
+        L.mixkv_select.argtypes = [pp, pout, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.mixkv_select.restype = C.c_int
+        L.mixkv_compress.argtypes = [pp, pin, pout, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.mixkv_compress.restype = C.c_int
+        L.mixkv_status_string.argtypes = [C.c_int]
+        L.mixkv_status_string.restype = C.c_char_p
+        L.mixkv_version.argtypes = []
+        L.mixkv_version.restype = C.c_int32
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().mixkv_status_string(status).decode()
+
+
+def make_params(dtype: str, batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, seq_len: int, window: int,
+                budget: int, pool: str = "max", pool_kernel: int = 7, causal_window: bool = True,
+                softmax_scale: float = 1.0, eps: float = 1e-6, intrinsic: str = "vnorm",
+                budget_mode: str = "fixed", budget_floor: int = 0) -> MixkvParams:
+    return MixkvParams(DTYPE[dtype], batch, n_q_heads, n_kv_heads, head_dim, seq_len, window, budget, POOL[pool],
+                       pool_kernel, int(causal_window), softmax_scale, eps, INTRINSIC[intrinsic], 0,
+                       BUDGET_MODE[budget_mode], budget_floor)
+
+
+@dataclass
+class LayerOut:
+    """Device tensors receiving one layer's outputs; members may be None where the C API allows NULL."""
+    scores: Optional[torch.Tensor] = None        # [batch, Hkv, N] f32
+    redundancy: Optional[torch.Tensor] = None    # [batch, Hkv] f32
+    indices: Optional[torch.Tensor] = None       # [batch, Hkv, B] i32 (adaptive: packed per batch item)
+    counts: Optional[torch.Tensor] = None        # [batch, Hkv] i32
+    offsets: Optional[torch.Tensor] = None       # [batch, Hkv + 1] i32
+    K_out: Optional[torch.Tensor] = None         # [batch, Hkv, B, D]
+    V_out: Optional[torch.Tensor] = None
+
+
+def alloc_layer_out(p: MixkvParams, device, scores=True, redundancy=True, select=True, gather=True) -> LayerOut:
+    """Allocate one layer's outputs with torch (plumbing for tests and the benchmark)."""
+    o = LayerOut()
+    bt, h, n, b, d = p.batch, p.n_kv_heads, p.seq_len, p.budget, p.head_dim
+    if scores:
+        o.scores = torch.empty((bt, h, n), dtype=torch.float32, device=device)
+    if redundancy:
+        o.redundancy = torch.empty((bt, h), dtype=torch.float32, device=device)
+    if select:
+        o.indices = torch.empty((bt, h, b), dtype=torch.int32, device=device)
+        o.counts = torch.empty((bt, h), dtype=torch.int32, device=device)
+        o.offsets = torch.empty((bt, h + 1), dtype=torch.int32, device=device)
+    if gather:
+        o.K_out = torch.empty((bt, h, b, d), dtype=TORCH_DTYPE[p.dtype], device=device)
+        o.V_out = torch.empty((bt, h, b, d), dtype=TORCH_DTYPE[p.dtype], device=device)
+    return o
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _in_array(Ks, Vs, Qs):
+    n = len(Ks)
+    arr = (MixkvLayerIn * n)()
+    for i, (K, V, Q) in enumerate(zip(Ks, Vs, Qs)):
+        assert K.dim() == 4 and K.stride(3) == 1 and V.shape == K.shape and V.stride() == K.stride()
+        assert Q is None or Q.is_contiguous()
+        arr[i] = MixkvLayerIn(K.data_ptr(), V.data_ptr(), K.stride(0), K.stride(1), K.stride(2),
+                              None if Q is None else Q.data_ptr())
+    return arr
+
+
+def _out_array(outs: Sequence[LayerOut]):
+    arr = (MixkvLayerOut * len(outs))()
+    for i, o in enumerate(outs):
+        arr[i] = MixkvLayerOut(_ptr(o.scores), _ptr(o.redundancy), _ptr(o.indices), _ptr(o.counts), _ptr(o.offsets),
+                               _ptr(o.K_out), _ptr(o.V_out))
+    return arr
+
+
+def _stream(stream) -> C.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _check(status: int, where: str):
+    if status != MIXKV_OK:
+        raise MixkvError(status, where)
+
+
+def mixkv_workspace_size(p: MixkvParams, n_layers: int) -> int:
+    n = C.c_size_t(0)
+    _check(lib().mixkv_workspace_size(C.byref(p), n_layers, C.byref(n)), "mixkv_workspace_size")
+    return n.value
+
+
+def alloc_workspace(p: MixkvParams, n_layers: int, device) -> torch.Tensor:
+    return torch.empty(mixkv_workspace_size(p, n_layers), dtype=torch.uint8, device=device)
+
+
+def _ws(workspace: Optional[torch.Tensor]):
+    if workspace is None:
+        return None, 0
+    return C.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()
+
+
+def mixkv_score(p: MixkvParams, Ks, Vs, Qs, outs: Sequence[LayerOut], workspace: torch.Tensor, stream=None):
+    wp, wb = _ws(workspace)
+    _check(lib().mixkv_score(C.byref(p), _in_array(Ks, Vs, Qs), _out_array(outs), len(outs), wp, wb, _stream(stream)),
+           "mixkv_score")
+
+
+def mixkv_select(p: MixkvParams, outs: Sequence[LayerOut], workspace: Optional[torch.Tensor] = None, stream=None):
+    wp, wb = _ws(workspace)
+    _check(lib().mixkv_select(C.byref(p), _out_array(outs), len(outs), wp, wb, _stream(stream)), "mixkv_select")
+
+
+def mixkv_compress(p: MixkvParams, Ks, Vs, Qs, outs: Sequence[LayerOut], workspace: torch.Tensor, stream=None):
+    wp, wb = _ws(workspace)
+    _check(lib().mixkv_compress(C.byref(p), _in_array(Ks, Vs, Qs), _out_array(outs), len(outs), wp, wb,
+                                _stream(stream)), "mixkv_compress")
+
+
+class PreparedCall:
+    """The C argument arrays of one call, built once (so a timed loop measures the library, not ctypes)."""
+
+    def __init__(self, p: MixkvParams, Ks, Vs, Qs, outs: Sequence[LayerOut], workspace: torch.Tensor):
+        self.p, self.n = p, len(outs)
+        self.ins, self.outs = _in_array(Ks, Vs, Qs), _out_array(outs)
+        self.wp, self.wb = _ws(workspace)
+        self._keep = (Ks, Vs, Qs, outs, workspace)
+        self._L = lib()
+
+    def compress(self, stream=None):
+        _check(self._L.mixkv_compress(C.byref(self.p), self.ins, self.outs, self.n, self.wp, self.wb, _stream(stream)),
+               "mixkv_compress")
+
+    def score(self, stream=None):
+        _check(self._L.mixkv_score(C.byref(self.p), self.ins, self.outs, self.n, self.wp, self.wb, _stream(stream)),
+               "mixkv_score")

@@ -1,0 +1,199 @@
+// Host side of libmixkv: argument validation, workspace carve-up and the launch sequence.
+#include <cmath>
+#include <cstring>
+
+#include "mixkv_internal.h"
+
+namespace mixkv {
+
+int stream_chunk_keys();
+int max_adaptive_heads();
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+mixkv_status make_shape(const mixkv_params *p, Shape *s) {
+  if (!p || !s) return MIXKV_ERR_INVALID_ARG;
+  if (p->dtype != MIXKV_F32 && p->dtype != MIXKV_BF16) return MIXKV_ERR_INVALID_ARG;
+  if (p->batch < 1 || p->n_q_heads < 1 || p->n_kv_heads < 1) return MIXKV_ERR_INVALID_ARG;
+  if (p->n_q_heads % p->n_kv_heads != 0) return MIXKV_ERR_INVALID_ARG;
+  if (p->head_dim != 64 && p->head_dim != 128) return MIXKV_ERR_UNSUPPORTED;
+  if (p->seq_len < 2) return MIXKV_ERR_INVALID_ARG;
+  if (p->window < 1 || p->window >= p->seq_len) return MIXKV_ERR_INVALID_ARG;
+  if (p->window > MIXKV_MAX_WINDOW) return MIXKV_ERR_UNSUPPORTED;
+  if (p->budget < p->window || p->budget > p->seq_len) return MIXKV_ERR_INVALID_ARG;
+  if (p->pool != MIXKV_POOL_NONE && p->pool != MIXKV_POOL_AVG && p->pool != MIXKV_POOL_MAX) return MIXKV_ERR_INVALID_ARG;
+  if (p->pool != MIXKV_POOL_NONE && (p->pool_kernel < 1 || p->pool_kernel > 63 || p->pool_kernel % 2 == 0))
+    return MIXKV_ERR_INVALID_ARG;
+  if (p->causal_window != 0 && p->causal_window != 1) return MIXKV_ERR_INVALID_ARG;
+  if (!(p->softmax_scale > 0.f) || !std::isfinite(p->softmax_scale)) return MIXKV_ERR_INVALID_ARG;
+  if (!(p->eps > 0.f) || !std::isfinite(p->eps)) return MIXKV_ERR_INVALID_ARG;
+  if (p->intrinsic != MIXKV_INTRINSIC_NONE && p->intrinsic != MIXKV_INTRINSIC_VNORM) return MIXKV_ERR_INVALID_ARG;
+  if (p->mix != MIXKV_MIX_HEAD_ADAPTIVE) return MIXKV_ERR_UNSUPPORTED;
+  if (p->budget_mode != MIXKV_BUDGET_FIXED && p->budget_mode != MIXKV_BUDGET_HEAD_ADAPTIVE) return MIXKV_ERR_INVALID_ARG;
+  const int G = p->n_q_heads / p->n_kv_heads;
+  if ((int64_t)G * p->window > MIXKV_MAX_GROUP_ROWS) return MIXKV_ERR_UNSUPPORTED;
+  if (p->budget_mode == MIXKV_BUDGET_HEAD_ADAPTIVE) {
+    if (p->budget_floor < 0 || p->budget_floor > p->budget - p->window) return MIXKV_ERR_INVALID_ARG;
+    if (p->n_kv_heads > max_adaptive_heads()) return MIXKV_ERR_UNSUPPORTED;
+    if ((int64_t)p->n_kv_heads * (p->seq_len - p->window) > INT32_MAX) return MIXKV_ERR_UNSUPPORTED;
+  }
+  if ((int64_t)p->batch * kLayersPerLaunch > 65535) return MIXKV_ERR_UNSUPPORTED;
+  if ((int64_t)p->batch * p->n_kv_heads * p->seq_len > INT32_MAX) return MIXKV_ERR_UNSUPPORTED;
+
+  s->batch = p->batch; s->hq = p->n_q_heads; s->hkv = p->n_kv_heads; s->G = G; s->D = p->head_dim;
+  s->N = p->seq_len; s->W = p->window; s->Nc = s->N - s->W; s->B = p->budget; s->Bp = s->B - s->W;
+  s->GW = G * s->W;
+  s->QT = (s->GW + 31) / 32;
+  s->chunk = stream_chunk_keys();
+  s->nchunks = (s->N + s->chunk - 1) / s->chunk;
+  s->Npad = s->nchunks * s->chunk;
+  s->units_per_layer = s->batch * s->hkv;
+  s->pool = p->pool; s->pool_k = p->pool == MIXKV_POOL_NONE ? 1 : p->pool_kernel;
+  s->causal = p->causal_window; s->intrinsic = p->intrinsic;
+  s->adaptive = p->budget_mode == MIXKV_BUDGET_HEAD_ADAPTIVE; s->floor_ = s->adaptive ? p->budget_floor : 0;
+  s->scale_log2e = (float)((double)p->softmax_scale * 1.4426950408889634);
+  s->eps = p->eps;
+  return MIXKV_OK;
+}
+
+void carve_workspace(const Shape &s, int64_t units, Workspace *w) {
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  const size_t QTR = (size_t)s.QT * 32;
+  w->counters = take((size_t)units * 4);
+  w->part_ml = take((size_t)units * s.nchunks * QTR * 8);
+  w->part_ksum = take((size_t)units * s.nchunks * s.D * 4);
+  w->brow = take((size_t)units * QTR * 4);
+  w->kbar = take((size_t)units * 2 * s.D * 4);
+  w->rbar = take((size_t)units * 4);
+  w->invnorm = take((size_t)units * s.Npad * 4);
+  w->vnorm = take((size_t)units * s.Npad * 4);
+  w->araw = take((size_t)units * s.Npad * 4);
+  w->sdiv = take((size_t)units * s.Npad * 4);
+  w->scores = take((size_t)units * s.N * 4);
+  w->total = off;
+}
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+enum Stage { kScore = 1, kSelect = 2, kGather = 4 };
+
+static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mixkv_layer_out *out, int32_t n_layers,
+                        void *workspace, size_t workspace_bytes, void *hip_stream, int stages) {
+  Shape s;
+  mixkv_status st = make_shape(params, &s);
+  if (st != MIXKV_OK) return st;
+  if (n_layers < 1 || n_layers > MIXKV_MAX_LAYERS || !out) return MIXKV_ERR_INVALID_ARG;
+  if ((stages & (kScore | kGather)) && !in) return MIXKV_ERR_INVALID_ARG;
+  const int eb = params->dtype == MIXKV_BF16 ? 2 : 4;
+  const int64_t units = (int64_t)n_layers * s.units_per_layer;
+  Workspace w;
+  carve_workspace(s, units, &w);
+  if (stages & kScore) {   // selection on caller-provided scores needs no workspace
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return MIXKV_ERR_INVALID_ARG;
+    if (workspace_bytes < w.total) return MIXKV_ERR_WORKSPACE_TOO_SMALL;
+  }
+
+  for (int l = 0; l < n_layers; ++l) {
+    if (stages & (kScore | kGather)) {
+      const mixkv_layer_in &li = in[l];
+      if (!li.K || !li.V || !aligned16(li.K) || !aligned16(li.V)) return MIXKV_ERR_INVALID_ARG;
+      if (li.kv_stride_n < s.D || li.kv_stride_h < 0 || li.kv_stride_b < 0) return MIXKV_ERR_INVALID_ARG;
+      if ((li.kv_stride_n * eb) % 16 || (li.kv_stride_h * eb) % 16 || (li.kv_stride_b * eb) % 16) return MIXKV_ERR_INVALID_ARG;
+      if ((stages & kScore) && (!li.Qwin || !aligned16(li.Qwin))) return MIXKV_ERR_INVALID_ARG;
+    }
+    const mixkv_layer_out &lo = out[l];
+    if (stages == kScore && !lo.scores) return MIXKV_ERR_INVALID_ARG;
+    if (stages == kSelect && !lo.scores) return MIXKV_ERR_INVALID_ARG;
+    if (stages & kSelect) {
+      if (!lo.indices || !lo.counts) return MIXKV_ERR_INVALID_ARG;
+      if (s.adaptive && !lo.offsets) return MIXKV_ERR_INVALID_ARG;
+    }
+    if (stages & kGather) {
+      if (!lo.K_out || !lo.V_out || !aligned16(lo.K_out) || !aligned16(lo.V_out)) return MIXKV_ERR_INVALID_ARG;
+    }
+  }
+
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  char *ws = reinterpret_cast<char *>(workspace);
+  if (stages & kScore) {
+    if (launch_zero_counters(reinterpret_cast<int32_t *>(ws + w.counters), units, stream) != hipSuccess) return MIXKV_ERR_HIP;
+  }
+  for (int l0 = 0; l0 < n_layers; l0 += kLayersPerLaunch) {
+    const int nl = (n_layers - l0 < kLayersPerLaunch) ? n_layers - l0 : kLayersPerLaunch;
+    LayerInTable ti;
+    LayerOutTable to;
+    std::memset(&ti, 0, sizeof(ti));
+    std::memset(&to, 0, sizeof(to));
+    const int64_t unit0 = (int64_t)l0 * s.units_per_layer;
+    for (int l = 0; l < nl; ++l) {
+      if (in) {
+        const mixkv_layer_in &li = in[l0 + l];
+        ti.l[l] = LayerIn{li.K, li.V, li.Qwin, li.kv_stride_b, li.kv_stride_h, li.kv_stride_n};
+      }
+      const mixkv_layer_out &lo = out[l0 + l];
+      float *scores = lo.scores;
+      if (!scores) scores = reinterpret_cast<float *>(ws + w.scores) + (unit0 + (int64_t)l * s.units_per_layer) * s.N;
+      to.l[l] = LayerOut{scores, lo.redundancy, lo.indices, lo.counts, lo.offsets, lo.K_out, lo.V_out};
+    }
+    const int nunits = nl * s.units_per_layer;
+    if (stages & kScore) {
+      if (launch_stats(s, params->dtype, ti, to, ws, w, unit0, nunits, stream) != hipSuccess) return MIXKV_ERR_HIP;
+      if (launch_attn(s, params->dtype, ti, ws, w, unit0, nunits, stream) != hipSuccess) return MIXKV_ERR_HIP;
+      if (launch_mix(s, to, ws, w, unit0, nunits, stream) != hipSuccess) return MIXKV_ERR_HIP;
+    }
+    if (stages & kSelect) {
+      if (launch_select(s, to, nl, stream) != hipSuccess) return MIXKV_ERR_HIP;
+    }
+    if (stages & kGather) {
+      if (launch_gather(s, params->dtype, ti, to, nl, stream) != hipSuccess) return MIXKV_ERR_HIP;
+    }
+  }
+  return MIXKV_OK;
+}
+
+}  // namespace mixkv
+
+extern "C" {
+
+mixkv_status mixkv_workspace_size(const mixkv_params *params, int32_t n_layers, size_t *bytes) {
+  mixkv::Shape s;
+  mixkv_status st = mixkv::make_shape(params, &s);
+  if (st != MIXKV_OK) return st;
+  if (!bytes || n_layers < 1 || n_layers > MIXKV_MAX_LAYERS) return MIXKV_ERR_INVALID_ARG;
+  mixkv::Workspace w;
+  mixkv::carve_workspace(s, (int64_t)n_layers * s.units_per_layer, &w);
+  *bytes = w.total;
+  return MIXKV_OK;
+}
+
+mixkv_status mixkv_score(const mixkv_params *params, const mixkv_layer_in *in, mixkv_layer_out *out, int32_t n_layers,
+                         void *workspace, size_t workspace_bytes, void *hip_stream) {
+  return mixkv::run(params, in, out, n_layers, workspace, workspace_bytes, hip_stream, mixkv::kScore);
+}
+
+mixkv_status mixkv_select(const mixkv_params *params, mixkv_layer_out *out, int32_t n_layers, void *workspace,
+                          size_t workspace_bytes, void *hip_stream) {
+  return mixkv::run(params, nullptr, out, n_layers, workspace, workspace_bytes, hip_stream, mixkv::kSelect);
+}
+
+mixkv_status mixkv_compress(const mixkv_params *params, const mixkv_layer_in *in, mixkv_layer_out *out,
+                            int32_t n_layers, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  return mixkv::run(params, in, out, n_layers, workspace, workspace_bytes, hip_stream,
+                    mixkv::kScore | mixkv::kSelect | mixkv::kGather);
+}
+
+const char *mixkv_status_string(mixkv_status status) {
+  switch (status) {
+    case MIXKV_OK: return "ok";
+    case MIXKV_ERR_INVALID_ARG: return "invalid argument";
+    case MIXKV_ERR_UNSUPPORTED: return "unsupported configuration";
+    case MIXKV_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case MIXKV_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+int32_t mixkv_version(void) { return MIXKV_VERSION; }
+
+}  // extern "C"

@@ -1,0 +1,75 @@
+// Internal declarations shared by the libmixkv translation units (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "mixkv.h"
+
+namespace mixkv {
+
+constexpr int kWave = 64;
+constexpr int kTileKeys = 32;          // keys per MFMA tile
+constexpr int kLayersPerLaunch = 32;   // pointer-table entries that fit in one kernel-argument block
+constexpr int kSelectThreads = 1024;
+
+// Per-layer device pointers handed to the kernels by value.
+struct LayerIn {
+  const void *K, *V, *Q;
+  int64_t sb, sh, sn;                  // K/V strides in elements
+};
+struct LayerInTable { LayerIn l[kLayersPerLaunch]; };
+
+struct LayerOut {
+  float *scores;                       // may point into the workspace
+  float *redundancy;                   // may be null
+  int32_t *indices, *counts, *offsets; // offsets may be null (fixed mode)
+  void *K_out, *V_out;
+};
+struct LayerOutTable { LayerOut l[kLayersPerLaunch]; };
+
+// Problem shape, identical for every layer of a call.
+struct Shape {
+  int32_t batch, hq, hkv, G, D, N, W, Nc, B, Bp;   // Bp = B - W
+  int32_t GW;            // G * W query rows per KV head
+  int32_t QT;            // ceil(GW / 32) query tiles
+  int32_t chunk;         // keys per workgroup in the two streaming kernels
+  int32_t nchunks;       // ceil(N / chunk)
+  int32_t Npad;          // nchunks * chunk, row length of the per-unit float arrays
+  int32_t units_per_layer;
+  int32_t pool, pool_k, causal, intrinsic, adaptive, floor_;
+  float scale_log2e;     // softmax_scale * log2(e)
+  float eps;
+};
+
+// Workspace carve-up (byte offsets from a 256-byte aligned base).  Sizes are per call (all units).
+struct Workspace {
+  size_t counters;       // int32 [units]
+  size_t part_ml;        // float2 [units][nchunks][QT*32]   running (max, sum) of each softmax row, log2 domain
+  size_t part_ksum;      // float  [units][nchunks][D]       partial sums of normalised keys
+  size_t brow;           // float  [units][QT*32]            per-row exponent offset: max + log2(sum * G*W)
+  size_t kbar;           // float  [units][2][D]             mean normalised key, split hi / lo for bf16
+  size_t rbar;           // float  [units]
+  size_t invnorm;        // float  [units][Npad]             1 / |K_i|
+  size_t vnorm;          // float  [units][Npad]             |V_i|
+  size_t araw;           // float  [units][Npad]             window/group mean attention before pooling
+  size_t sdiv;           // float  [units][Npad]             -Khat_i . Kbar
+  size_t scores;         // float  [units][N]                used when the caller passes no scores buffer
+  size_t total;
+};
+
+mixkv_status make_shape(const mixkv_params *p, Shape *s);
+void carve_workspace(const Shape &s, int64_t units, Workspace *w);
+
+// Kernel launchers (one per pipeline stage).  `unit0` is the first unit of this launch group,
+// `nunits` the number of units it covers (whole layers).
+hipError_t launch_zero_counters(int32_t *counters, int64_t n, hipStream_t st);
+hipError_t launch_stats(const Shape &s, int dtype, const LayerInTable &in, const LayerOutTable &out, char *ws,
+                        const Workspace &w, int64_t unit0, int nunits, hipStream_t st);
+hipError_t launch_attn(const Shape &s, int dtype, const LayerInTable &in, char *ws, const Workspace &w,
+                       int64_t unit0, int nunits, hipStream_t st);
+hipError_t launch_mix(const Shape &s, const LayerOutTable &out, char *ws, const Workspace &w, int64_t unit0,
+                      int nunits, hipStream_t st);
+hipError_t launch_select(const Shape &s, const LayerOutTable &out, int nlayers, hipStream_t st);
+hipError_t launch_gather(const Shape &s, int dtype, const LayerInTable &in, const LayerOutTable &out, int nlayers,
+                         hipStream_t st);
+
+}  // namespace mixkv

@@ -1,0 +1,176 @@
+"""Shared plumbing of the GPU parity tests: upload a synthetic layer, call the C ABI through the
+binding, run the oracle on the same values, and compare by the rules stated below.
+
+Comparison rules (written out here so the tolerance is visible in the tests):
+  * mixed scores: |gpu_i - ora_i| <= tol * max(|ora_i|, mean_j |ora_j|) per unit, tol = 2e-3 for
+    bf16 inputs and 1e-5 for fp32 inputs;
+  * redundancy r: absolute 1e-5 (bf16) / 1e-6 (fp32);
+  * kept index sets: exactly b' unique candidates, ascending, window last; with tau the b'-th
+    largest oracle score and band = tol * max(|tau|, mean|s|): every candidate with
+    s > tau + band is kept, none with s < tau - band is kept (so the sets are identical unless
+    candidates lie inside the band);
+  * gathered rows: bit-identical to the source rows at the returned indices.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import mixkv_oracle as O
+from paper_2510_20707_amd import binding as B
+from paper_2510_20707_amd import synth
+
+TOL = {"bf16": 2e-3, "f32": 1e-5}
+RTOL_R = {"bf16": 1e-5, "f32": 1e-6}
+
+
+def oracle_params(wl: synth.Workload, **over) -> O.Params:
+    kw = dict(n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, window=wl.window, budget=wl.budget, pool=wl.pool,
+              pool_kernel=wl.pool_kernel, causal_window=True, softmax_scale=wl.softmax_scale, eps=wl.eps,
+              intrinsic="vnorm", budget_mode=wl.budget_mode, budget_floor=wl.budget_floor)
+    kw.update(over)
+    return O.Params(**kw)
+
+
+def gpu_params(wl: synth.Workload, **over) -> B.MixkvParams:
+    kw = dict(dtype=wl.dtype, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, head_dim=wl.head_dim,
+              seq_len=wl.seq_len, window=wl.window, budget=wl.budget, pool=wl.pool, pool_kernel=wl.pool_kernel,
+              causal_window=True, softmax_scale=wl.softmax_scale, eps=wl.eps, intrinsic="vnorm",
+              budget_mode=wl.budget_mode, budget_floor=wl.budget_floor)
+    kw.update(over)
+    return B.make_params(**kw)
+
+
+def to_device(wl: synth.Workload, arr: np.ndarray, device="cuda:0") -> torch.Tensor:
+    """Upload an array of values that are exactly representable in wl.dtype."""
+    if wl.dtype == "bf16":
+        bits = synth.round_to_bf16_bits(arr)
+        return torch.from_numpy(bits.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(arr, dtype=np.float32)).to(device)
+
+
+def to_host_bits(t: torch.Tensor) -> np.ndarray:
+    """Raw element bits of a device tensor (uint16 for bf16, uint32 for f32)."""
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.view(torch.int32).cpu().numpy().view(np.uint32)
+
+
+def host_bits(wl: synth.Workload, arr: np.ndarray) -> np.ndarray:
+    if wl.dtype == "bf16":
+        return synth.round_to_bf16_bits(arr)
+    return np.ascontiguousarray(arr, dtype=np.float32).view(np.uint32)
+
+
+def run_compress(wl: synth.Workload, layers, device="cuda:0", want_scores=True, **over):
+    """mixkv_compress on a list of synth.Layer.  Returns (params, list of LayerOut on device)."""
+    p = gpu_params(wl, **over)
+    Ks = [to_device(wl, l.K, device) for l in layers]
+    Vs = [to_device(wl, l.V, device) for l in layers]
+    Qs = [to_device(wl, l.Q, device) for l in layers]
+    outs = [B.alloc_layer_out(p, device, scores=want_scores) for _ in layers]
+    ws = B.alloc_workspace(p, len(layers), device)
+    B.mixkv_compress(p, Ks, Vs, Qs, outs, ws)
+    torch.cuda.synchronize()
+    return p, outs
+
+
+def check_scores(dtype, gpu, ora, what=""):
+    tol = TOL[dtype]
+    ref = np.maximum(np.abs(ora), np.abs(ora).mean())
+    err = np.abs(gpu.astype(np.float64) - ora) / ref
+    assert np.all(np.isfinite(gpu)), f"{what}: non-finite GPU score"
+    assert err.max() <= tol, f"{what}: score error {err.max():.3e} > {tol} at {int(err.argmax())}"
+    return float(err.max())
+
+
+def check_topk_set(dtype, kept: np.ndarray, s_ora: np.ndarray, k: int, what=""):
+    """`kept` (candidate indices) is a valid top-k of the oracle scores up to the tolerance band."""
+    assert kept.shape[0] == k, f"{what}: kept {kept.shape[0]} != {k}"
+    if k == 0:
+        return 0
+    assert np.all(np.diff(kept) > 0), f"{what}: kept indices not strictly ascending"
+    assert kept[0] >= 0 and kept[-1] < s_ora.shape[0], f"{what}: index out of range"
+    if k == s_ora.shape[0]:
+        return 0
+    tau = np.sort(s_ora)[::-1][k - 1]
+    band = TOL[dtype] * max(abs(tau), np.abs(s_ora).mean())
+    must = np.nonzero(s_ora > tau + band)[0]
+    never = np.nonzero(s_ora < tau - band)[0]
+    keptset = set(kept.tolist())
+    missing = [i for i in must.tolist() if i not in keptset]
+    wrong = [i for i in never.tolist() if i in keptset]
+    assert not missing, f"{what}: clear winners not kept: {missing[:5]}"
+    assert not wrong, f"{what}: clear losers kept: {wrong[:5]}"
+    return int(((s_ora >= tau - band) & (s_ora <= tau + band)).sum())   # band population (k-th itself included)
+
+
+def check_layer(wl: synth.Workload, lay: synth.Layer, p: B.MixkvParams, out: B.LayerOut, units=None, **over):
+    """Compare one layer of GPU output with the oracle.  `units`: iterable of (b, h) to check with
+    the oracle (default all); invariants are checked on every unit."""
+    op = oracle_params(wl, **over)
+    Bt, Hkv, N, D, W = wl.batch, wl.n_kv_heads, wl.seq_len, wl.head_dim, wl.window
+    Bud = op.budget
+    Nc, G = N - W, wl.group
+    adaptive = op.budget_mode == "adaptive"
+    idx_g = out.indices.cpu().numpy().reshape(Bt, Hkv * Bud)
+    cnt_g = out.counts.cpu().numpy()
+    off_g = out.offsets.cpu().numpy()
+    sc_g = out.scores.cpu().numpy() if out.scores is not None else None
+    red_g = out.redundancy.cpu().numpy() if out.redundancy is not None else None
+    Kb, Vb = host_bits(wl, lay.K), host_bits(wl, lay.V)
+    Ko = to_host_bits(out.K_out).reshape(Bt, Hkv * Bud, D)
+    Vo = to_host_bits(out.V_out).reshape(Bt, Hkv * Bud, D)
+    todo = set(units) if units is not None else {(b, h) for b in range(Bt) for h in range(Hkv)}
+    stats = dict(max_err=0.0, band=0, exact=0, checked=0)
+    for b in range(Bt):
+        assert cnt_g[b].sum() == Hkv * Bud
+        np.testing.assert_array_equal(off_g[b], np.concatenate([[0], np.cumsum(cnt_g[b])]))
+        s_ora_heads = {}
+        for h in range(Hkv):
+            lo, c = int(off_g[b, h]), int(cnt_g[b, h])
+            idx = idx_g[b, lo:lo + c]
+            if not adaptive:
+                assert c == Bud
+            assert c >= W + (op.budget_floor if adaptive else 0)
+            np.testing.assert_array_equal(idx[c - W:], np.arange(Nc, N))
+            kept = idx[:c - W]
+            assert len(set(kept.tolist())) == kept.shape[0] and (kept.size == 0 or (kept.min() >= 0 and kept.max() < Nc))
+            assert np.all(np.diff(idx) > 0)
+            # gathered rows are the source rows, bit for bit
+            np.testing.assert_array_equal(Ko[b, lo:lo + c], Kb[b, h][idx])
+            np.testing.assert_array_equal(Vo[b, lo:lo + c], Vb[b, h][idx])
+            if sc_g is not None:
+                assert np.all(np.isposinf(sc_g[b, h, Nc:]))
+            if (b, h) not in todo:
+                continue
+            u = O.score_unit(lay.K[b, h], lay.V[b, h], lay.Q[b, h * G:(h + 1) * G], op)
+            s_ora_heads[h] = u["s_comp"]
+            what = f"{wl.name} b{b} h{h}"
+            if sc_g is not None:
+                stats["max_err"] = max(stats["max_err"], check_scores(wl.dtype, sc_g[b, h, :Nc], u["s_comp"], what))
+            if red_g is not None:
+                assert abs(float(red_g[b, h]) - float(u["r"])) <= RTOL_R[wl.dtype], f"{what}: r {red_g[b, h]} vs {u['r']}"
+            band = check_topk_set(wl.dtype, kept, u["s_comp"], c - W, what)
+            stats["band"] += max(0, band - 1)
+            stats["checked"] += 1
+            if not adaptive:
+                ora_idx = O.select_unit(u["s_comp"], Bud - W, N, W)
+                stats["exact"] += int(np.array_equal(ora_idx, idx))
+        if adaptive and len(s_ora_heads) == Hkv:
+            # budgets may differ from the oracle's only through candidates inside the band of the pooled threshold
+            s_all = np.stack([s_ora_heads[h] for h in range(Hkv)])
+            bp_ora = O.adaptive_budgets(s_all, Bud, W, op.budget_floor)
+            rest = Hkv * (Bud - W - op.budget_floor)
+            if rest > 0:
+                taken = np.zeros_like(s_all, dtype=bool)
+                for h in range(Hkv):
+                    taken[h, O.top_indices(s_all[h], op.budget_floor)] = True
+                flat = np.where(taken, -np.inf, s_all)
+                tau = np.sort(flat.reshape(-1))[::-1][rest - 1]
+                band = TOL[wl.dtype] * max(abs(tau), np.abs(s_all).mean())
+                for h in range(Hkv):
+                    slack = int(((s_all[h] >= tau - band) & (s_all[h] <= tau + band)).sum()) + 1
+                    assert abs(int(cnt_g[b, h]) - W - int(bp_ora[h])) <= slack, \
+                        f"{wl.name} b{b} h{h}: budget {cnt_g[b, h] - W} vs oracle {bp_ora[h]} (slack {slack})"
+    return stats

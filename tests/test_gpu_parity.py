@@ -1,0 +1,181 @@
+"""GPU parity: the HIP path through the C ABI against the float64 oracle on identical seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mixkv_oracle as O
+from paper_2510_20707_amd import binding as B
+from paper_2510_20707_amd import synth
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+WL = synth.WORKLOADS
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def _run_and_check(wl, n_layers=None, units=None, layer_ids=None, **over):
+    layer_ids = list(range(n_layers or wl.n_layers)) if layer_ids is None else layer_ids
+    layers = [synth.make_layer(wl, l) for l in layer_ids]
+    _say(f"[case] {wl.name} dtype={wl.dtype} L={len(layers)} Bt={wl.batch} Hq={wl.n_q_heads} Hkv={wl.n_kv_heads} "
+         f"D={wl.head_dim} N={wl.seq_len} W={wl.window} B={over.get('budget', wl.budget)} over={over}")
+    p, outs = H.run_compress(wl, layers, **over)
+    tot = dict(max_err=0.0, band=0, exact=0, checked=0)
+    for lay, out in zip(layers, outs):
+        st = H.check_layer(wl, lay, p, out, units=units, **over)
+        tot["max_err"] = max(tot["max_err"], st["max_err"])
+        for k in ("band", "exact", "checked"):
+            tot[k] += st[k]
+    _say(f"       checked {tot['checked']} units: max score err {tot['max_err']:.2e}, identical index sets "
+         f"{tot['exact']}, near-tie candidates {tot['band']}")
+    return tot
+
+
+def test_c1_tiny_fp32():
+    st = _run_and_check(WL["c1"])
+    assert st["exact"] == st["checked"] == 2
+
+
+def test_c2_single_layer_bf16():
+    _run_and_check(WL["c2"])
+
+
+@pytest.mark.parametrize("over", [
+    dict(pool="avg"), dict(pool="none"), dict(intrinsic="none"), dict(causal_window=False),
+    dict(pool="max", pool_kernel=3, softmax_scale=0.125), dict(budget=8), dict(budget=512),
+])
+def test_c1_variants(over):
+    _run_and_check(WL["c1"], **over)
+
+
+@pytest.mark.parametrize("over", [dict(pool="avg"), dict(intrinsic="none"), dict(causal_window=False, pool="none")])
+def test_c2_variants(over):
+    _run_and_check(WL["c2"], **over)
+
+
+@pytest.mark.parametrize("dtype,D,N,W,Hq,Hkv,B", [
+    ("bf16", 64, 1000, 5, 6, 2, 37),       # G*W = 15 rows (one padded tile), ragged key tail
+    ("f32", 128, 777, 9, 4, 4, 100),       # G = 1, fp32 with D = 128
+    ("bf16", 128, 333, 32, 16, 2, 40),     # G*W = 256 rows = 8 tiles, two chunks
+    ("bf16", 128, 2049, 17, 3, 1, 64),     # one key past a chunk boundary, odd window
+    ("f32", 64, 64, 31, 2, 1, 40),         # window half of the sequence
+])
+def test_ragged_shapes(dtype, D, N, W, Hq, Hkv, B):
+    wl = WL["c2"].with_(name="ragged", dtype=dtype, head_dim=D, seq_len=N, window=W, n_q_heads=Hq, n_kv_heads=Hkv,
+                        budget=B, batch=2, text_prefix=min(16, N // 4), text_suffix_start=N - max(W, N // 8))
+    _run_and_check(wl, n_layers=2)
+
+
+def test_budget_edges():
+    wl = WL["c1"]
+    _run_and_check(wl, budget=wl.window)          # B' = 0: window only
+    _run_and_check(wl, budget=wl.seq_len)         # keep everything
+
+
+def test_identical_keys_degenerate_head():
+    # r = 1, constant diversity: every mixed score is ~0 and any selection is a valid tie-break
+    wl = WL["c1"]
+    lay = synth.make_layer(wl, 0)
+    lay.K[:] = lay.K[0, 0, 0]
+    p, outs = H.run_compress(wl, [lay])
+    red = outs[0].redundancy.cpu().numpy()
+    assert np.all(np.abs(red - 1.0) < 1e-5)
+    sc = outs[0].scores.cpu().numpy()[:, :, :wl.seq_len - wl.window]
+    u = O.score_unit(lay.K[0, 0], lay.V[0, 0], lay.Q[0, :2], H.oracle_params(wl))
+    assert np.abs(sc[0, 0]).max() < 1e-4 * np.abs(u["s_imp"]).max()
+    idx = outs[0].indices.cpu().numpy()
+    for h in range(2):
+        assert len(set(idx[0, h].tolist())) == wl.budget
+
+
+def test_c3_two_layers_all_budgets():
+    wl = WL["c3"]
+    for budget in (64, 128, 256, 512):
+        _run_and_check(wl, layer_ids=[0, 17], units=[(0, 0), (0, 3)], budget=budget)
+
+
+def test_c3_full_cache_bench_configuration():
+    # the launch configuration bench.py times: all 28 layers in one call; oracle on sampled units,
+    # invariants (unique, ascending, window kept, rows bit-identical) on every unit
+    wl = WL["c3"]
+    layers = [synth.make_layer(wl, l) for l in range(wl.n_layers)]
+    _say(f"[case] c3 full cache, {wl.n_layers} layers in one call")
+    p, outs = H.run_compress(wl, layers)
+    sample = {0: [(0, 1)], 9: [(0, 2)], 27: [(0, 0), (0, 3)]}
+    for l, (lay, out) in enumerate(zip(layers, outs)):
+        st = H.check_layer(wl, lay, p, out, units=sample.get(l, []))
+        if l in sample:
+            _say(f"       layer {l}: {st}")
+
+
+def test_c4_llama_shaped_two_layers():
+    _run_and_check(WL["c4"], layer_ids=[0, 31], units=[(0, 0), (0, 7)])
+
+
+def test_c5_long_video_adaptive_one_layer():
+    wl = WL["c5"].with_(batch=2)
+    _run_and_check(wl, layer_ids=[3], units=[(0, h) for h in range(4)])
+
+
+def test_adaptive_small_all_units():
+    wl = WL["c2"].with_(name="adaptive-small", seq_len=1024, text_suffix_start=960, batch=3, budget=96,
+                        budget_mode="adaptive", budget_floor=16, sigma=(0.1, 0.8))
+    _run_and_check(wl, n_layers=2)
+    _run_and_check(wl, n_layers=1, budget_floor=0)
+    _run_and_check(wl, n_layers=1, budget_floor=64)     # floor == B': nothing left to pool
+
+
+def test_more_layers_than_one_launch_group():
+    wl = WL["c1"].with_(n_layers=35)
+    _run_and_check(wl, n_layers=35)
+
+
+def test_strided_cache_and_no_optional_outputs():
+    wl = WL["c2"].with_(seq_len=1024, text_suffix_start=960)
+    lay = synth.make_layer(wl, 0)
+    p = H.gpu_params(wl)
+    dev = "cuda:0"
+    # K and V live in one [Bt, Hkv, 2, N+8, D] buffer: head stride and batch stride differ from the dense ones
+    buf = torch.zeros((wl.batch, wl.n_kv_heads, 2, wl.seq_len + 8, wl.head_dim), dtype=torch.bfloat16, device=dev)
+    buf[:, :, 0, :wl.seq_len] = H.to_device(wl, lay.K)
+    buf[:, :, 1, :wl.seq_len] = H.to_device(wl, lay.V)
+    K, V = buf[:, :, 0, :wl.seq_len], buf[:, :, 1, :wl.seq_len]
+    out = B.alloc_layer_out(p, dev, scores=False, redundancy=False)
+    out.offsets = None
+    ws = B.alloc_workspace(p, 1, dev)
+    B.mixkv_compress(p, [K], [V], [H.to_device(wl, lay.Q)], [out], ws)
+    torch.cuda.synchronize()
+    ref_p, ref = H.run_compress(wl, [lay])
+    assert torch.equal(out.indices, ref[0].indices)
+    assert torch.equal(out.K_out.view(torch.int16), ref[0].K_out.view(torch.int16))
+    assert torch.equal(out.V_out.view(torch.int16), ref[0].V_out.view(torch.int16))
+
+
+def test_two_runs_are_bit_identical():
+    wl = WL["c2"]
+    lay = synth.make_layer(wl, 0)
+    _, a = H.run_compress(wl, [lay])
+    _, b = H.run_compress(wl, [lay])
+    assert torch.equal(a[0].scores.view(torch.int32), b[0].scores.view(torch.int32))
+    assert torch.equal(a[0].indices, b[0].indices)
+    assert torch.equal(a[0].redundancy.view(torch.int32), b[0].redundancy.view(torch.int32))
+
+
+def test_score_entry_point_matches_compress_scores():
+    wl = WL["c2"].with_(seq_len=2048, text_suffix_start=1984)
+    lay = synth.make_layer(wl, 0)
+    p, ref = H.run_compress(wl, [lay])
+    dev = "cuda:0"
+    out = B.alloc_layer_out(p, dev, select=False, gather=False)
+    ws = B.alloc_workspace(p, 1, dev)
+    B.mixkv_score(p, [H.to_device(wl, lay.K)], [H.to_device(wl, lay.V)], [H.to_device(wl, lay.Q)], [out], ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out.scores.view(torch.int32), ref[0].scores.view(torch.int32))
+    # ... and mixkv_select on those scores reproduces compress' indices
+    sel = B.alloc_layer_out(p, dev, scores=False, redundancy=False, gather=False)
+    sel.scores = out.scores
+    B.mixkv_select(p, [sel])
+    torch.cuda.synchronize()
+    assert torch.equal(sel.indices, ref[0].indices) and torch.equal(sel.counts, ref[0].counts)
