@@ -1,0 +1,198 @@
+#!/usr/bin/env python3
+"""Benchmark of the MixKV compression step on one MI355X.
+
+One step = one mixkv_compress call over a whole synthetic cache (all layers, all KV heads):
+score -> mix -> top-B -> gather.  Default workload: the Qwen2-VL-7B-shaped 28-layer, 8K-token
+cache (workload "c3"), budget 64.  Prints ONE JSON line.
+
+  value        cached tokens compressed per second (batch * N / step time); inputs resident in HBM
+  roofline     the dominant kernel's algorithmic bytes per launch / its average duration, measured
+               with HIP events on the launch stream (mixkv_compress_profiled), against 8 TB/s
+  cpu_baseline the float64 oracle on the same inputs on the host cores (process pool), before the
+               GPU is touched
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+os.environ.setdefault("OMP_NUM_THREADS", "1")      # one BLAS thread per oracle worker
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2510_20707_amd import synth  # noqa: E402
+
+HBM_PEAK = 8.0e12
+MFMA_BF16_PEAK = 2.5e15
+
+_LAYERS = None
+_WL = None
+_BUDGET = None
+
+
+def _oracle_layer(l):
+    from oracle import mixkv_oracle as O
+    wl = _WL
+    p = O.Params(wl.n_q_heads, wl.n_kv_heads, wl.window, _BUDGET, pool=wl.pool, pool_kernel=wl.pool_kernel,
+                 softmax_scale=wl.softmax_scale, eps=wl.eps, budget_mode=wl.budget_mode, budget_floor=wl.budget_floor)
+    out = O.compress_layer(_LAYERS[l].K, _LAYERS[l].V, _LAYERS[l].Q, p)
+    return l, [[i.astype(np.int32) for i in row] for row in out["indices"]], out["scores"].astype(np.float32)
+
+
+def cpu_baseline(wl, layers, budget, max_layers):
+    """Time the oracle as it stands on a bounded sample (the first `max_layers` layers)."""
+    import multiprocessing as mp
+    global _LAYERS, _WL, _BUDGET
+    _LAYERS, _WL, _BUDGET = layers, wl, budget
+    n = min(max_layers, len(layers))
+    workers = max(1, min(n, len(os.sched_getaffinity(0)), int(os.environ.get("MIXKV_BENCH_WORKERS", "16"))))
+    ctx = mp.get_context("fork")                   # children inherit the generated layers; no GPU state exists yet
+    with ctx.Pool(workers) as pool:
+        pool.map(abs, range(workers))              # spin the workers up outside the timed region
+        t0 = time.perf_counter()
+        res = pool.map(_oracle_layer, range(n), chunksize=1)
+        dt = time.perf_counter() - t0
+    # scaled to the metric: tokens of the whole cache per second if every layer cost what the sample did
+    tokens_per_s = wl.batch * wl.seq_len / (dt * len(layers) / n)
+    return dict(value=tokens_per_s, unit="tokens/s", cores=workers, kind="oracle",
+                sample=f"{n} of {len(layers)} layers ({n * wl.batch * wl.n_kv_heads} units) in {dt:.2f} s, "
+                       f"process pool of {workers}, 1 BLAS thread each; scaled by {len(layers)}/{n}"), {r[0]: r for r in res}
+
+
+def algorithmic_bytes(wl, budget, scores_out):
+    """Bytes the method itself must move per unit: K once, V once, the window queries, the kept rows
+    read and written, the indices; optionally the N-long score vector."""
+    e = 2 if wl.dtype == "bf16" else 4
+    n, d = wl.seq_len, wl.head_dim
+    per_unit = n * d * e * 2 + wl.group * wl.window * d * e + 4 * budget * d * e + 4 * budget
+    if scores_out:
+        per_unit += 4 * n
+    return per_unit
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c3", choices=sorted(synth.WORKLOADS))
+    ap.add_argument("--budget", type=int, default=None)
+    ap.add_argument("--layers", type=int, default=None, help="use only the first L layers (not the headline)")
+    ap.add_argument("--copies", type=int, default=3, help="distinct device copies of the cache, used round-robin")
+    ap.add_argument("--cpu-layers", type=int, default=28, help="layers the oracle baseline runs (0 = skip)")
+    ap.add_argument("--no-parity", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path has no cross-GPU step); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    wl = synth.WORKLOADS[args.workload]
+    if args.layers:
+        wl = wl.with_(n_layers=args.layers)
+    budget = args.budget or wl.budget
+    t0 = time.perf_counter()
+    layers = [synth.make_layer(wl, l) for l in range(wl.n_layers)]
+    t_gen = time.perf_counter() - t0
+
+    cpu, oracle_res = (None, {})
+    if args.cpu_layers > 0:
+        cpu, oracle_res = cpu_baseline(wl, layers, budget, args.cpu_layers)
+
+    import torch
+    from paper_2510_20707_amd import binding as B
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    p = B.make_params(wl.dtype, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.seq_len, wl.window, budget,
+                      pool=wl.pool, pool_kernel=wl.pool_kernel, softmax_scale=wl.softmax_scale, eps=wl.eps,
+                      budget_mode=wl.budget_mode, budget_floor=wl.budget_floor)
+
+    def up(a):
+        if wl.dtype == "bf16":
+            return torch.from_numpy(synth.round_to_bf16_bits(a).view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(a).to(dev)
+
+    base = [(up(l.K), up(l.V), up(l.Q)) for l in layers]
+    copies = [base] + [[(k.clone(), v.clone(), q.clone()) for k, v, q in base] for _ in range(max(0, args.copies - 1))]
+    outs = [B.alloc_layer_out(p, dev, scores=False, redundancy=True) for _ in layers]
+    ws = B.alloc_workspace(p, len(layers), dev)
+    calls = [B.PreparedCall(p, [x[0] for x in c], [x[1] for x in c], [x[2] for x in c], outs, ws) for c in copies]
+    stream = torch.cuda.current_stream()
+
+    for i in range(args.warmup):
+        calls[i % len(calls)].compress(stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        calls[i % len(calls)].compress(stream)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    # per-kernel durations with HIP events on the launch stream, same inputs, same round-robin
+    stage_ms = {}
+    nprof = max(3, min(args.steps, 20))
+    for i in range(nprof):
+        for k, v in calls[i % len(calls)].compress_profiled(stream).items():
+            stage_ms[k] = stage_ms.get(k, 0.0) + v / nprof
+
+    parity = None
+    if oracle_res and not args.no_parity:
+        # the last profiled call ran on copy (nprof-1) % copies; all copies hold the same values
+        torch.cuda.synchronize()
+        same, total = 0, 0
+        for l, (_, idx_o, _) in oracle_res.items():
+            idx_g = outs[l].indices.cpu().numpy()
+            for b in range(wl.batch):
+                off = 0
+                for h in range(wl.n_kv_heads):
+                    n = idx_o[b][h].shape[0]
+                    g = idx_g[b, h] if wl.budget_mode == "fixed" else idx_g.reshape(wl.batch, -1)[b, off:off + n]
+                    same += int(np.array_equal(g, idx_o[b][h]))
+                    total += 1
+                    off += n
+        parity = dict(units=total, identical_index_sets=same,
+                      note="sets may differ only by near-ties inside the 2e-3 band; tests/ apply the band rule")
+
+    units = wl.n_units
+    e = 2 if wl.dtype == "bf16" else 4
+    bytes_step = algorithmic_bytes(wl, budget, scores_out=False) * units
+    dom = max(("stats", "attn"), key=lambda k: stage_ms.get(k, 0.0))
+    kv_bytes = wl.seq_len * wl.head_dim * e
+    q_bytes = wl.group * wl.window * wl.head_dim * e
+    dom_bytes = ((2 * kv_bytes if dom == "stats" else kv_bytes) + q_bytes) * units      # per launch
+    dom_s = stage_ms[dom] * 1e-3
+    gemm_flops = 2.0 * wl.group * wl.window * wl.seq_len * wl.head_dim * units             # one pass
+    out = {
+        "metric": "cached tokens compressed/sec (all layers·heads) at 8K ctx; % of HBM peak",
+        "value": wl.batch * wl.seq_len / (dt / args.steps),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {wl.n_layers} layers x {wl.n_q_heads}Q/{wl.n_kv_heads}KV heads, D={wl.head_dim}, "
+                               f"N={wl.seq_len}, W={wl.window}, B={budget}, batch={wl.batch}, {wl.budget_mode} budgets, "
+                               f"pool=max{wl.pool_kernel}, VNorm on",
+                   "units": units, "input_copies_round_robin": len(copies)},
+        "hbm_frac_end_to_end": bytes_step / (dt / args.steps) / HBM_PEAK,
+        "algorithmic_bytes_per_step": bytes_step,
+        "head_tokens_per_s": units * wl.seq_len / (dt / args.steps),
+        "stage_ms": {k: round(v, 5) for k, v in stage_ms.items()},
+        "mfma_tflops": {k: gemm_flops / (stage_ms[k] * 1e-3) / 1e12 for k in ("stats", "attn") if stage_ms.get(k)},
+        "roofline": {"bound": "hbm", "kernel": dom + "_kernel", "achieved": dom_bytes / dom_s / 1e9,
+                     "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": dom_bytes / dom_s / HBM_PEAK, "traffic": None},
+        "cpu_baseline": cpu,
+        "parity_vs_oracle": parity,
+        "host_gen_s": round(t_gen, 2),
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -143,6 +143,19 @@ mixkv_status mixkv_select(const mixkv_params *params, mixkv_layer_out *out, int3
 mixkv_status mixkv_compress(const mixkv_params *params, const mixkv_layer_in *in, mixkv_layer_out *out,
                             int32_t n_layers, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Profiling aid: mixkv_compress with every kernel launch bracketed by a pair of HIP events on
+ * `hip_stream`.  Synchronises the stream before returning and writes the milliseconds each
+ * pipeline stage took to the HOST array stage_ms[MIXKV_N_STAGES] (summed over launch groups when
+ * n_layers exceeds one group).  Stage names come from mixkv_stage_name.  Outputs are those of
+ * mixkv_compress (Algorithm 1).
+ */
+#define MIXKV_N_STAGES 6
+mixkv_status mixkv_compress_profiled(const mixkv_params *params, const mixkv_layer_in *in, mixkv_layer_out *out,
+                                     int32_t n_layers, void *workspace, size_t workspace_bytes, void *hip_stream,
+                                     float *stage_ms);
+const char *mixkv_stage_name(int32_t stage);
+
 const char *mixkv_status_string(mixkv_status status);
 int32_t mixkv_version(void);
 

@@ -23,6 +23,7 @@ POOL = {"none": 0, "avg": 1, "max": 2}
 BUDGET_MODE = {"fixed": 0, "adaptive": 1}
 INTRINSIC = {"none": 0, "vnorm": 1}
 TORCH_DTYPE = {0: torch.float32, 1: torch.bfloat16}
+N_STAGES = 6
 
 
 class MixkvParams(C.Structure):
@@ -70,6 +71,11 @@ def lib() -> C.CDLL:
         L.mixkv_select.restype = C.c_int
         L.mixkv_compress.argtypes = [pp, pin, pout, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
         L.mixkv_compress.restype = C.c_int
+        L.mixkv_compress_profiled.argtypes = [pp, pin, pout, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p,
+                                              C.POINTER(C.c_float)]
+        L.mixkv_compress_profiled.restype = C.c_int
+        L.mixkv_stage_name.argtypes = [C.c_int32]
+        L.mixkv_stage_name.restype = C.c_char_p
         L.mixkv_status_string.argtypes = [C.c_int]
         L.mixkv_status_string.restype = C.c_char_p
         L.mixkv_version.argtypes = []
@@ -201,6 +207,12 @@ class PreparedCall:
     def compress(self, stream=None):
         _check(self._L.mixkv_compress(C.byref(self.p), self.ins, self.outs, self.n, self.wp, self.wb, _stream(stream)),
                "mixkv_compress")
+
+    def compress_profiled(self, stream=None) -> dict:
+        ms = (C.c_float * N_STAGES)()
+        _check(self._L.mixkv_compress_profiled(C.byref(self.p), self.ins, self.outs, self.n, self.wp, self.wb,
+                                               _stream(stream), ms), "mixkv_compress_profiled")
+        return {self._L.mixkv_stage_name(i).decode(): float(ms[i]) for i in range(N_STAGES)}
 
     def score(self, stream=None):
         _check(self._L.mixkv_score(C.byref(self.p), self.ins, self.outs, self.n, self.wp, self.wb, _stream(stream)),

@@ -6,7 +6,7 @@
 
 namespace mixkv {
 
-int stream_chunk_keys();
+int stream_chunk_keys(int dtype, int D);
 int max_adaptive_heads();
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -44,7 +44,7 @@ mixkv_status make_shape(const mixkv_params *p, Shape *s) {
   s->N = p->seq_len; s->W = p->window; s->Nc = s->N - s->W; s->B = p->budget; s->Bp = s->B - s->W;
   s->GW = G * s->W;
   s->QT = (s->GW + 31) / 32;
-  s->chunk = stream_chunk_keys();
+  s->chunk = stream_chunk_keys(p->dtype, p->head_dim);
   s->nchunks = (s->N + s->chunk - 1) / s->chunk;
   s->Npad = s->nchunks * s->chunk;
   s->units_per_layer = s->batch * s->hkv;
@@ -60,7 +60,6 @@ void carve_workspace(const Shape &s, int64_t units, Workspace *w) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   const size_t QTR = (size_t)s.QT * 32;
-  w->counters = take((size_t)units * 4);
   w->part_ml = take((size_t)units * s.nchunks * QTR * 8);
   w->part_ksum = take((size_t)units * s.nchunks * s.D * 4);
   w->brow = take((size_t)units * QTR * 4);
@@ -78,8 +77,41 @@ static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 enum Stage { kScore = 1, kSelect = 2, kGather = 4 };
 
+// Optional per-kernel timing: each launch is bracketed by a pair of events on the call's stream.
+struct StageTimer {
+  hipStream_t stream;
+  float *ms;                                   // host [MIXKV_N_STAGES], may be null (no timing)
+  hipEvent_t ev[2 * MIXKV_N_STAGES * (MIXKV_MAX_LAYERS / kLayersPerLaunch + 1)];
+  int stage_of[MIXKV_N_STAGES * (MIXKV_MAX_LAYERS / kLayersPerLaunch + 1)];
+  int n = 0;
+  bool failed = false;
+  template <class F> hipError_t operator()(int stage, F launch) {
+    if (!ms) return launch();
+    hipEvent_t a, b;
+    if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { failed = true; return launch(); }
+    (void)hipEventRecord(a, stream);
+    hipError_t e = launch();
+    (void)hipEventRecord(b, stream);
+    ev[2 * n] = a; ev[2 * n + 1] = b; stage_of[n] = stage; ++n;
+    return e;
+  }
+  mixkv_status finish() {
+    if (!ms) return MIXKV_OK;
+    for (int i = 0; i < MIXKV_N_STAGES; ++i) ms[i] = 0.f;
+    hipError_t e = hipStreamSynchronize(stream);
+    for (int i = 0; i < n; ++i) {
+      float t = 0.f;
+      if (e == hipSuccess && hipEventElapsedTime(&t, ev[2 * i], ev[2 * i + 1]) == hipSuccess) ms[stage_of[i]] += t;
+      (void)hipEventDestroy(ev[2 * i]);
+      (void)hipEventDestroy(ev[2 * i + 1]);
+    }
+    return (e == hipSuccess && !failed) ? MIXKV_OK : MIXKV_ERR_HIP;
+  }
+};
+
 static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mixkv_layer_out *out, int32_t n_layers,
-                        void *workspace, size_t workspace_bytes, void *hip_stream, int stages) {
+                        void *workspace, size_t workspace_bytes, void *hip_stream, int stages,
+                        float *stage_ms = nullptr) {
   Shape s;
   mixkv_status st = make_shape(params, &s);
   if (st != MIXKV_OK) return st;
@@ -116,9 +148,18 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
 
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
   char *ws = reinterpret_cast<char *>(workspace);
+  int num_cus = 0;
   if (stages & kScore) {
-    if (launch_zero_counters(reinterpret_cast<int32_t *>(ws + w.counters), units, stream) != hipSuccess) return MIXKV_ERR_HIP;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&num_cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || num_cus < 1)
+      return MIXKV_ERR_HIP;
   }
+  StageTimer timed;
+  timed.stream = stream;
+  timed.ms = stage_ms;
+  mixkv_status result = MIXKV_OK;
+  auto ok = [&](hipError_t e) { if (e != hipSuccess) result = MIXKV_ERR_HIP; return e == hipSuccess; };
   for (int l0 = 0; l0 < n_layers; l0 += kLayersPerLaunch) {
     const int nl = (n_layers - l0 < kLayersPerLaunch) ? n_layers - l0 : kLayersPerLaunch;
     LayerInTable ti;
@@ -137,19 +178,20 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
       to.l[l] = LayerOut{scores, lo.redundancy, lo.indices, lo.counts, lo.offsets, lo.K_out, lo.V_out};
     }
     const int nunits = nl * s.units_per_layer;
-    if (stages & kScore) {
-      if (launch_stats(s, params->dtype, ti, to, ws, w, unit0, nunits, stream) != hipSuccess) return MIXKV_ERR_HIP;
-      if (launch_attn(s, params->dtype, ti, ws, w, unit0, nunits, stream) != hipSuccess) return MIXKV_ERR_HIP;
-      if (launch_mix(s, to, ws, w, unit0, nunits, stream) != hipSuccess) return MIXKV_ERR_HIP;
+    if (result == MIXKV_OK && (stages & kScore)) {
+      const int grid = stream_grid(s, nunits, num_cus);
+      ok(timed(0, [&] { return launch_stats(s, params->dtype, ti, ws, w, unit0, nunits, grid, stream); })) &&
+          ok(timed(1, [&] { return launch_finalize(s, to, ws, w, unit0, nunits, grid, stream); })) &&
+          ok(timed(2, [&] { return launch_attn(s, params->dtype, ti, ws, w, unit0, nunits, grid, stream); })) &&
+          ok(timed(3, [&] { return launch_mix(s, to, ws, w, unit0, nunits, stream); }));
     }
-    if (stages & kSelect) {
-      if (launch_select(s, to, nl, stream) != hipSuccess) return MIXKV_ERR_HIP;
-    }
-    if (stages & kGather) {
-      if (launch_gather(s, params->dtype, ti, to, nl, stream) != hipSuccess) return MIXKV_ERR_HIP;
-    }
+    if (result == MIXKV_OK && (stages & kSelect)) ok(timed(4, [&] { return launch_select(s, to, nl, stream); }));
+    if (result == MIXKV_OK && (stages & kGather))
+      ok(timed(5, [&] { return launch_gather(s, params->dtype, ti, to, nl, stream); }));
+    if (result != MIXKV_OK) break;
   }
-  return MIXKV_OK;
+  mixkv_status fin = timed.finish();
+  return result != MIXKV_OK ? result : fin;
 }
 
 }  // namespace mixkv
@@ -181,6 +223,19 @@ mixkv_status mixkv_compress(const mixkv_params *params, const mixkv_layer_in *in
                             int32_t n_layers, void *workspace, size_t workspace_bytes, void *hip_stream) {
   return mixkv::run(params, in, out, n_layers, workspace, workspace_bytes, hip_stream,
                     mixkv::kScore | mixkv::kSelect | mixkv::kGather);
+}
+
+mixkv_status mixkv_compress_profiled(const mixkv_params *params, const mixkv_layer_in *in, mixkv_layer_out *out,
+                                     int32_t n_layers, void *workspace, size_t workspace_bytes, void *hip_stream,
+                                     float *stage_ms) {
+  if (!stage_ms) return MIXKV_ERR_INVALID_ARG;
+  return mixkv::run(params, in, out, n_layers, workspace, workspace_bytes, hip_stream,
+                    mixkv::kScore | mixkv::kSelect | mixkv::kGather, stage_ms);
+}
+
+const char *mixkv_stage_name(int32_t stage) {
+  static const char *names[MIXKV_N_STAGES] = {"stats", "finalize", "attn", "mix", "select", "gather"};
+  return (stage >= 0 && stage < MIXKV_N_STAGES) ? names[stage] : "";
 }
 
 const char *mixkv_status_string(mixkv_status status) {

@@ -42,9 +42,9 @@ struct Shape {
 
 // Workspace carve-up (byte offsets from a 256-byte aligned base).  Sizes are per call (all units).
 struct Workspace {
-  size_t counters;       // int32 [units]
-  size_t part_ml;        // float2 [units][nchunks][QT*32]   running (max, sum) of each softmax row, log2 domain
-  size_t part_ksum;      // float  [units][nchunks][D]       partial sums of normalised keys
+  size_t part_ml;        // float2 [units*nchunks][QT*32]    per-run (max, sum) of each softmax row, log2 domain,
+                         //                                  at the slot of the run's first item
+  size_t part_ksum;      // float  [units*nchunks][D]        per-run partial sums of normalised keys
   size_t brow;           // float  [units][QT*32]            per-row exponent offset: max + log2(sum * G*W)
   size_t kbar;           // float  [units][2][D]             mean normalised key, split hi / lo for bf16
   size_t rbar;           // float  [units]
@@ -61,11 +61,15 @@ void carve_workspace(const Shape &s, int64_t units, Workspace *w);
 
 // Kernel launchers (one per pipeline stage).  `unit0` is the first unit of this launch group,
 // `nunits` the number of units it covers (whole layers).
-hipError_t launch_zero_counters(int32_t *counters, int64_t n, hipStream_t st);
-hipError_t launch_stats(const Shape &s, int dtype, const LayerInTable &in, const LayerOutTable &out, char *ws,
-                        const Workspace &w, int64_t unit0, int nunits, hipStream_t st);
+// `grid` (from stream_grid) is the number of workgroups of the two streaming kernels; finalize
+// needs it to find the runs stats_kernel wrote.
+int stream_grid(const Shape &s, int nunits, int num_cus);
+hipError_t launch_stats(const Shape &s, int dtype, const LayerInTable &in, char *ws, const Workspace &w, int64_t unit0,
+                        int nunits, int grid, hipStream_t st);
+hipError_t launch_finalize(const Shape &s, const LayerOutTable &out, char *ws, const Workspace &w, int64_t unit0,
+                           int nunits, int grid, hipStream_t st);
 hipError_t launch_attn(const Shape &s, int dtype, const LayerInTable &in, char *ws, const Workspace &w,
-                       int64_t unit0, int nunits, hipStream_t st);
+                       int64_t unit0, int nunits, int grid, hipStream_t st);
 hipError_t launch_mix(const Shape &s, const LayerOutTable &out, char *ws, const Workspace &w, int64_t unit0,
                       int nunits, hipStream_t st);
 hipError_t launch_select(const Shape &s, const LayerOutTable &out, int nlayers, hipStream_t st);

@@ -348,19 +348,9 @@ __global__ __launch_bounds__(256) void gather_kernel(Shape s, int eb, LayerInTab
   *reinterpret_cast<uint4 *>(reinterpret_cast<char *>(O.V_out) + dst_off) = vv;
 }
 
-__global__ void zero_kernel(int32_t *p, int64_t n) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = 0;
-}
-
 // ------------------------------------------------------------------------------------------------
 // launchers
 // ------------------------------------------------------------------------------------------------
-hipError_t launch_zero_counters(int32_t *counters, int64_t n, hipStream_t st) {
-  hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, counters, n);
-  return hipGetLastError();
-}
-
 hipError_t launch_mix(const Shape &s, const LayerOutTable &out, char *ws, const Workspace &w, int64_t unit0, int nunits,
                       hipStream_t st) {
   hipLaunchKernelGGL(mix_kernel, dim3(nunits), dim3(kSelectThreads), 0, st, s, out, ws, w, unit0);
