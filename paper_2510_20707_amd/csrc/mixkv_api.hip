@@ -60,8 +60,11 @@ void carve_workspace(const Shape &s, int64_t units, Workspace *w) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   const size_t QTR = (size_t)s.QT * 32;
-  w->part_ml = take((size_t)units * s.nchunks * QTR * 8);
-  w->part_ksum = take((size_t)units * s.nchunks * s.D * 4);
+  // one slot per run of the streaming kernels: each launch group owns kMaxStreamGrid + its units
+  const size_t per_group = (size_t)kMaxStreamGrid + (size_t)kLayersPerLaunch * s.units_per_layer;
+  const size_t groups = ((size_t)(units / s.units_per_layer) + kLayersPerLaunch - 1) / kLayersPerLaunch;
+  w->part_ml = take(groups * per_group * QTR * 8);
+  w->part_ksum = take(groups * per_group * s.D * 4);
   w->brow = take((size_t)units * QTR * 4);
   w->kbar = take((size_t)units * 2 * s.D * 4);
   w->rbar = take((size_t)units * 4);
@@ -180,8 +183,9 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
     const int nunits = nl * s.units_per_layer;
     if (result == MIXKV_OK && (stages & kScore)) {
       const int grid = stream_grid(s, nunits, num_cus);
-      ok(timed(0, [&] { return launch_stats(s, params->dtype, ti, ws, w, unit0, nunits, grid, stream); })) &&
-          ok(timed(1, [&] { return launch_finalize(s, to, ws, w, unit0, nunits, grid, stream); })) &&
+      const int64_t slot0 = (int64_t)(l0 / kLayersPerLaunch) * (kMaxStreamGrid + kLayersPerLaunch * s.units_per_layer);
+      ok(timed(0, [&] { return launch_stats(s, params->dtype, ti, ws, w, unit0, nunits, grid, slot0, stream); })) &&
+          ok(timed(1, [&] { return launch_finalize(s, to, ws, w, unit0, nunits, grid, slot0, stream); })) &&
           ok(timed(2, [&] { return launch_attn(s, params->dtype, ti, ws, w, unit0, nunits, grid, stream); })) &&
           ok(timed(3, [&] { return launch_mix(s, to, ws, w, unit0, nunits, stream); }));
     }

@@ -10,6 +10,7 @@ constexpr int kWave = 64;
 constexpr int kTileKeys = 32;          // keys per MFMA tile
 constexpr int kLayersPerLaunch = 32;   // pointer-table entries that fit in one kernel-argument block
 constexpr int kSelectThreads = 1024;
+constexpr int kMaxStreamGrid = 1024;    // upper bound on the workgroups of a streaming kernel launch
 
 // Per-layer device pointers handed to the kernels by value.
 struct LayerIn {
@@ -42,16 +43,15 @@ struct Shape {
 
 // Workspace carve-up (byte offsets from a 256-byte aligned base).  Sizes are per call (all units).
 struct Workspace {
-  size_t part_ml;        // float2 [units*nchunks][QT*32]    per-run (max, sum) of each softmax row, log2 domain,
-                         //                                  at the slot of the run's first item
-  size_t part_ksum;      // float  [units*nchunks][D]        per-run partial sums of normalised keys
+  size_t part_ml;        // float2 [slots][QT*32]            per-run (max, sum) of each softmax row, log2 domain
+  size_t part_ksum;      // float  [slots][D]                per-run partial sums of normalised keys
   size_t brow;           // float  [units][QT*32]            per-row exponent offset: max + log2(sum * G*W)
   size_t kbar;           // float  [units][2][D]             mean normalised key, split hi / lo for bf16
   size_t rbar;           // float  [units]
   size_t invnorm;        // float  [units][Npad]             1 / |K_i|
   size_t vnorm;          // float  [units][Npad]             |V_i|
   size_t araw;           // float  [units][Npad]             window/group mean attention before pooling
-  size_t sdiv;           // float  [units][Npad]             -Khat_i . Kbar
+  size_t sdiv;           // float  [units][Npad]             K_i . Kbar (the mix kernel applies -1/|K_i|)
   size_t scores;         // float  [units][N]                used when the caller passes no scores buffer
   size_t total;
 };
@@ -64,10 +64,11 @@ void carve_workspace(const Shape &s, int64_t units, Workspace *w);
 // `grid` (from stream_grid) is the number of workgroups of the two streaming kernels; finalize
 // needs it to find the runs stats_kernel wrote.
 int stream_grid(const Shape &s, int nunits, int num_cus);
+// `slot0` is the first partial slot of this launch group (each group owns kMaxStreamGrid + its units).
 hipError_t launch_stats(const Shape &s, int dtype, const LayerInTable &in, char *ws, const Workspace &w, int64_t unit0,
-                        int nunits, int grid, hipStream_t st);
+                        int nunits, int grid, int64_t slot0, hipStream_t st);
 hipError_t launch_finalize(const Shape &s, const LayerOutTable &out, char *ws, const Workspace &w, int64_t unit0,
-                           int nunits, int grid, hipStream_t st);
+                           int nunits, int grid, int64_t slot0, hipStream_t st);
 hipError_t launch_attn(const Shape &s, int dtype, const LayerInTable &in, char *ws, const Workspace &w,
                        int64_t unit0, int nunits, int grid, hipStream_t st);
 hipError_t launch_mix(const Shape &s, const LayerOutTable &out, char *ws, const Workspace &w, int64_t unit0,

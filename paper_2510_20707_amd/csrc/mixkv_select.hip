@@ -169,7 +169,9 @@ __global__ __launch_bounds__(kSelectThreads) void mix_kernel(Shape s, LayerOutTa
   float *scores = out.l[layer].scores + (int64_t)bh * s.N;
   const float *araw = reinterpret_cast<const float *>(ws + w.araw) + unit * s.Npad;
   const float *vnorm = reinterpret_cast<const float *>(ws + w.vnorm) + unit * s.Npad;
-  const float *sdiv = reinterpret_cast<const float *>(ws + w.sdiv) + unit * s.Npad;
+  const float *kdot = reinterpret_cast<const float *>(ws + w.sdiv) + unit * s.Npad;
+  const float *invn = reinterpret_cast<const float *>(ws + w.invnorm) + unit * s.Npad;
+  auto sdiv_at = [&](int i) { return -kdot[i] * invn[i]; };   // s_div_i = -Khat_i . Kbar
   const float r = reinterpret_cast<const float *>(ws + w.rbar)[unit];
   const int Nc = s.Nc;
   const bool use_v = s.intrinsic == MIXKV_INTRINSIC_VNORM;
@@ -181,7 +183,7 @@ __global__ __launch_bounds__(kSelectThreads) void mix_kernel(Shape s, LayerOutTa
     scores[i] = a;                          // parked here; re-read by the same thread below
     sum_ex += a;
     if (use_v) { float v = vnorm[i]; vmin = fminf(vmin, v); vmax = fmaxf(vmax, v); }
-    float d = sdiv[i];
+    float d = sdiv_at(i);
     dmin = fminf(dmin, d);
     dmax = fmaxf(dmax, d);
   }
@@ -198,7 +200,7 @@ __global__ __launch_bounds__(kSelectThreads) void mix_kernel(Shape s, LayerOutTa
   float sum_in = 0.f, sum_dn = 0.f;
   for (int i = tid; i < Nc; i += NT) {
     if (use_v) sum_in += (vnorm[i] - vmin) / vden;
-    sum_dn += (sdiv[i] - dmin) / dden;
+    sum_dn += (sdiv_at(i) - dmin) / dden;
   }
   const float mean_dn = block_reduce<OpSum>(sum_dn, fscr) * inv_n;
   if (use_v) {
@@ -215,7 +217,7 @@ __global__ __launch_bounds__(kSelectThreads) void mix_kernel(Shape s, LayerOutTa
   const float mean_imp = block_reduce<OpSum>(sum_imp, fscr) * inv_n;
   const float f_div = mean_imp / (mean_dn + s.eps);
   for (int i = tid; i < Nc; i += NT) {
-    float dn = (sdiv[i] - dmin) / dden;
+    float dn = (sdiv_at(i) - dmin) / dden;
     scores[i] = (1.f - r) * scores[i] + r * (dn * f_div);
   }
   for (int i = Nc + tid; i < s.N; i += NT) scores[i] = INFINITY;

@@ -1,9 +1,11 @@
 // The two kernels that stream the cache: window-attention statistics + key/value statistics
 // (stats_kernel) and the normalised attention column sums + diversity dot products (attn_kernel).
 //
-// Both are MFMA kernels.  A workgroup owns `chunk` consecutive keys of one unit (one layer,
-// batch item and KV head); each wave owns TPW tiles of 32 keys, held in registers in MFMA
-// fragment form, and sweeps the G*W window-query rows in tiles of 32 that live in LDS.
+// Both are MFMA kernels built the same way.  A workgroup walks runs of consecutive key chunks of
+// one unit (one layer, batch item and KV head).  The G*W window-query rows are split into tiles of
+// 32 and every wave keeps its TQ tiles in registers for the whole run ("query-stationary"); the
+// keys stream through LDS: each chunk is fetched with direct global->LDS loads (whole rows,
+// bank-rotated) into one of two buffers while the other is being consumed by all waves.
 //
 // Fragment form.  The contraction index d of Q.K^T may be visited in any order as long as both
 // operands agree, so a lane (key or row = lane % 32, half = lane / 32) simply owns every other
@@ -19,8 +21,23 @@
 // (paper Sec. 3.2, extrinsic importance: mean over the window queries of the attention weights).
 #include "mixkv_internal.h"
 
-#ifndef MIXKV_PREFETCH
-#define MIXKV_PREFETCH 0   // register double-buffering of the next chunk spills at 2 waves per SIMD
+#ifdef MIXKV_TIMING
+// Developer aid, compiled out by default: cycle totals of wave 0 of every workgroup of attn_kernel.
+__device__ unsigned long long mixkv_dbg[1024 * 16];
+#define TSTAMP(v) unsigned long long v = __builtin_readcyclecounter()
+#define TACC(slot, a, b) tacc[slot] += (b) - (a)
+#define TDECL unsigned long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0}
+#define TFLUSH do { if (threadIdx.x == 0) for (int i_ = 0; i_ < 8; ++i_) mixkv_dbg[blockIdx.x * 16 + 8 + i_] = tacc[i_]; } while (0)
+extern "C" int mixkv_debug_read(unsigned long long *host, int clear) {
+  if (hipMemcpyFromSymbol(host, HIP_SYMBOL(mixkv_dbg), sizeof(mixkv_dbg)) != hipSuccess) return 1;
+  if (clear) { static unsigned long long z[1024 * 16]; return hipMemcpyToSymbol(HIP_SYMBOL(mixkv_dbg), z, sizeof(z)) != hipSuccess; }
+  return 0;
+}
+#else
+#define TSTAMP(v)
+#define TACC(slot, a, b)
+#define TDECL
+#define TFLUSH
 #endif
 
 namespace mixkv {
@@ -88,64 +105,100 @@ __device__ __forceinline__ UnitCoord unit_coord(const Shape &s, int ul) {
   return c;
 }
 
-// LDS slot of lane (half, r) inside fragment c: rotating the row by 2c + half keeps both the
-// fragment reads (consecutive lanes of one half) and the staging writes (the 16 pieces of one row)
-// free of bank conflicts.
-__device__ __forceinline__ int frag_slot(int c, int half, int r) { return half * 32 + ((r + 2 * c + half) & 31); }
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void glb_void_t;
 
-// Stage the [QT*32, D] query block of one KV head into LDS in fragment order:
-// fragment (t, c) is 64 slots x 16 bytes.  Rows >= GW are zero.
-template <int DT, int D>
-__device__ __forceinline__ void stage_queries(const Shape &s, const char *Qb, uint4 *qs, int tid, int nthreads) {
-  constexpr int EB = Tr<DT>::EB, EPC = Tr<DT>::EPC, NCHK = D / (2 * EPC), PPR = D * EB / 16;
-  const int pieces = s.QT * 32 * PPR;
-  for (int p = tid; p < pieces; p += nthreads) {
-    int row = p / PPR, piece = p - row * PPR;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (row < s.GW) v = *reinterpret_cast<const uint4 *>(Qb + ((int64_t)row * D) * EB + piece * 16);
-    int c = piece >> 1, half = piece & 1;
-    qs[((row >> 5) * NCHK + c) * 64 + frag_slot(c, half, row & 31)] = v;
-  }
-}
-
-template <int DT, int D>
-__device__ __forceinline__ void load_key_tile(const char *Kb, int64_t row_bytes, int key, int half, Frag *kf) {
-  constexpr int EPC = Tr<DT>::EPC, NCHK = D / (2 * EPC);
-  const char *p = Kb + key * row_bytes + half * 16;
-#pragma unroll
-  for (int c = 0; c < NCHK; ++c) kf[c].q = *reinterpret_cast<const uint4 *>(p + c * 32);
+// Key tiles per chunk: at most four, and few enough that two workgroups (two key buffers, the
+// mean-key tile and the column-sum scratch each) fit in the 160 KB of LDS of a CU.
+__host__ __device__ constexpr int chunk_tiles(int dtype, int D) {
+  const int tile_bytes = D * (dtype == MIXKV_BF16 ? 2 : 4) * 32;
+  return tile_bytes <= 8192 ? 4 : 1;
 }
 
 // Work split of the two streaming kernels.  An item is one chunk of one unit (item = unit_local *
 // nchunks + chunk); workgroup g of G owns the contiguous items [g*T/G, (g+1)*T/G) and walks them in
-// runs that stay inside one unit, so the unit's queries are staged once per run.
+// runs that stay inside one unit.  Run (g, unit_local) writes its partials to slot g + unit_local,
+// which is unique because both grow along the global order of runs.
 __device__ __forceinline__ int64_t wg_first_item(int64_t g, int64_t G, int64_t T) { return g * T / G; }
+
+// LDS image of a key tile: 32 rows of D*EB bytes, row-major, with the 16-byte pieces of row r
+// stored at piece index (p ^ swz(r)).  The rotation makes the MFMA fragment reads (16 consecutive
+// rows, one piece index) hit 16 different bank groups, while a direct-to-LDS load instruction
+// (64 consecutive 16-byte slots) still covers whole rows of global memory.
+template <int DT, int D>
+__device__ __forceinline__ int tile_swz(int r) {
+  constexpr int PPR = D * Tr<DT>::EB / 16;
+  return PPR == 8 ? (r >> 1) & 7 : r & 15;
+}
+
+// Issue the direct-to-LDS loads of one chunk of KT key tiles.  Load j covers slots [64j, 64j+64)
+// of the chunk image; lane i fetches the piece that belongs in slot 64j + i.  Waves take loads
+// round-robin.  The address is a wave-uniform 64-bit base plus a 32-bit lane offset.  In the last
+// chunk of a sequence, keys past N-1 re-read key N-1 (their results are masked or discarded).
+template <int DT, int D, int WAVES>
+__device__ __forceinline__ void fetch_chunk(const char *Kb, int64_t row_bytes, int cbase, int N, uint4 *buf, int wave,
+                                            int lane) {
+  constexpr int PPR = D * Tr<DT>::EB / 16, KT = chunk_tiles(DT, D), CH = KT * 32, LOADS = KT * 32 * PPR / 64;
+  constexpr int RPL = 64 / PPR > 0 ? 64 / PPR : 1;       // rows per load (PPR <= 32)
+  static_assert(PPR <= 64 && 64 % PPR == 0, "row pieces must divide a load");
+  const int lrow = lane / PPR, lq = lane % PPR;
+  const uint32_t rb = (uint32_t)row_bytes;
+  if (cbase + CH <= N) {
+#pragma unroll
+    for (int jj = 0; jj < (LOADS + WAVES - 1) / WAVES; ++jj) {
+      const int j = jj * WAVES + wave;
+      if (LOADS % WAVES != 0 && j >= LOADS) break;
+      const char *base = Kb + (int64_t)(cbase + j * RPL) * row_bytes;             // wave-uniform
+      const uint32_t off = (uint32_t)lrow * rb + (uint32_t)((lq ^ tile_swz<DT, D>((j * RPL + lrow) & 31)) * 16);
+      __builtin_amdgcn_global_load_lds((glb_void_t *)(base + off), (lds_void_t *)(buf + j * 64), 16, 0, 0);
+    }
+  } else {
+#pragma unroll
+    for (int jj = 0; jj < (LOADS + WAVES - 1) / WAVES; ++jj) {
+      const int j = jj * WAVES + wave;
+      if (LOADS % WAVES != 0 && j >= LOADS) break;
+      const int row = j * RPL + lrow;
+      const int krow = min(cbase + row, N - 1);
+      const char *src = Kb + (int64_t)krow * row_bytes + (lq ^ tile_swz<DT, D>(row & 31)) * 16;
+      __builtin_amdgcn_global_load_lds((glb_void_t *)src, (lds_void_t *)(buf + j * 64), 16, 0, 0);
+    }
+  }
+}
+
+// Fragment c of key tile k for lane (row l32, half): piece 2c + half of row l32.
+template <int DT, int D>
+__device__ __forceinline__ uint4 read_key_frag(const uint4 *kb, int k, int c, int l32, int half) {
+  constexpr int PPR = D * Tr<DT>::EB / 16;
+  return kb[(k * 32 + l32) * PPR + ((2 * c + half) ^ tile_swz<DT, D>(l32))];
+}
 
 // ------------------------------------------------------------------------------------------------
 // stats_kernel: first pass over K (and the only pass over V).
-//   * running softmax (max, sum) of every window-query row over the run's keys;
+//   * running softmax (max, sum) of every window-query row over the run's keys: keys on the MFMA
+//     output rows, query rows on the columns, so a lane follows one query row per tile;
 //   * 1/|K_i| and the partial sum of the normalised keys (paper Sec. 3.2 diversity metrics,
 //     Sec. 3.3 Eq. 3-4: only the sum of normalised keys is needed, never the T x T matrix);
 //   * |V_i| (Sec. 3.2, VNorm intrinsic importance).
-// Per-run partials go to the workspace slot of the run's first item; finalize_kernel folds them.
+// Per-run partials go to the workspace; finalize_kernel folds them.
 // ------------------------------------------------------------------------------------------------
-template <int DT, int D, int WAVES, int TPW>
+template <int DT, int D, int WAVES, int TQ>
 __global__ __launch_bounds__(WAVES * 64, 2) void stats_kernel(Shape s, LayerInTable in, char *ws, Workspace w,
-                                                          int64_t unit0, int nunits) {
+                                                             int64_t unit0, int nunits, int64_t slot0) {
   constexpr int EB = Tr<DT>::EB, EPC = Tr<DT>::EPC, NCHK = D / (2 * EPC), NE = D / 2, PPR = D * EB / 16;
-  constexpr int NT = WAVES * 64, CH = WAVES * TPW * 32;
-  constexpr int VB = 4, VPT = CH * PPR / NT / VB;      // V pieces per thread: VB batches of VPT
-  static_assert(CH * PPR % (NT * VB) == 0, "V tiling");
-  extern __shared__ uint4 smem[];
-  const int QTR = s.QT * 32;
-  uint4 *qs = smem;                                                       // [QT * NCHK * 64]
-  float2 *ml_s = reinterpret_cast<float2 *>(smem + s.QT * NCHK * 64);     // [WAVES][QTR]
-  float *ks_s = reinterpret_cast<float *>(ml_s + WAVES * QTR);            // [WAVES][D]
+  constexpr int NT = WAVES * 64, KT = chunk_tiles(DT, D), CH = KT * 32, FRAGS = KT * NCHK;
+  constexpr int VPT = (32 * PPR + NT - 1) / NT;           // V pieces per thread and key tile
+  // Two separately declared key buffers: the compiler can then tell that reads of one do not
+  // depend on the direct-to-LDS loads in flight into the other.
+  __shared__ uint4 kbuf_a[FRAGS * 64], kbuf_b[FRAGS * 64];
+  __shared__ float ks_s[WAVES * D];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
-  const int N = s.N, Nc = s.Nc;
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps its address math scalar
+  const int N = s.N, Nc = s.Nc, QTR = s.QT * 32;
   const float c2 = s.scale_log2e;
   const int free_limit = s.causal ? Nc : N - 1;      // keys <= this are visible to every row
+  const int nq = max(0, min(TQ, s.QT - wave * TQ));  // query tiles this wave owns
+  const bool use_v = s.intrinsic == MIXKV_INTRINSIC_VNORM;
   const int64_t T = (int64_t)nunits * s.nchunks;
   int64_t item = wg_first_item(blockIdx.x, gridDim.x, T);
   const int64_t item_end = wg_first_item(blockIdx.x + 1, gridDim.x, T);
@@ -163,42 +216,52 @@ __global__ __launch_bounds__(WAVES * 64, 2) void stats_kernel(Shape s, LayerInTa
     const int64_t row_bytes = L.sn * EB;
     float *invnorm = reinterpret_cast<float *>(ws + w.invnorm) + unit * s.Npad;
     float *vnorm = reinterpret_cast<float *>(ws + w.vnorm) + unit * s.Npad;
-    const bool use_v = s.intrinsic == MIXKV_INTRINSIC_VNORM;
 
-    __syncthreads();                       // the previous run is done with LDS
-    stage_queries<DT, D>(s, Qb, qs, tid, NT);
-    for (int r = lane; r < QTR; r += 64) ml_s[wave * QTR + r] = make_float2(-INFINITY, 0.f);
+    __syncthreads();                                   // the previous run is done with LDS
+    fetch_chunk<DT, D, WAVES>(Kb, row_bytes, c0 * CH, N, kbuf_a, wave, lane);
     for (int d = lane; d < D; d += 64) ks_s[wave * D + d] = 0.f;
 
-    Frag kfa[TPW][NCHK], kfb[TPW][NCHK];
-    auto load_chunk = [&](int chunk, Frag (&kf)[TPW][NCHK]) {
+    // this wave's query tiles, in fragment form, for the whole run (tiles past QT are zero)
+    Frag qf[TQ][NCHK];
+    int lim[TQ];
+    float m[TQ], l[TQ];
 #pragma unroll
-      for (int j = 0; j < TPW; ++j) {
-        const int key = chunk * CH + (wave * TPW + j) * 32 + l32;
-        load_key_tile<DT, D>(Kb, row_bytes, min(key, N - 1), half, kf[j]);
+    for (int q = 0; q < TQ; ++q) {
+      const int row = (wave * TQ + q) * 32 + l32;
+      const bool live = row < s.GW;
+      const char *qrow = Qb + ((int64_t)(live ? row : 0) * D) * EB + half * 16;
+#pragma unroll
+      for (int c = 0; c < NCHK; ++c) {
+        uint4 v = *reinterpret_cast<const uint4 *>(qrow + c * 32);
+        qf[q][c].q = live ? v : make_uint4(0, 0, 0, 0);
       }
-    };
-    load_chunk(c0, kfa);
-    __syncthreads();                       // queries staged
+      lim[q] = s.causal ? Nc + row % s.W : N - 1;     // last key this row attends to
+      m[q] = -INFINITY;
+      l[q] = 0.f;
+    }
 
-    // one chunk: kf holds its keys, the next chunk's keys are fetched into kn meanwhile
-    auto do_chunk = [&](int chunk, bool has_next, Frag (&kf)[TPW][NCHK], Frag (&kn)[TPW][NCHK]) {
-      const int cbase = chunk * CH;
-      if (has_next) load_chunk(chunk + 1, kn);
-      // ---- |V_i|: VB batches of VPT 16-byte pieces per thread, consumed one q-tile later than issued
+    // one chunk: its keys are in `kb`; the next chunk streams into `kn` meanwhile
+    auto do_chunk = [&](int it, const uint4 *kb, uint4 *kn) {
+      const int cbase = (c0 + it) * CH;
+      __builtin_amdgcn_s_waitcnt(0);                   // this wave's share of the chunk has landed
+      __syncthreads();                                 // ... and everybody else's; the other buffer is free
+      if (it + 1 < nit) fetch_chunk<DT, D, WAVES>(Kb, row_bytes, cbase + CH, N, kn, wave, lane);
+
+      // |V_i| rides along: the rows of key tile k are fetched one tile ahead of their use
       Frag vb[VPT];
-      auto v_issue = [&](int b) {
+      auto v_issue = [&](int k) {
 #pragma unroll
         for (int i = 0; i < VPT; ++i) {
-          const int p = (b * VPT + i) * NT + tid, key = cbase + p / PPR;
-          vb[i].q = make_uint4(0, 0, 0, 0);
-          if (key < Nc) vb[i].q = *reinterpret_cast<const uint4 *>(Vb + key * row_bytes + (p % PPR) * 16);
+          const int p = i * NT + tid, key = cbase + k * 32 + p / PPR;
+          const bool on = p < 32 * PPR && key < Nc;
+          uint4 v = *reinterpret_cast<const uint4 *>(Vb + (on ? key : 0) * row_bytes + (p % PPR) * 16);
+          vb[i].q = on ? v : make_uint4(0, 0, 0, 0);
         }
       };
-      auto v_consume = [&](int b) {
+      auto v_consume = [&](int k) {
 #pragma unroll
         for (int i = 0; i < VPT; ++i) {
-          const int p = (b * VPT + i) * NT + tid, key = cbase + p / PPR;
+          const int p = i * NT + tid, key = cbase + k * 32 + p / PPR;
           float ss = 0.f;
 #pragma unroll
           for (int e = 0; e < EPC; ++e) {
@@ -207,146 +270,123 @@ __global__ __launch_bounds__(WAVES * 64, 2) void stats_kernel(Shape s, LayerInTa
           }
 #pragma unroll
           for (int sft = PPR / 2; sft >= 1; sft >>= 1) ss += __shfl_xor(ss, sft);
-          if (p % PPR == 0 && key < Nc) vnorm[key] = sqrtf(ss);
+          if (p % PPR == 0 && p < 32 * PPR && key < Nc) vnorm[key] = sqrtf(ss);
         }
       };
       if (use_v) v_issue(0);
 
-      // ---- key norms and the sum of normalised keys
-      {
-        float inv[TPW];
+#pragma unroll 1
+      for (int k = 0; k < KT; ++k) {
+        const int tb = cbase + k * 32;
+        if (tb < N) {
+          Frag kf[NCHK];
 #pragma unroll
-        for (int j = 0; j < TPW; ++j) {
-          const int key = cbase + (wave * TPW + j) * 32 + l32;
-          float ss = 0.f;
+          for (int c = 0; c < NCHK; ++c) kf[c].q = read_key_frag<DT, D>(kb, k, c, l32, half);
+
+          // ---- softmax statistics of all TQ tiles; the MFMA chains are independent
+          f32x16 acc[TQ];
+#pragma unroll
+          for (int q = 0; q < TQ; ++q)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[q][i] = 0.f;
 #pragma unroll
           for (int c = 0; c < NCHK; ++c)
 #pragma unroll
-            for (int e = 0; e < EPC; ++e) {
-              float v = frag_elem<DT>(kf[j][c], e);
-              ss = fmaf(v, v, ss);
-            }
-          ss += __shfl_xor(ss, 32);
-          const bool valid = key < N;
-          inv[j] = valid ? 1.f / fmaxf(sqrtf(ss), 1e-30f) : 0.f;
-          if (valid && half == 0) invnorm[key] = inv[j];
-        }
-        // Groups of 32 accumulators (to bound register use).  Fixed-order butterfly over the 32
-        // lanes of a half: every step halves the number of accumulators a lane carries; a lane
-        // ends with one, summed over all 32 keys.
-        constexpr int NG = 32, NGRP = NE / NG, CG = NCHK / NGRP;
+            for (int q = 0; q < TQ; ++q) acc[q] = mma<DT>(kf[c], qf[q][c], acc[q]);
+          if (tb + 31 > free_limit) {                  // tile reaches into the window or past N: mask
 #pragma unroll
-        for (int grp = 0; grp < NGRP; ++grp) {
-          float ks[NG];
+            for (int q = 0; q < TQ; ++q)
 #pragma unroll
-          for (int e = 0; e < NG; ++e) ks[e] = 0.f;
-#pragma unroll
-          for (int j = 0; j < TPW; ++j)
-#pragma unroll
-            for (int c = 0; c < CG; ++c)
-#pragma unroll
-              for (int e = 0; e < EPC; ++e)
-                ks[c * EPC + e] = fmaf(inv[j], frag_elem<DT>(kf[j][grp * CG + c], e), ks[c * EPC + e]);
-          int n = NG, start = 0;
-#pragma unroll
-          for (int sft = 16; sft >= 1; sft >>= 1) {
-            const int hn = n >> 1;
-            const bool up = (lane & sft) != 0;
-#pragma unroll
-            for (int i = 0; i < hn; ++i) {
-              float send = up ? ks[i] : ks[i + hn];
-              float keep = up ? ks[i + hn] : ks[i];
-              ks[i] = keep + __shfl_xor(send, sft);
-            }
-            start += up ? hn : 0;
-            n = hn;
+              for (int i = 0; i < 16; ++i) {
+                int kidx = tb + 8 * (i >> 2) + 4 * half + (i & 3);
+                acc[q][i] = (kidx > lim[q]) ? -INFINITY : acc[q][i];
+              }
           }
 #pragma unroll
-          for (int i = 0; i < NG / 32; ++i) {
-            int e = start + i, c = grp * CG + e / EPC, jj = e % EPC;
-            ks_s[wave * D + (2 * c + half) * EPC + jj] += ks[i];    // this lane owns the slot
+          for (int q = 0; q < TQ; ++q) {
+            float tmax = fmaxf(acc[q][0], acc[q][1]);
+#pragma unroll
+            for (int i = 2; i < 16; i += 2) tmax = fmaxf(fmaxf(tmax, acc[q][i]), acc[q][i + 1]);
+            const float mn = fmaxf(m[q], tmax * c2);          // c2 > 0: scaling commutes with max
+            const float mu = (mn == -INFINITY) ? 0.f : mn;
+            float sum = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(acc[q][i], c2, -mu));
+            l[q] = l[q] * fast_exp2(m[q] - mu) + sum;
+            m[q] = mn;
           }
-        }
-      }
 
-      // ---- softmax statistics: keys on the MFMA output rows, query rows on the columns (lane % 32)
-      for (int t = 0; t < s.QT; ++t) {
-        Frag qf[NCHK];
+          // ---- key norms and the sum of normalised keys: one wave per tile, round-robin
+          if ((k + it * KT) % WAVES == wave) {
+            const int key = tb + l32;
+            float ss = 0.f;
 #pragma unroll
-        for (int c = 0; c < NCHK; ++c) qf[c].q = qs[(t * NCHK + c) * 64 + frag_slot(c, half, l32)];
-        const int row = t * 32 + l32;
-        const int lim = s.causal ? Nc + row % s.W : N - 1;   // last key this row attends to
-        float2 ml = ml_s[wave * QTR + t * 32 + l32 + 0 * half];
-        float m = ml.x, l = ml.y;
-        if (half) { m = -INFINITY; l = 0.f; }                // the running pair lives in half 0
+            for (int c = 0; c < NCHK; ++c)
 #pragma unroll
-        for (int j = 0; j < TPW; ++j) {
-          const int tb = cbase + (wave * TPW + j) * 32;
-          if (tb >= N) continue;
-          f32x16 acc;
+              for (int e = 0; e < EPC; ++e) {
+                float v = frag_elem<DT>(kf[c], e);
+                ss = fmaf(v, v, ss);
+              }
+            ss += __shfl_xor(ss, 32);
+            const bool valid = key < N;
+            const float inv = valid ? 1.f / fmaxf(sqrtf(ss), 1e-30f) : 0.f;
+            if (valid && half == 0) invnorm[key] = inv;
+            // Groups of 32 accumulators (to bound register use).  Fixed-order butterfly over the
+            // 32 lanes of a half: every step halves the number of accumulators a lane carries; a
+            // lane ends with one, summed over all 32 keys.
+            constexpr int NG = 32, NGRP = NE / NG, CG = NCHK / NGRP;
 #pragma unroll
-          for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+            for (int grp = 0; grp < NGRP; ++grp) {
+              float ks[NG];
 #pragma unroll
-          for (int c = 0; c < NCHK; ++c) acc = mma<DT>(kf[j][c], qf[c], acc);
-          if (tb + 31 > free_limit) {
+              for (int c = 0; c < CG; ++c)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              int kidx = tb + 8 * (i >> 2) + 4 * half + (i & 3);
-              if (kidx > lim) acc[i] = -INFINITY;
+                for (int e = 0; e < EPC; ++e) ks[c * EPC + e] = inv * frag_elem<DT>(kf[grp * CG + c], e);
+              int n = NG, start = 0;
+#pragma unroll
+              for (int sft = 16; sft >= 1; sft >>= 1) {
+                const int hn = n >> 1;
+                const bool up = (lane & sft) != 0;
+                const uint32_t um = up ? 0xffffffffu : 0u;    // bit select: keeps the accumulators in registers
+#pragma unroll
+                for (int i = 0; i < hn; ++i) {
+                  const uint32_t lo = __float_as_uint(ks[i]), hi = __float_as_uint(ks[i + hn]);
+                  const float send = __uint_as_float((lo & um) | (hi & ~um));
+                  const float keep = __uint_as_float((hi & um) | (lo & ~um));
+                  ks[i] = keep + __shfl_xor(send, sft);
+                }
+                start += up ? hn : 0;
+                n = hn;
+              }
+              const int c = grp * CG + start / EPC, jj = start % EPC;
+              ks_s[wave * D + (2 * c + half) * EPC + jj] += ks[0];    // this lane owns the slot
             }
           }
-          float tmax = fmaxf(acc[0], acc[1]);
-#pragma unroll
-          for (int i = 2; i < 16; i += 2) tmax = fmaxf(fmaxf(tmax, acc[i]), acc[i + 1]);
-          const float mn = fmaxf(m, tmax * c2);              // c2 > 0: scaling commutes with max
-          const float mu = (mn == -INFINITY) ? 0.f : mn;
-          float sum = 0.f;
-#pragma unroll
-          for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(acc[i], c2, -mu));
-          l = l * fast_exp2(m - mu) + sum;
-          m = mn;
         }
-        ml_merge(m, l, __shfl_xor(m, 32), __shfl_xor(l, 32));
-        if (half == 0) ml_s[wave * QTR + row] = make_float2(m, l);
-        if (use_v && t < VB) {
-          v_consume(t);
-          if (t + 1 < VB) v_issue(t + 1);
+        if (use_v) {
+          v_consume(k);
+          if (k + 1 < KT) v_issue(k + 1);
         }
       }
-      if (use_v)
-        for (int b = min(s.QT, VB); b < VB; ++b) {
-          if (b > 0) v_issue(b);       // batch 0 was issued before the q-tile loop
-          v_consume(b);
-        }
     };
-
-#if MIXKV_PREFETCH
     for (int it = 0; it < nit; it += 2) {
-      do_chunk(c0 + it, it + 1 < nit, kfa, kfb);
-      if (it + 1 < nit) do_chunk(c0 + it + 1, it + 2 < nit, kfb, kfa);
+      do_chunk(it, kbuf_a, kbuf_b);
+      if (it + 1 < nit) do_chunk(it + 1, kbuf_b, kbuf_a);
     }
-#else
-    for (int it = 0; it < nit; ++it) {
-      if (it > 0) load_chunk(c0 + it, kfa);
-      do_chunk(c0 + it, false, kfa, kfb);
-    }
-#endif
-    __syncthreads();   // ml_s, ks_s complete
 
-    // ---- run partials to global, waves folded in a fixed order
-    float2 *part_ml = reinterpret_cast<float2 *>(ws + w.part_ml) + (unit0 * s.nchunks + item) * QTR;
-    for (int r = tid; r < QTR; r += NT) {
-      float m = -INFINITY, l = 0.f;
-      for (int wv = 0; wv < WAVES; ++wv) {
-        float2 p = ml_s[wv * QTR + r];
-        ml_merge(m, l, p.x, p.y);
-      }
-      part_ml[r] = make_float2(m, l);
+    // ---- run partials to global
+    const int64_t slot = slot0 + blockIdx.x + ul;
+    float2 *part_ml = reinterpret_cast<float2 *>(ws + w.part_ml) + slot * QTR;
+#pragma unroll
+    for (int q = 0; q < TQ; ++q) {
+      ml_merge(m[q], l[q], __shfl_xor(m[q], 32), __shfl_xor(l[q], 32));
+      if (q < nq && half == 0) part_ml[(wave * TQ + q) * 32 + l32] = make_float2(m[q], l[q]);
     }
-    float *part_ks = reinterpret_cast<float *>(ws + w.part_ksum) + (unit0 * s.nchunks + item) * D;
+    __syncthreads();                                   // ks_s complete
+    float *part_ks = reinterpret_cast<float *>(ws + w.part_ksum) + slot * D;
     for (int d = tid; d < D; d += NT) {
       float a = 0.f;
-      for (int wv = 0; wv < WAVES; ++wv) a += ks_s[wv * D + d];
+      for (int wv = 0; wv < WAVES; ++wv) a += ks_s[wv * D + d];   // fixed order
       part_ks[d] = a;
     }
     item += nit;
@@ -361,48 +401,46 @@ __global__ __launch_bounds__(WAVES * 64, 2) void stats_kernel(Shape s, LayerInTa
 // it after every workgroup of stats_kernel, so no fences or atomics are needed.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void finalize_kernel(Shape s, LayerOutTable out, char *ws, Workspace w,
-                                                      int64_t unit0, int nunits, int G) {
+                                                      int64_t unit0, int nunits, int G, int64_t slot0) {
   __shared__ double red_s[4];
-  __shared__ int g_lo_s;
+  __shared__ int g_lo_s, g_hi_s;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, NT = 256;
   const int ul = blockIdx.x;
   const int64_t unit = unit0 + ul;
   const UnitCoord uc = unit_coord(s, ul);
   const int QTR = s.QT * 32, D = s.D, N = s.N;
   const int64_t T = (int64_t)nunits * s.nchunks, first = (int64_t)ul * s.nchunks, last = first + s.nchunks;
-  // Workgroup g of stats_kernel wrote, for this unit, one partial at slot max(start(g), first) if its
-  // item range [start(g), start(g+1)) meets [first, last).  g_lo is the workgroup owning item `first`.
+  // The workgroups g_lo..g_hi of stats_kernel are those whose item range meets [first, last);
+  // each wrote one partial for this unit, at slot g + ul.
   if (tid == 0) {
     int64_t g = first * G / T;
     while (g > 0 && wg_first_item(g, G, T) > first) --g;
     while (wg_first_item(g + 1, G, T) <= first) ++g;
     g_lo_s = (int)g;
+    while (g + 1 < G && wg_first_item(g + 1, G, T) < last) ++g;
+    g_hi_s = (int)g;
   }
   __syncthreads();
-  const int g_lo = g_lo_s;
-  const float2 *all_ml = reinterpret_cast<const float2 *>(ws + w.part_ml) + unit0 * s.nchunks * QTR;
+  const int g_lo = g_lo_s, g_hi = g_hi_s;
+  const float2 *all_ml = reinterpret_cast<const float2 *>(ws + w.part_ml) + (slot0 + ul) * QTR;
   float *brow = reinterpret_cast<float *>(ws + w.brow) + unit * QTR;
   for (int r = tid; r < QTR; r += NT) {
     float m = -INFINITY, l = 0.f;
-    for (int64_t g = g_lo; g < G; ++g) {
-      const int64_t a = max(wg_first_item(g, G, T), first), b = min(wg_first_item(g + 1, G, T), last);
-      if (a >= last) break;
-      if (b <= a) continue;
-      float2 p = all_ml[a * QTR + r];
+    for (int g = g_lo; g <= g_hi; ++g) {
+      if (wg_first_item(g + 1, G, T) <= wg_first_item(g, G, T)) continue;     // workgroup without items
+      float2 p = all_ml[(int64_t)g * QTR + r];
       ml_merge(m, l, p.x, p.y);
     }
     brow[r] = (r < s.GW) ? m + log2f(l) + log2f((float)s.GW) : INFINITY;
   }
-  const float *all_ks = reinterpret_cast<const float *>(ws + w.part_ksum) + unit0 * s.nchunks * D;
+  const float *all_ks = reinterpret_cast<const float *>(ws + w.part_ksum) + (slot0 + ul) * D;
   float *kbar = reinterpret_cast<float *>(ws + w.kbar) + unit * D;
   double sq = 0.0;
   for (int d = tid; d < D; d += NT) {
     float a = 0.f;
-    for (int64_t g = g_lo; g < G; ++g) {
-      const int64_t ia = max(wg_first_item(g, G, T), first), ib = min(wg_first_item(g + 1, G, T), last);
-      if (ia >= last) break;
-      if (ib <= ia) continue;
-      a += all_ks[ia * D + d];
+    for (int g = g_lo; g <= g_hi; ++g) {
+      if (wg_first_item(g + 1, G, T) <= wg_first_item(g, G, T)) continue;
+      a += all_ks[(int64_t)g * D + d];
     }
     kbar[d] = a / (float)N;
     sq += (double)a * (double)a;
@@ -423,30 +461,41 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, LayerOutTable ou
 
 // ------------------------------------------------------------------------------------------------
 // attn_kernel: second pass over K.
-//   a_i   = (1 / (G*W)) * sum over window rows of softmax weights on key i   (Sec. 3.2, extrinsic)
-//   sdiv_i = -(K_i . Kbar) / |K_i|                                          (Sec. 3.2, diversity)
-// Query rows on the MFMA output rows, keys on the columns: the sum over rows is a register sum.
-// The mean key rides along as one more tile of "query" rows (split hi + lo for bf16 so that the
-// dot product keeps fp32 accuracy).
+//   a_i    = (1 / (G*W)) * sum over window rows of softmax weights on key i   (Sec. 3.2, extrinsic)
+//   kdot_i = K_i . Kbar; the mix kernel turns it into -(K_i . Kbar) / |K_i|   (Sec. 3.2, diversity)
+// Query rows on the MFMA output rows, keys on the columns: a wave's sum over its rows is a register
+// sum; the waves' partial column sums meet in LDS and are added in a fixed order.  The mean key is
+// two more "query" rows (hi + lo bf16 halves, so the dot keeps fp32 accuracy).  When the padded
+// query block has a spare tile they sit in its rows 0 and 1 and cost nothing; otherwise every wave
+// applies a separate mean-key tile to every WAVES-th key tile.
 // ------------------------------------------------------------------------------------------------
-template <int DT, int D, int WAVES, int TPW>
+template <int DT, int D, int WAVES, int TQ>
 __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTable in, char *ws, Workspace w,
-                                                         int64_t unit0, int nunits) {
+                                                            int64_t unit0, int nunits) {
   constexpr int EB = Tr<DT>::EB, EPC = Tr<DT>::EPC, NCHK = D / (2 * EPC);
-  constexpr int NT = WAVES * 64, CH = WAVES * TPW * 32;
-  extern __shared__ uint4 smem[];
-  const int QTR = s.QT * 32;
-  uint4 *qs = smem;                                                          // [(QT + 1) * NCHK * 64]
-  float *brow_s = reinterpret_cast<float *>(smem + (s.QT + 1) * NCHK * 64);  // [QTR]
-  int *lim_s = reinterpret_cast<int *>(brow_s + QTR);                        // [QTR]
+  constexpr int NT = WAVES * 64, KT = chunk_tiles(DT, D), CH = KT * 32, FRAGS = KT * NCHK;
+  __shared__ uint4 kbuf_a[FRAGS * 64], kbuf_b[FRAGS * 64];   // separate objects, see stats_kernel
+  __shared__ uint4 kbar_s[NCHK * 4];                         // mean-key rows 0/1 x halves, 16-byte pieces
+  __shared__ float cs_s[2 * WAVES * CH];                     // [2][WAVES][CH] partial column sums
+  __shared__ float nb_s[WAVES * TQ * 32];                    // -b_r per query row (-inf rows give weight 0)
+  __shared__ int lim_s[WAVES * TQ * 32];                     // last key each query row attends to
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
-  const int N = s.N, Nc = s.Nc;
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps its address math scalar
+  const int N = s.N, Nc = s.Nc, QTR = s.QT * 32;
   const float c2 = s.scale_log2e;
   const int free_limit = s.causal ? Nc : N - 1;
+  for (int r = tid; r < WAVES * TQ * 32; r += NT) lim_s[r] = s.causal ? Nc + r % s.W : N - 1;
+  // the mean key rides in rows 0/1 of the first tile past the live rows, if the block has one
+  const bool spare = s.QT < WAVES * TQ;
+  const int kb_wave = s.QT / TQ, kb_q = s.QT % TQ;
   const int64_t T = (int64_t)nunits * s.nchunks;
   int64_t item = wg_first_item(blockIdx.x, gridDim.x, T);
   const int64_t item_end = wg_first_item(blockIdx.x + 1, gridDim.x, T);
+  TDECL;
+#ifdef MIXKV_TIMING
+  if (threadIdx.x == 0) { mixkv_dbg[blockIdx.x * 16 + 4] = wall_clock64(); mixkv_dbg[blockIdx.x * 16 + 6] = __builtin_readcyclecounter(); }
+#endif
 
   while (item < item_end) {
     const int ul = (int)(item / s.nchunks), c0 = (int)(item - (int64_t)ul * s.nchunks);
@@ -457,195 +506,234 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
     const char *Kb = reinterpret_cast<const char *>(L.K) + ((int64_t)uc.b * L.sb + (int64_t)uc.h * L.sh) * EB;
     const char *Qb = reinterpret_cast<const char *>(L.Q) + ((int64_t)(uc.b * s.hq + uc.h * s.G) * s.W * D) * EB;
     const int64_t row_bytes = L.sn * EB;
-    const float *invnorm = reinterpret_cast<const float *>(ws + w.invnorm) + unit * s.Npad;
     float *araw = reinterpret_cast<float *>(ws + w.araw) + unit * s.Npad;
-    float *sdiv = reinterpret_cast<float *>(ws + w.sdiv) + unit * s.Npad;
+    float *kdot = reinterpret_cast<float *>(ws + w.sdiv) + unit * s.Npad;   // K_i . Kbar, not yet normalised
+    const float *brow = reinterpret_cast<const float *>(ws + w.brow) + unit * QTR;
+    const float *kbar = reinterpret_cast<const float *>(ws + w.kbar) + unit * D;
 
-    Frag kfa[TPW][NCHK], kfb[TPW][NCHK];
-    auto load_chunk = [&](int chunk, Frag (&kf)[TPW][NCHK]) {
-#pragma unroll
-      for (int j = 0; j < TPW; ++j) {
-        const int key = chunk * CH + (wave * TPW + j) * 32 + l32;
-        load_key_tile<DT, D>(Kb, row_bytes, min(key, N - 1), half, kf[j]);
-      }
-    };
-    load_chunk(c0, kfa);                   // in flight while the queries are staged
+    TSTAMP(p0);
+    __syncthreads();                                   // the previous run is done with LDS
+    fetch_chunk<DT, D, WAVES>(Kb, row_bytes, c0 * CH, N, kbuf_a, wave, lane);
+    TSTAMP(p1);
 
-    __syncthreads();                       // the previous run is done with LDS
-    stage_queries<DT, D>(s, Qb, qs, tid, NT);
-    {
-      // extra tile: row 0 (and row 1 for bf16) carry the mean normalised key
-      const float *kbar = reinterpret_cast<const float *>(ws + w.kbar) + unit * D;
-      uint4 *xt = qs + s.QT * NCHK * 64;
-      for (int p = tid; p < NCHK * 64; p += NT) {
-        const int c = p >> 6, ln = p & 63, row = ln & 31, hf = ln >> 5;
-        Frag f;
-        f.q = make_uint4(0, 0, 0, 0);
-        if (row < 2) {
-          const float *src = kbar + (2 * c + hf) * EPC;
-          if constexpr (DT == MIXKV_BF16) {
+    // The mean key as two rows of 16-byte pieces: row 0 carries the mean key (its bf16 head), row 1
+    // the bf16 remainder (zero for f32).  Piece (c, half) of row r sits at kbar_s[(c * 2 + half) * 2 + r].
+    for (int p = tid; p < NCHK * 4; p += NT) {
+      const int row = p & 1, hf = (p >> 1) & 1, c = p >> 2;
+      const float *src = kbar + (2 * c + hf) * EPC;
+      Frag f;
+      f.q = make_uint4(0, 0, 0, 0);
+      if constexpr (DT == MIXKV_BF16) {
 #pragma unroll
-            for (int e = 0; e < EPC; ++e) {
-              float v = src[e];
-              uint16_t hi = f32_to_bf16_rne(v);
-              uint16_t bits = hi;
-              if (row == 1) bits = f32_to_bf16_rne(v - __uint_as_float((uint32_t)hi << 16));
-              f.u[e >> 1] |= (uint32_t)bits << ((e & 1) * 16);
-            }
-          } else {
-            if (row == 0)
-#pragma unroll
-              for (int e = 0; e < EPC; ++e) f.f[e] = src[e];
-          }
+        for (int e = 0; e < EPC; ++e) {
+          float v = src[e];
+          uint16_t hi = f32_to_bf16_rne(v);
+          uint16_t bits = hi;
+          if (row == 1) bits = f32_to_bf16_rne(v - __uint_as_float((uint32_t)hi << 16));
+          f.u[e >> 1] |= (uint32_t)bits << ((e & 1) * 16);
         }
-        xt[c * 64 + frag_slot(c, hf, row)] = f.q;
+      } else {
+        if (row == 0) f.q = *reinterpret_cast<const uint4 *>(src);
       }
-      const float *brow = reinterpret_cast<const float *>(ws + w.brow) + unit * QTR;
-      for (int r = tid; r < QTR; r += NT) {
-        brow_s[r] = brow[r];
-        lim_s[r] = s.causal ? Nc + r % s.W : N - 1;
+      kbar_s[p] = f.q;
+    }
+    for (int r = tid; r < WAVES * TQ * 32; r += NT) nb_s[r] = (r < QTR) ? -brow[r] : -INFINITY;
+    TSTAMP(p2);
+    __syncthreads();                                   // kbar_s visible
+    TSTAMP(p3);
+
+    // this wave's query tiles, in fragment form, for the whole run (tiles past QT are zero,
+    // except for the two mean-key rows)
+    Frag qf[TQ][NCHK];
+#pragma unroll
+    for (int q = 0; q < TQ; ++q) {
+      const int row = (wave * TQ + q) * 32 + l32;
+      const bool live = row < s.GW;
+      const bool mean_rows = spare && wave == kb_wave && q == kb_q && l32 < 2;
+      const char *qrow = Qb + ((int64_t)(live ? row : 0) * D) * EB + half * 16;
+#pragma unroll
+      for (int c = 0; c < NCHK; ++c) {
+        uint4 v = *reinterpret_cast<const uint4 *>(qrow + c * 32);
+        uint4 mk = kbar_s[(c * 2 + half) * 2 + (l32 & 1)];
+        qf[q][c].q = live ? v : (mean_rows ? mk : make_uint4(0, 0, 0, 0));
       }
     }
-    __syncthreads();
 
-    auto do_chunk = [&](int chunk, bool has_next, Frag (&kf)[TPW][NCHK], Frag (&kn)[TPW][NCHK]) {
-      const int cbase = chunk * CH;
-      if (has_next) load_chunk(chunk + 1, kn);
-      float colsum[TPW];
+    TSTAMP(p4);
+    TACC(4, p0, p1); TACC(5, p1, p2); TACC(6, p2, p3); TACC(7, p3, p4);
+    // add the waves' partial column sums of chunk `chunk` (buffer pb) in a fixed order
+    auto flush_colsums = [&](int chunk, int pb) {
+      for (int i = tid; i < CH; i += NT) {
+        const int key = chunk * CH + i;
+        float a = 0.f;
+        for (int wv = 0; wv < WAVES; ++wv) a += cs_s[(pb * WAVES + wv) * CH + i];
+        if (key < Nc) araw[key] = a;
+      }
+    };
+
+    auto do_chunk = [&](int it, const uint4 *kb, uint4 *kn) {
+      const int cbase = (c0 + it) * CH;
+      TSTAMP(t0);
+      __builtin_amdgcn_s_waitcnt(0);
+      TSTAMP(t1);
+      __syncthreads();
+      TSTAMP(t2);
+      if (it + 1 < nit) fetch_chunk<DT, D, WAVES>(Kb, row_bytes, cbase + CH, N, kn, wave, lane);
+      if (it > 0) flush_colsums(c0 + it - 1, (it - 1) & 1);
+      float *cs = cs_s + ((it & 1) * WAVES + wave) * CH;
+      TSTAMP(t3);
+      TACC(0, t0, t1); TACC(1, t1, t2); TACC(2, t2, t3);
+
+      Frag kf[NCHK];
 #pragma unroll
-      for (int j = 0; j < TPW; ++j) colsum[j] = 0.f;
-      for (int t = 0; t < s.QT; ++t) {
-        Frag qf[NCHK];
+      for (int c = 0; c < NCHK; ++c) kf[c].q = read_key_frag<DT, D>(kb, 0, c, l32, half);
+#pragma unroll 1
+      for (int k = 0; k < KT; ++k) {
+        const int tb = cbase + k * 32;
+        f32x16 acc[TQ];
 #pragma unroll
-        for (int c = 0; c < NCHK; ++c) qf[c].q = qs[(t * NCHK + c) * 64 + frag_slot(c, half, l32)];
-        float nb[16];
+        for (int q = 0; q < TQ; ++q)
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          float4 b4 = *reinterpret_cast<const float4 *>(&brow_s[t * 32 + 8 * k + 4 * half]);
-          nb[4 * k + 0] = -b4.x; nb[4 * k + 1] = -b4.y; nb[4 * k + 2] = -b4.z; nb[4 * k + 3] = -b4.w;
+          for (int i = 0; i < 16; ++i) acc[q][i] = 0.f;
+#pragma unroll
+        for (int c = 0; c < NCHK; ++c)
+#pragma unroll
+          for (int q = 0; q < TQ; ++q) acc[q] = mma<DT>(qf[q][c], kf[c], acc[q]);
+        float kd = 0.f;
+        if (!spare) {
+          // no spare tile: a separate mean-key tile on every WAVES-th key tile
+          if ((k + it * KT) % WAVES == wave) {
+            f32x16 acd;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acd[i] = 0.f;
+#pragma unroll
+            for (int c = 0; c < NCHK; ++c) {
+              Frag kbf;
+              kbf.q = kbar_s[(c * 2 + half) * 2 + (l32 & 1)];
+              if (l32 >= 2) kbf.q = make_uint4(0, 0, 0, 0);
+              acd = mma<DT>(kbf, kf[c], acd);
+            }
+            kd = acd[0] + acd[1];
+          }
         }
+        // the fragments of the next tile travel LDS -> registers under this tile's arithmetic
+        if (k + 1 < KT) {
 #pragma unroll
-        for (int j = 0; j < TPW; ++j) {
-          const int tb = cbase + (wave * TPW + j) * 32;
-          if (tb >= N) continue;
-          f32x16 acc;
+          for (int c = 0; c < NCHK; ++c) kf[c].q = read_key_frag<DT, D>(kb, k + 1, c, l32, half);
+        }
+        if (spare) kd = (kb_q == 0 ? acc[0][0] + acc[0][1] : acc[TQ - 1][0] + acc[TQ - 1][1]);   // rows 0, 1: half 0
+        const bool kd_mine = spare ? wave == kb_wave : (k + it * KT) % WAVES == wave;
+        const int key = tb + l32;
+        if (kd_mine && half == 0 && key < Nc) kdot[key] = kd;
+
+        if (tb + 31 > free_limit) {                    // tile reaches into the window or past N: mask
 #pragma unroll
-          for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-#pragma unroll
-          for (int c = 0; c < NCHK; ++c) acc = mma<DT>(qf[c], kf[j][c], acc);
-          float sum = 0.f;
-          if (tb + 31 > free_limit) {
-            const int key = tb + l32;
+          for (int q = 0; q < TQ; ++q)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-              const int row = t * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-              float p = fast_exp2(fmaf(acc[i], c2, nb[i]));
-              sum += (key <= lim_s[row]) ? p : 0.f;
+              const int row = (wave * TQ + q) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+              acc[q][i] = (key <= lim_s[row]) ? acc[q][i] : -INFINITY;
             }
-          } else {
+        }
+        float colsum = 0.f;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(acc[i], c2, nb[i]));
+        for (int q = 0; q < TQ; ++q)
+#pragma unroll
+          for (int k4 = 0; k4 < 4; ++k4) {
+            const float4 nb = *reinterpret_cast<const float4 *>(&nb_s[(wave * TQ + q) * 32 + 8 * k4 + 4 * half]);
+            colsum += fast_exp2(fmaf(acc[q][4 * k4 + 0], c2, nb.x)) + fast_exp2(fmaf(acc[q][4 * k4 + 1], c2, nb.y)) +
+                      fast_exp2(fmaf(acc[q][4 * k4 + 2], c2, nb.z)) + fast_exp2(fmaf(acc[q][4 * k4 + 3], c2, nb.w));
           }
-          colsum[j] += sum;
-        }
+        colsum += __shfl_xor(colsum, 32);
+        if (half == 0) cs[k * 32 + l32] = (tb < N) ? colsum : 0.f;
       }
-      // diversity dot products and write-out
-      Frag qf[NCHK];
-#pragma unroll
-      for (int c = 0; c < NCHK; ++c) qf[c].q = qs[(s.QT * NCHK + c) * 64 + frag_slot(c, half, l32)];
-#pragma unroll
-      for (int j = 0; j < TPW; ++j) {
-        const int tb = cbase + (wave * TPW + j) * 32;
-        if (tb >= N) continue;
-        f32x16 acc;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-#pragma unroll
-        for (int c = 0; c < NCHK; ++c) acc = mma<DT>(qf[c], kf[j][c], acc);
-        const float dot = acc[0] + acc[1];                       // rows 0 and 1 live in half 0
-        const float a = colsum[j] + __shfl_xor(colsum[j], 32);
-        const int key = tb + l32;
-        if (half == 0 && key < Nc) {
-          araw[key] = a;
-          sdiv[key] = -dot * invnorm[key];
-        }
-      }
+      TSTAMP(t4);
+      TACC(3, t3, t4);
     };
-
-#if MIXKV_PREFETCH
     for (int it = 0; it < nit; it += 2) {
-      do_chunk(c0 + it, it + 1 < nit, kfa, kfb);
-      if (it + 1 < nit) do_chunk(c0 + it + 1, it + 2 < nit, kfb, kfa);
+      do_chunk(it, kbuf_a, kbuf_b);
+      if (it + 1 < nit) do_chunk(it + 1, kbuf_b, kbuf_a);
     }
-#else
-    for (int it = 0; it < nit; ++it) {
-      if (it > 0) load_chunk(c0 + it, kfa);
-      do_chunk(c0 + it, false, kfa, kfb);
-    }
-#endif
+    __syncthreads();
+    flush_colsums(c0 + nit - 1, (nit - 1) & 1);
     item += nit;
   }
+  TFLUSH;
+#ifdef MIXKV_TIMING
+  if (threadIdx.x == 0) { mixkv_dbg[blockIdx.x * 16 + 5] = wall_clock64(); mixkv_dbg[blockIdx.x * 16 + 7] = __builtin_readcyclecounter(); }
+#endif
 }
 
 // ------------------------------------------------------------------------------------------------
 // launchers
 // ------------------------------------------------------------------------------------------------
-constexpr int kWaves = 4;
-constexpr int kWgPerCu = 2;           // resident workgroups per CU the grid is sized for
-// Key tiles per wave: two where a tile's fragments take 32 registers, one for f32 with D = 128.
-template <int DT, int D> struct Tpw { static constexpr int v = (D * Tr<DT>::EB > 256) ? 1 : 2; };
+int stream_chunk_keys(int dtype, int D) { return chunk_tiles(dtype, D) * 32; }
 
-int stream_chunk_keys(int dtype, int D) {
-  const int tpw = (D * (dtype == MIXKV_BF16 ? 2 : 4) > 256) ? 1 : 2;
-  return kWaves * tpw * kTileKeys;
+// Waves per workgroup and query tiles per wave for a given number of query tiles.
+static void stream_config(int QT, int *waves, int *tq) {
+  *waves = QT <= 8 ? 4 : 8;
+  *tq = QT <= 4 ? 1 : 2;
 }
 
 // Grid of the two streaming kernels: enough workgroups to fill the chip once, never more than items.
 int stream_grid(const Shape &s, int nunits, int num_cus) {
+  int waves, tq;
+  stream_config(s.QT, &waves, &tq);
   const int64_t T = (int64_t)nunits * s.nchunks;
-  const int64_t cap = (int64_t)num_cus * kWgPerCu;
+  int64_t cap = (int64_t)num_cus * (waves == 4 ? 2 : 1);
+  if (cap > kMaxStreamGrid) cap = kMaxStreamGrid;
   return (int)(T < cap ? T : cap);
+}
+
+template <int DT, int D, int WAVES, int TQ>
+static hipError_t launch_stats_c(const Shape &s, const LayerInTable &in, char *ws, const Workspace &w, int64_t unit0,
+                                 int nunits, int grid, int64_t slot0, hipStream_t st) {
+  auto kern = stats_kernel<DT, D, WAVES, TQ>;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES * 64), 0, st, s, in, ws, w, unit0, nunits, slot0);
+  return hipGetLastError();
+}
+
+template <int DT, int D, int WAVES, int TQ>
+static hipError_t launch_attn_c(const Shape &s, const LayerInTable &in, char *ws, const Workspace &w, int64_t unit0,
+                                int nunits, int grid, hipStream_t st) {
+  auto kern = attn_kernel<DT, D, WAVES, TQ>;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES * 64), 0, st, s, in, ws, w, unit0, nunits);
+  return hipGetLastError();
 }
 
 template <int DT, int D>
 static hipError_t launch_stats_t(const Shape &s, const LayerInTable &in, char *ws, const Workspace &w, int64_t unit0,
-                                 int nunits, int grid, hipStream_t st) {
-  constexpr int NCHK = D / (2 * Tr<DT>::EPC);
-  const int QTR = s.QT * 32;
-  size_t lds = (size_t)s.QT * NCHK * 1024 + (size_t)kWaves * QTR * 8 + (size_t)kWaves * D * 4;
-  auto kern = stats_kernel<DT, D, kWaves, Tpw<DT, D>::v>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(kWaves * 64), lds, st, s, in, ws, w, unit0, nunits);
-  return hipGetLastError();
+                                 int nunits, int grid, int64_t slot0, hipStream_t st) {
+  int waves, tq;
+  stream_config(s.QT, &waves, &tq);
+  if (waves == 4 && tq == 1) return launch_stats_c<DT, D, 4, 1>(s, in, ws, w, unit0, nunits, grid, slot0, st);
+  if (waves == 4) return launch_stats_c<DT, D, 4, 2>(s, in, ws, w, unit0, nunits, grid, slot0, st);
+  return launch_stats_c<DT, D, 8, 2>(s, in, ws, w, unit0, nunits, grid, slot0, st);
 }
 
 template <int DT, int D>
 static hipError_t launch_attn_t(const Shape &s, const LayerInTable &in, char *ws, const Workspace &w, int64_t unit0,
                                 int nunits, int grid, hipStream_t st) {
-  constexpr int NCHK = D / (2 * Tr<DT>::EPC);
-  const int QTR = s.QT * 32;
-  size_t lds = (size_t)(s.QT + 1) * NCHK * 1024 + (size_t)QTR * 8;
-  auto kern = attn_kernel<DT, D, kWaves, Tpw<DT, D>::v>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(kWaves * 64), lds, st, s, in, ws, w, unit0, nunits);
-  return hipGetLastError();
+  int waves, tq;
+  stream_config(s.QT, &waves, &tq);
+  if (waves == 4 && tq == 1) return launch_attn_c<DT, D, 4, 1>(s, in, ws, w, unit0, nunits, grid, st);
+  if (waves == 4) return launch_attn_c<DT, D, 4, 2>(s, in, ws, w, unit0, nunits, grid, st);
+  return launch_attn_c<DT, D, 8, 2>(s, in, ws, w, unit0, nunits, grid, st);
 }
 
 hipError_t launch_stats(const Shape &s, int dtype, const LayerInTable &in, char *ws, const Workspace &w, int64_t unit0,
-                        int nunits, int grid, hipStream_t st) {
+                        int nunits, int grid, int64_t slot0, hipStream_t st) {
   if (dtype == MIXKV_BF16) {
-    if (s.D == 128) return launch_stats_t<MIXKV_BF16, 128>(s, in, ws, w, unit0, nunits, grid, st);
-    return launch_stats_t<MIXKV_BF16, 64>(s, in, ws, w, unit0, nunits, grid, st);
+    if (s.D == 128) return launch_stats_t<MIXKV_BF16, 128>(s, in, ws, w, unit0, nunits, grid, slot0, st);
+    return launch_stats_t<MIXKV_BF16, 64>(s, in, ws, w, unit0, nunits, grid, slot0, st);
   }
-  if (s.D == 128) return launch_stats_t<MIXKV_F32, 128>(s, in, ws, w, unit0, nunits, grid, st);
-  return launch_stats_t<MIXKV_F32, 64>(s, in, ws, w, unit0, nunits, grid, st);
+  if (s.D == 128) return launch_stats_t<MIXKV_F32, 128>(s, in, ws, w, unit0, nunits, grid, slot0, st);
+  return launch_stats_t<MIXKV_F32, 64>(s, in, ws, w, unit0, nunits, grid, slot0, st);
 }
 
 hipError_t launch_finalize(const Shape &s, const LayerOutTable &out, char *ws, const Workspace &w, int64_t unit0,
-                           int nunits, int grid, hipStream_t st) {
-  hipLaunchKernelGGL(finalize_kernel, dim3(nunits), dim3(256), 0, st, s, out, ws, w, unit0, nunits, grid);
+                           int nunits, int grid, int64_t slot0, hipStream_t st) {
+  hipLaunchKernelGGL(finalize_kernel, dim3(nunits), dim3(256), 0, st, s, out, ws, w, unit0, nunits, grid, slot0);
   return hipGetLastError();
 }
 
