@@ -150,7 +150,7 @@ mixkv_status mixkv_compress(const mixkv_params *params, const mixkv_layer_in *in
  * n_layers exceeds one group).  Stage names come from mixkv_stage_name.  Outputs are those of
  * mixkv_compress (Algorithm 1).
  */
-#define MIXKV_N_STAGES 6
+#define MIXKV_N_STAGES 5
 mixkv_status mixkv_compress_profiled(const mixkv_params *params, const mixkv_layer_in *in, mixkv_layer_out *out,
                                      int32_t n_layers, void *workspace, size_t workspace_bytes, void *hip_stream,
                                      float *stage_ms);

@@ -23,7 +23,7 @@ POOL = {"none": 0, "avg": 1, "max": 2}
 BUDGET_MODE = {"fixed": 0, "adaptive": 1}
 INTRINSIC = {"none": 0, "vnorm": 1}
 TORCH_DTYPE = {0: torch.float32, 1: torch.bfloat16}
-N_STAGES = 6
+N_STAGES = 5
 
 
 class MixkvParams(C.Structure):

@@ -8,6 +8,9 @@ namespace mixkv {
 
 int stream_chunk_keys(int dtype, int D);
 int max_adaptive_heads();
+bool mixsel_supported(const Shape &s);
+hipError_t launch_mixsel(const Shape &s, bool select, const LayerOutTable &out, char *ws, const Workspace &w,
+                         int64_t unit0, int nunits, hipStream_t st);
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -65,13 +68,12 @@ void carve_workspace(const Shape &s, int64_t units, Workspace *w) {
   const size_t groups = ((size_t)(units / s.units_per_layer) + kLayersPerLaunch - 1) / kLayersPerLaunch;
   w->part_ml = take(groups * per_group * QTR * 8);
   w->part_ksum = take(groups * per_group * s.D * 4);
-  w->brow = take((size_t)units * QTR * 4);
-  w->kbar = take((size_t)units * 2 * s.D * 4);
   w->rbar = take((size_t)units * 4);
-  w->invnorm = take((size_t)units * s.Npad * 4);
-  w->vnorm = take((size_t)units * s.Npad * 4);
-  w->araw = take((size_t)units * s.Npad * 4);
-  w->sdiv = take((size_t)units * s.Npad * 4);
+  // per-key rows; the slack lets 16-byte vector loads of a row's tail run past the last row
+  w->invnorm = take((size_t)units * s.Npad * 4 + 256);
+  w->vnorm = take((size_t)units * s.Npad * 4 + 256);
+  w->araw = take((size_t)units * s.Npad * 4 + 256);
+  w->sdiv = take((size_t)units * s.Npad * 4 + 256);
   w->scores = take((size_t)units * s.N * 4);
   w->total = off;
 }
@@ -170,6 +172,10 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
     std::memset(&ti, 0, sizeof(ti));
     std::memset(&to, 0, sizeof(to));
     const int64_t unit0 = (int64_t)l0 * s.units_per_layer;
+    // One fused kernel mixes the scores and, in fixed-budget mode, selects; scores reach memory
+    // only if somebody reads them (the caller, or the separate selection kernels).
+    const bool fused = (stages & kScore) && mixsel_supported(s);
+    const bool fused_select = fused && (stages & kSelect) && !s.adaptive;
     for (int l = 0; l < nl; ++l) {
       if (in) {
         const mixkv_layer_in &li = in[l0 + l];
@@ -177,7 +183,8 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
       }
       const mixkv_layer_out &lo = out[l0 + l];
       float *scores = lo.scores;
-      if (!scores) scores = reinterpret_cast<float *>(ws + w.scores) + (unit0 + (int64_t)l * s.units_per_layer) * s.N;
+      if (!scores && !fused_select)
+        scores = reinterpret_cast<float *>(ws + w.scores) + (unit0 + (int64_t)l * s.units_per_layer) * s.N;
       to.l[l] = LayerOut{scores, lo.redundancy, lo.indices, lo.counts, lo.offsets, lo.K_out, lo.V_out};
     }
     const int nunits = nl * s.units_per_layer;
@@ -185,13 +192,16 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
       const int grid = stream_grid(s, nunits, num_cus);
       const int64_t slot0 = (int64_t)(l0 / kLayersPerLaunch) * (kMaxStreamGrid + kLayersPerLaunch * s.units_per_layer);
       ok(timed(0, [&] { return launch_stats(s, params->dtype, ti, ws, w, unit0, nunits, grid, slot0, stream); })) &&
-          ok(timed(1, [&] { return launch_finalize(s, to, ws, w, unit0, nunits, grid, slot0, stream); })) &&
-          ok(timed(2, [&] { return launch_attn(s, params->dtype, ti, ws, w, unit0, nunits, grid, stream); })) &&
-          ok(timed(3, [&] { return launch_mix(s, to, ws, w, unit0, nunits, stream); }));
+          ok(timed(1, [&] { return launch_attn(s, params->dtype, ti, to, ws, w, unit0, nunits, grid, slot0, stream); })) &&
+          ok(timed(2, [&] {
+            return fused ? launch_mixsel(s, fused_select, to, ws, w, unit0, nunits, stream)
+                         : launch_mix(s, to, ws, w, unit0, nunits, stream);
+          }));
     }
-    if (result == MIXKV_OK && (stages & kSelect)) ok(timed(4, [&] { return launch_select(s, to, nl, stream); }));
+    if (result == MIXKV_OK && (stages & kSelect) && !fused_select)
+      ok(timed(3, [&] { return launch_select(s, to, nl, stream); }));
     if (result == MIXKV_OK && (stages & kGather))
-      ok(timed(5, [&] { return launch_gather(s, params->dtype, ti, to, nl, stream); }));
+      ok(timed(4, [&] { return launch_gather(s, params->dtype, ti, to, nl, stream); }));
     if (result != MIXKV_OK) break;
   }
   mixkv_status fin = timed.finish();
@@ -238,7 +248,7 @@ mixkv_status mixkv_compress_profiled(const mixkv_params *params, const mixkv_lay
 }
 
 const char *mixkv_stage_name(int32_t stage) {
-  static const char *names[MIXKV_N_STAGES] = {"stats", "finalize", "attn", "mix", "select", "gather"};
+  static const char *names[MIXKV_N_STAGES] = {"stats", "attn", "mix", "select", "gather"};
   return (stage >= 0 && stage < MIXKV_N_STAGES) ? names[stage] : "";
 }
 

@@ -45,8 +45,6 @@ struct Shape {
 struct Workspace {
   size_t part_ml;        // float2 [slots][QT*32]            per-run (max, sum) of each softmax row, log2 domain
   size_t part_ksum;      // float  [slots][D]                per-run partial sums of normalised keys
-  size_t brow;           // float  [units][QT*32]            per-row exponent offset: max + log2(sum * G*W)
-  size_t kbar;           // float  [units][2][D]             mean normalised key, split hi / lo for bf16
   size_t rbar;           // float  [units]
   size_t invnorm;        // float  [units][Npad]             1 / |K_i|
   size_t vnorm;          // float  [units][Npad]             |V_i|
@@ -61,16 +59,13 @@ void carve_workspace(const Shape &s, int64_t units, Workspace *w);
 
 // Kernel launchers (one per pipeline stage).  `unit0` is the first unit of this launch group,
 // `nunits` the number of units it covers (whole layers).
-// `grid` (from stream_grid) is the number of workgroups of the two streaming kernels; finalize
-// needs it to find the runs stats_kernel wrote.
+// `grid` (from stream_grid) is the number of workgroups of the two streaming kernels; `slot0` is the
+// first partial slot of this launch group (each group owns kMaxStreamGrid + its units).
 int stream_grid(const Shape &s, int nunits, int num_cus);
-// `slot0` is the first partial slot of this launch group (each group owns kMaxStreamGrid + its units).
 hipError_t launch_stats(const Shape &s, int dtype, const LayerInTable &in, char *ws, const Workspace &w, int64_t unit0,
                         int nunits, int grid, int64_t slot0, hipStream_t st);
-hipError_t launch_finalize(const Shape &s, const LayerOutTable &out, char *ws, const Workspace &w, int64_t unit0,
-                           int nunits, int grid, int64_t slot0, hipStream_t st);
-hipError_t launch_attn(const Shape &s, int dtype, const LayerInTable &in, char *ws, const Workspace &w,
-                       int64_t unit0, int nunits, int grid, hipStream_t st);
+hipError_t launch_attn(const Shape &s, int dtype, const LayerInTable &in, const LayerOutTable &out, char *ws,
+                       const Workspace &w, int64_t unit0, int nunits, int grid, int64_t slot0, hipStream_t st);
 hipError_t launch_mix(const Shape &s, const LayerOutTable &out, char *ws, const Workspace &w, int64_t unit0,
                       int nunits, hipStream_t st);
 hipError_t launch_select(const Shape &s, const LayerOutTable &out, int nlayers, hipStream_t st);

@@ -1,0 +1,382 @@
+// mixsel_kernel: score mixing and (optionally) the fixed-budget top-B' selection of one unit in a
+// single workgroup, with every per-key quantity held in registers.
+//
+// Thread t owns the EPT consecutive candidates [t*EPT, (t+1)*EPT), so the kept indices come out in
+// ascending order from a plain prefix sum.  The pooled attention needs neighbours, so the raw
+// attention row is staged once in LDS.  The selection is a most-significant-digit radix select on
+// order-preserving integer keys kept in registers; it starts at the first bit in which the keys of
+// the head differ at all, which keeps the first histogram from collapsing into one bin.
+//
+// Paper: Sec. 3.2 Eq. 2 (importance = attention + scaled value norm), Sec. 3.3 (min-max and mean
+// matching of the diversity, Eq. 5 mix), Sec. 3.1 / Algorithm 1 (TopB with B' = B - W).
+#include "mixkv_internal.h"
+#include "mixkv_wave.h"
+
+#ifdef MIXKV_TIMING
+__device__ unsigned long long mixsel_dbg[1024 * 8];
+#define MS_STAMP(i) do { if (threadIdx.x == 0) mixsel_dbg[blockIdx.x * 8 + (i)] = __builtin_readcyclecounter(); } while (0)
+extern "C" int mixsel_debug_read(unsigned long long *host) {
+  return hipMemcpyFromSymbol(host, HIP_SYMBOL(mixsel_dbg), sizeof(mixsel_dbg)) != hipSuccess;
+}
+#else
+#define MS_STAMP(i)
+#endif
+
+namespace mixkv {
+
+constexpr int kMsMaxThreads = 1024, kMsMaxWaves = kMsMaxThreads / 64;
+constexpr int kDigit = 11, kBins = 1 << kDigit;     // radix-select digit
+
+struct MsScratch {
+  float f[kMsMaxWaves][8];
+  float fr[8];
+  uint32_t u[kMsMaxWaves][2];
+  uint32_t ur[2];
+  int i[kMsMaxWaves + 1];
+  int hist[kBins];
+  int bin, krem, cut;
+};
+
+// Block-wide reduction of NS sums, NMIN minima and NMAX maxima at once; every thread gets the
+// results back in place.  Fixed order: lanes in lane order inside a wave, then waves in wave order.
+template <int NW, int NS, int NMIN, int NMAX>
+__device__ __forceinline__ void block_reduce_mixed(float (&v)[NS + NMIN + NMAX], MsScratch &sc) {
+  constexpr int NV = NS + NMIN + NMAX;
+  static_assert(NV <= 8 && NW <= 16, "scratch holds eight values for sixteen waves");
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int k = 0; k < NV; ++k)
+    v[k] = k < NS ? wave_reduce<WSum>(v[k], 0.f)
+                  : (k < NS + NMIN ? wave_reduce<WMin>(v[k], INFINITY) : wave_reduce<WMax>(v[k], -INFINITY));
+  __syncthreads();                       // scratch may still be read from a previous call
+  if (lane == 0)
+#pragma unroll
+    for (int k = 0; k < NV; ++k) sc.f[wave][k] = v[k];
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    // every wave folds the NW partials itself (one row of lanes), so no third barrier is needed
+    const float id = k < NS ? 0.f : (k < NS + NMIN ? INFINITY : -INFINITY);
+    float x = (lane & 15) < NW ? sc.f[lane & 15][k] : id;
+    x = k < NS ? row_scan_incl<WSum>(x, id) : (k < NS + NMIN ? row_scan_incl<WMin>(x, id) : row_scan_incl<WMax>(x, id));
+    v[k] = read_lane(x, 15);
+  }
+}
+
+template <int NW>
+__device__ __forceinline__ void block_minmax_u32(uint32_t &lo, uint32_t &hi, MsScratch &sc) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  lo = wave_reduce<WMin>(lo, 0xffffffffu);
+  hi = wave_reduce<WMax>(hi, 0u);
+  __syncthreads();
+  if (lane == 0) { sc.u[wave][0] = lo; sc.u[wave][1] = hi; }
+  __syncthreads();
+  uint32_t a = (lane & 15) < NW ? sc.u[lane & 15][0] : 0xffffffffu;
+  uint32_t b = (lane & 15) < NW ? sc.u[lane & 15][1] : 0u;
+  lo = read_lane(row_scan_incl<WMin>(a, 0xffffffffu), 15);
+  hi = read_lane(row_scan_incl<WMax>(b, 0u), 15);
+}
+
+// Exclusive prefix sum of one int per thread (thread order); *total receives the block sum.
+__device__ __forceinline__ int read_lane_dyn(int x, int lane_uniform) {
+  return __builtin_amdgcn_readlane(x, __builtin_amdgcn_readfirstlane(lane_uniform));
+}
+
+template <int NW>
+__device__ __forceinline__ int block_scan_excl(int v, MsScratch &sc, int *total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int wtot;
+  const int inc = wave_scan_incl_add(v, &wtot);
+  __syncthreads();
+  if (lane == 0) sc.i[wave] = wtot;
+  __syncthreads();
+  const int x = (lane & 15) < NW ? sc.i[lane & 15] : 0;
+  const int y = row_scan_incl<WSum>(x, 0);              // inclusive over the waves, in every row of lanes
+  *total = read_lane(y, 15);
+  const int before = wave == 0 ? 0 : read_lane_dyn(y, wave - 1);
+  return before + inc - v;
+}
+
+__device__ __forceinline__ uint32_t order_key_u(float x) {
+  uint32_t u = __float_as_uint(x);
+  if (u == 0x80000000u) u = 0;                          // -0 and +0 are the same score
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// One count into a shared histogram bin per lane, with the lanes that share the wave's most common
+// bin (as seen from its first active lane) merged into a single atomic.
+__device__ __forceinline__ void hist_add(int *hist, int bin, bool on) {
+  const unsigned long long act = __ballot(on);
+  if (act == 0) return;
+  const int first = __ffsll((long long)act) - 1;                  // wave-uniform
+  const int b0 = __builtin_amdgcn_readlane(bin, first);
+  const unsigned long long same = __ballot(on && bin == b0);
+  const int lane = threadIdx.x & 63;
+  if (lane == first) atomicAdd(&hist[b0], __popcll(same));
+  if (on && bin != b0) atomicAdd(&hist[bin], 1);
+}
+
+template <int THREADS, int EPT, bool SELECT>
+__global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable out, char *ws, Workspace w,
+                                                           int64_t unit0) {
+  constexpr int NW = THREADS / 64;
+  extern __shared__ float a_s[];                        // [Nc] raw window attention of this head
+  __shared__ MsScratch sc;
+  const int tid = threadIdx.x, ul = blockIdx.x;
+  const int64_t unit = unit0 + ul;
+  const int layer = ul / s.units_per_layer, bh = ul - layer * s.units_per_layer;
+  const LayerOut O = out.l[layer];
+  const float *araw = reinterpret_cast<const float *>(ws + w.araw) + unit * s.Npad;
+  const float *vnorm = reinterpret_cast<const float *>(ws + w.vnorm) + unit * s.Npad;
+  const float *kdot = reinterpret_cast<const float *>(ws + w.sdiv) + unit * s.Npad;
+  const float *invn = reinterpret_cast<const float *>(ws + w.invnorm) + unit * s.Npad;
+  const float r = reinterpret_cast<const float *>(ws + w.rbar)[unit];
+  const int Nc = s.Nc, N = s.N, base = tid * EPT;
+  const bool use_v = s.intrinsic == MIXKV_INTRINSIC_VNORM;
+  const float inv_n = 1.f / (float)Nc;
+
+  MS_STAMP(0);
+  // ---- load: EPT consecutive candidates per thread (the per-unit rows are padded past Nc)
+  float a[EPT], v[EPT], d[EPT];
+#pragma unroll
+  for (int e4 = 0; e4 < EPT; e4 += 4) {
+    const int i = base + e4;
+    float4 ar = make_float4(0.f, 0.f, 0.f, 0.f), vr = ar, kr = ar, nr = ar;
+    if (i < Nc) {
+      ar = *reinterpret_cast<const float4 *>(araw + i);
+      kr = *reinterpret_cast<const float4 *>(kdot + i);
+      nr = *reinterpret_cast<const float4 *>(invn + i);
+      if (use_v) vr = *reinterpret_cast<const float4 *>(vnorm + i);
+    }
+    a[e4] = ar.x; a[e4 + 1] = ar.y; a[e4 + 2] = ar.z; a[e4 + 3] = ar.w;
+    v[e4] = vr.x; v[e4 + 1] = vr.y; v[e4 + 2] = vr.z; v[e4 + 3] = vr.w;
+    d[e4] = -kr.x * nr.x; d[e4 + 1] = -kr.y * nr.y; d[e4 + 2] = -kr.z * nr.z; d[e4 + 3] = -kr.w * nr.w;   // s_div
+  }
+  // The raw attention row goes to LDS with one pad word per 32 so that the strided accesses of
+  // consecutive-range owners spread over the banks.
+  auto slot = [](int i) { return i + (i >> 5); };
+#pragma unroll
+  for (int e = 0; e < EPT; ++e)
+    if (base + e < Nc) a_s[slot(base + e)] = a[e];
+  __syncthreads();
+  MS_STAMP(1);
+
+  // ---- pooled attention (candidates only) and the first round of statistics
+  if (s.pool != MIXKV_POOL_NONE && s.pool_k > 1) {
+    const int hk = s.pool_k >> 1;
+    const bool is_max = s.pool == MIXKV_POOL_MAX;
+    const float fill = is_max ? -INFINITY : 0.f;        // out-of-range taps: ignored by max, zero for avg
+    if (hk <= 3) {
+      // sliding window in registers: own values plus three neighbours on either side
+      float win[EPT + 6];
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        const int il = base - 3 + j, ir = base + EPT + j;
+        win[j] = (il >= 0 && il < Nc) ? a_s[slot(il)] : fill;
+        win[EPT + 3 + j] = (ir < Nc) ? a_s[slot(ir)] : fill;
+      }
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) win[3 + e] = (base + e < Nc) ? a[e] : fill;
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) {
+        float acc = win[3 + e];
+        if (is_max) {
+          if (hk >= 1) acc = fmaxf(acc, fmaxf(win[2 + e], win[4 + e]));
+          if (hk >= 2) acc = fmaxf(acc, fmaxf(win[1 + e], win[5 + e]));
+          if (hk >= 3) acc = fmaxf(acc, fmaxf(win[e], win[6 + e]));
+        } else {
+          // same left-to-right order as a plain loop over the taps
+          acc = 0.f;
+          if (hk >= 3) acc += win[e];
+          if (hk >= 2) acc += win[1 + e];
+          if (hk >= 1) acc += win[2 + e];
+          acc += win[3 + e];
+          if (hk >= 1) acc += win[4 + e];
+          if (hk >= 2) acc += win[5 + e];
+          if (hk >= 3) acc += win[6 + e];
+          acc = acc / (float)s.pool_k;
+        }
+        a[e] = acc;
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) {
+        const int i = base + e;
+        if (i < Nc) {
+          const int lo = max(0, i - hk), hi = min(Nc - 1, i + hk);
+          float acc = a_s[slot(lo)];
+          if (is_max) {
+            for (int j = lo + 1; j <= hi; ++j) acc = fmaxf(acc, a_s[slot(j)]);
+          } else {
+            for (int j = lo + 1; j <= hi; ++j) acc += a_s[slot(j)];
+            acc = acc / (float)s.pool_k;
+          }
+          a[e] = acc;
+        }
+      }
+    }
+  }
+  // One round of statistics over the candidates.  The means of the min-max normalised value norm
+  // and diversity follow from the plain sums: sum((x - min) * c) = (sum(x) - Nc * min) * c, and
+  // mean(s_imp) = mean(s_ex) + f_in * mean(s_in_norm).
+  float st[7] = {0.f, 0.f, 0.f, INFINITY, INFINITY, -INFINITY, -INFINITY};   // sums a, v, d | min v, d | max v, d
+#pragma unroll
+  for (int e = 0; e < EPT; ++e)
+    if (base + e < Nc) {
+      st[0] += a[e]; st[1] += v[e]; st[2] += d[e];
+      st[3] = fminf(st[3], v[e]); st[4] = fminf(st[4], d[e]);
+      st[5] = fmaxf(st[5], v[e]); st[6] = fmaxf(st[6], d[e]);
+    }
+  MS_STAMP(2);
+  block_reduce_mixed<NW, 3, 2, 2>(st, sc);
+  MS_STAMP(3);
+  const float mean_ex = st[0] * inv_n;
+  const float vmin = st[3], dmin = st[4];
+  const float rvden = 1.f / (st[5] - vmin + s.eps), rdden = 1.f / (st[6] - dmin + s.eps);
+  const float mean_in = (st[1] - (float)Nc * vmin) * rvden * inv_n;     // mean of the normalised value norm
+  const float mean_dn = (st[2] - (float)Nc * dmin) * rdden * inv_n;     // mean of the normalised diversity
+  const float f_in = use_v ? mean_ex / (mean_in + s.eps) : 0.f;         // Sec. 3.2: scale VNorm to mean(s_ex)
+  const float mean_imp = use_v ? mean_ex + f_in * mean_in : mean_ex;
+  const float f_div = mean_imp / (mean_dn + s.eps);                      // Sec. 3.3: scale diversity to mean(s_imp)
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    const float imp = use_v ? a[e] + (v[e] - vmin) * rvden * f_in : a[e];          // Eq. 2
+    a[e] = (1.f - r) * imp + r * ((d[e] - dmin) * rdden * f_div);                  // Eq. 5: s_comp
+  }
+
+  if (O.scores) {
+    float *scores = O.scores + (int64_t)bh * N;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e)
+      if (base + e < Nc) scores[base + e] = a[e];
+    for (int i = Nc + tid; i < N; i += THREADS) scores[i] = INFINITY;
+  }
+  if constexpr (!SELECT) return;
+
+  // ---- fixed-budget TopB': the B' candidates with the largest s_comp, ties to the smaller index
+  int32_t *idx = O.indices + (int64_t)bh * s.B;
+  const int Bp = s.Bp;
+  if (Bp > 0) {
+    uint32_t key[EPT];
+    uint32_t kmin = 0xffffffffu, kmax = 0;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      key[e] = order_key_u(a[e]);
+      if (base + e < Nc) { kmin = min(kmin, key[e]); kmax = max(kmax, key[e]); }
+    }
+    block_minmax_u32<NW>(kmin, kmax, sc);
+    MS_STAMP(4);
+    // bits at and above `undecided` are common to all keys; digits of up to kDigit bits from there down
+    int undecided = kmin == kmax ? 0 : 32 - __clz((int)(kmin ^ kmax));
+    uint32_t prefix = undecided >= 32 ? 0u : (kmax >> undecided) << undecided;
+    int k = Bp;
+    while (undecided > 0) {
+      const int wbits = min(kDigit, undecided), shift = undecided - wbits;
+      const uint32_t himask = undecided >= 32 ? 0u : ~0u << undecided;
+      for (int i = tid; i < kBins; i += THREADS) sc.hist[i] = 0;
+      __syncthreads();
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) {
+        const bool on = base + e < Nc && (key[e] & himask) == (prefix & himask);
+        hist_add(sc.hist, (int)((key[e] >> shift) & ((1u << wbits) - 1u)), on);
+      }
+      __syncthreads();
+      // walk the bins from the top: thread t sums bins [kBins - (t+1)*BPT, kBins - t*BPT)
+      constexpr int BPT = (kBins + THREADS - 1) / THREADS;
+      int cnt = 0;
+#pragma unroll
+      for (int j = 0; j < BPT; ++j) {
+        const int bi = kBins - 1 - (tid * BPT + j);
+        cnt += bi >= 0 ? sc.hist[bi] : 0;
+      }
+      int total;
+      const int excl = block_scan_excl<NW>(cnt, sc, &total);
+      if (excl < k && k <= excl + cnt) {
+        int run = excl;
+#pragma unroll
+        for (int j = 0; j < BPT; ++j) {
+          const int bi = kBins - 1 - (tid * BPT + j);
+          const int c = bi >= 0 ? sc.hist[bi] : 0;
+          if (run < k && k <= run + c) { sc.bin = bi; sc.krem = k - run; }
+          run += c;
+        }
+      }
+      __syncthreads();
+      prefix |= (uint32_t)sc.bin << shift;
+      k = sc.krem;
+      undecided = shift;
+      __syncthreads();
+    }
+    MS_STAMP(5);
+    const uint32_t tau = prefix;       // the B'-th largest key; k of the keys equal to it are still needed
+    // one scan carries both counts: keys above tau (low half) and keys equal to tau (high half)
+    int ngt = 0, neq = 0;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      const bool in = base + e < Nc;
+      ngt += (in && key[e] > tau) ? 1 : 0;
+      neq += (in && key[e] == tau) ? 1 : 0;
+    }
+    int total;
+    const int packed = block_scan_excl<NW>(ngt | (neq << 16), sc, &total);
+    int seen = packed >> 16;                          // equal keys at smaller indices
+    int pos = (packed & 0xffff) + min(seen, k);       // kept entries at smaller indices
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      if (base + e < Nc) {
+        bool sel = key[e] > tau;
+        if (key[e] == tau) sel = seen++ < k;
+        if (sel) {
+          if (pos < Bp) idx[pos] = base + e;
+          ++pos;
+        }
+      }
+    }
+  }
+  MS_STAMP(6);
+  for (int wv = tid; wv < s.W; wv += THREADS) idx[Bp + wv] = Nc + wv;
+  if (tid == 0) {
+    const int h = bh % s.hkv, b = bh / s.hkv;
+    O.counts[bh] = s.B;
+    if (O.offsets) {
+      O.offsets[b * (s.hkv + 1) + h] = h * s.B;
+      if (h == s.hkv - 1) O.offsets[b * (s.hkv + 1) + s.hkv] = s.hkv * s.B;
+    }
+  }
+}
+
+// Largest sequence the fused kernel handles: 32 candidates per thread, and the raw attention row
+// must fit in LDS next to the scratch.
+bool mixsel_supported(const Shape &s) { return s.Nc <= kMsMaxThreads * 32 && (size_t)(s.Nc + s.Nc / 32 + 1) * 4 <= 140 * 1024; }
+
+template <int THREADS, int EPT>
+static hipError_t launch_mixsel_e(const Shape &s, bool select, const LayerOutTable &out, char *ws, const Workspace &w,
+                                  int64_t unit0, int nunits, hipStream_t st) {
+  const size_t lds = (size_t)(s.Nc + s.Nc / 32 + 1) * 4;
+  if (select) {
+    auto kern = mixsel_kernel<THREADS, EPT, true>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(nunits), dim3(THREADS), lds, st, s, out, ws, w, unit0);
+  } else {
+    auto kern = mixsel_kernel<THREADS, EPT, false>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(nunits), dim3(THREADS), lds, st, s, out, ws, w, unit0);
+  }
+  return hipGetLastError();
+}
+
+// Mix (and, with `select`, fixed-budget selection) for `nunits` units starting at unit0.  Few
+// waves per workgroup keep the many block-wide steps cheap; long heads get more threads.
+hipError_t launch_mixsel(const Shape &s, bool select, const LayerOutTable &out, char *ws, const Workspace &w,
+                         int64_t unit0, int nunits, hipStream_t st) {
+  const int nc = s.Nc;
+  if (nc <= 256 * 8) return launch_mixsel_e<256, 8>(s, select, out, ws, w, unit0, nunits, st);
+  if (nc <= 512 * 8) return launch_mixsel_e<512, 8>(s, select, out, ws, w, unit0, nunits, st);
+  if (nc <= 1024 * 8) return launch_mixsel_e<1024, 8>(s, select, out, ws, w, unit0, nunits, st);
+  if (nc <= 1024 * 16) return launch_mixsel_e<1024, 16>(s, select, out, ws, w, unit0, nunits, st);
+  return launch_mixsel_e<1024, 32>(s, select, out, ws, w, unit0, nunits, st);
+}
+
+}  // namespace mixkv

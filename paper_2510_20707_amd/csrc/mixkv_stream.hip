@@ -20,6 +20,7 @@
 // give the weight already divided by the row sum and by the number of rows
 // (paper Sec. 3.2, extrinsic importance: mean over the window queries of the attention weights).
 #include "mixkv_internal.h"
+#include "mixkv_wave.h"
 
 #ifdef MIXKV_TIMING
 // Developer aid, compiled out by default: cycle totals of wave 0 of every workgroup of attn_kernel.
@@ -131,26 +132,29 @@ __device__ __forceinline__ int tile_swz(int r) {
   return PPR == 8 ? (r >> 1) & 7 : r & 15;
 }
 
-// Issue the direct-to-LDS loads of one chunk of KT key tiles.  Load j covers slots [64j, 64j+64)
-// of the chunk image; lane i fetches the piece that belongs in slot 64j + i.  Waves take loads
-// round-robin.  The address is a wave-uniform 64-bit base plus a 32-bit lane offset.  In the last
-// chunk of a sequence, keys past N-1 re-read key N-1 (their results are masked or discarded).
+// Issue the direct-to-LDS loads of key tile k of the chunk that starts at key cbase.  Load j covers
+// slots [64j, 64j+64) of the tile image; lane i fetches the piece that belongs in slot 64j + i.
+// Waves take loads round-robin.  The address is a wave-uniform 64-bit base plus a 32-bit lane
+// offset.  In the last chunk of a sequence, keys past N-1 re-read key N-1 (their results are
+// masked or discarded).
 template <int DT, int D, int WAVES>
-__device__ __forceinline__ void fetch_chunk(const char *Kb, int64_t row_bytes, int cbase, int N, uint4 *buf, int wave,
-                                            int lane) {
-  constexpr int PPR = D * Tr<DT>::EB / 16, KT = chunk_tiles(DT, D), CH = KT * 32, LOADS = KT * 32 * PPR / 64;
-  constexpr int RPL = 64 / PPR > 0 ? 64 / PPR : 1;       // rows per load (PPR <= 32)
+__device__ __forceinline__ void fetch_tile(const char *Kb, int64_t row_bytes, int cbase, int k, int N, uint4 *buf,
+                                           int wave, int lane) {
+  constexpr int PPR = D * Tr<DT>::EB / 16, LOADS = 32 * PPR / 64;      // loads per tile
+  constexpr int RPL = 64 / PPR > 0 ? 64 / PPR : 1;                      // rows per load (PPR <= 32)
   static_assert(PPR <= 64 && 64 % PPR == 0, "row pieces must divide a load");
   const int lrow = lane / PPR, lq = lane % PPR;
   const uint32_t rb = (uint32_t)row_bytes;
-  if (cbase + CH <= N) {
+  const int tb = cbase + k * 32;
+  uint4 *tile = buf + k * 32 * PPR;
+  if (tb + 32 <= N) {
 #pragma unroll
     for (int jj = 0; jj < (LOADS + WAVES - 1) / WAVES; ++jj) {
       const int j = jj * WAVES + wave;
       if (LOADS % WAVES != 0 && j >= LOADS) break;
-      const char *base = Kb + (int64_t)(cbase + j * RPL) * row_bytes;             // wave-uniform
-      const uint32_t off = (uint32_t)lrow * rb + (uint32_t)((lq ^ tile_swz<DT, D>((j * RPL + lrow) & 31)) * 16);
-      __builtin_amdgcn_global_load_lds((glb_void_t *)(base + off), (lds_void_t *)(buf + j * 64), 16, 0, 0);
+      const char *base = Kb + (int64_t)(tb + j * RPL) * row_bytes;               // wave-uniform
+      const uint32_t off = (uint32_t)lrow * rb + (uint32_t)((lq ^ tile_swz<DT, D>(j * RPL + lrow)) * 16);
+      __builtin_amdgcn_global_load_lds((glb_void_t *)(base + off), (lds_void_t *)(tile + j * 64), 16, 0, 0);
     }
   } else {
 #pragma unroll
@@ -158,11 +162,18 @@ __device__ __forceinline__ void fetch_chunk(const char *Kb, int64_t row_bytes, i
       const int j = jj * WAVES + wave;
       if (LOADS % WAVES != 0 && j >= LOADS) break;
       const int row = j * RPL + lrow;
-      const int krow = min(cbase + row, N - 1);
-      const char *src = Kb + (int64_t)krow * row_bytes + (lq ^ tile_swz<DT, D>(row & 31)) * 16;
-      __builtin_amdgcn_global_load_lds((glb_void_t *)src, (lds_void_t *)(buf + j * 64), 16, 0, 0);
+      const int krow = min(tb + row, N - 1);
+      const char *src = Kb + (int64_t)krow * row_bytes + (lq ^ tile_swz<DT, D>(row)) * 16;
+      __builtin_amdgcn_global_load_lds((glb_void_t *)src, (lds_void_t *)(tile + j * 64), 16, 0, 0);
     }
   }
+}
+
+template <int DT, int D, int WAVES>
+__device__ __forceinline__ void fetch_chunk(const char *Kb, int64_t row_bytes, int cbase, int N, uint4 *buf, int wave,
+                                            int lane) {
+#pragma unroll
+  for (int k = 0; k < chunk_tiles(DT, D); ++k) fetch_tile<DT, D, WAVES>(Kb, row_bytes, cbase, k, N, buf, wave, lane);
 }
 
 // Fragment c of key tile k for lane (row l32, half): piece 2c + half of row l32.
@@ -179,7 +190,7 @@ __device__ __forceinline__ uint4 read_key_frag(const uint4 *kb, int k, int c, in
 //   * 1/|K_i| and the partial sum of the normalised keys (paper Sec. 3.2 diversity metrics,
 //     Sec. 3.3 Eq. 3-4: only the sum of normalised keys is needed, never the T x T matrix);
 //   * |V_i| (Sec. 3.2, VNorm intrinsic importance).
-// Per-run partials go to the workspace; finalize_kernel folds them.
+// Per-run partials go to the workspace; attn_kernel folds them at the start of its runs.
 // ------------------------------------------------------------------------------------------------
 template <int DT, int D, int WAVES, int TQ>
 __global__ __launch_bounds__(WAVES * 64, 2) void stats_kernel(Shape s, LayerInTable in, char *ws, Workspace w,
@@ -245,17 +256,20 @@ __global__ __launch_bounds__(WAVES * 64, 2) void stats_kernel(Shape s, LayerInTa
       const int cbase = (c0 + it) * CH;
       __builtin_amdgcn_s_waitcnt(0);                   // this wave's share of the chunk has landed
       __syncthreads();                                 // ... and everybody else's; the other buffer is free
-      if (it + 1 < nit) fetch_chunk<DT, D, WAVES>(Kb, row_bytes, cbase + CH, N, kn, wave, lane);
+      const bool has_next = it + 1 < nit;
 
-      // |V_i| rides along: the rows of key tile k are fetched one tile ahead of their use
-      Frag vb[VPT];
+      // |V_i| rides along: the rows of key tile k are requested one tile ahead of their use, and
+      // always *before* the slice of the next chunk's keys issued in the same tile step.  The
+      // memory counter retires in order, so waiting for value rows only ever waits for key loads
+      // that are at least one tile step old.
+      Frag vb[VPT], vn[VPT];                           // rows in use / rows in flight
       auto v_issue = [&](int k) {
 #pragma unroll
         for (int i = 0; i < VPT; ++i) {
           const int p = i * NT + tid, key = cbase + k * 32 + p / PPR;
           const bool on = p < 32 * PPR && key < Nc;
-          uint4 v = *reinterpret_cast<const uint4 *>(Vb + (on ? key : 0) * row_bytes + (p % PPR) * 16);
-          vb[i].q = on ? v : make_uint4(0, 0, 0, 0);
+          uint4 v = *reinterpret_cast<const uint4 *>(Vb + (int64_t)(on ? key : 0) * row_bytes + (p % PPR) * 16);
+          vn[i].q = on ? v : make_uint4(0, 0, 0, 0);
         }
       };
       auto v_consume = [&](int k) {
@@ -268,9 +282,10 @@ __global__ __launch_bounds__(WAVES * 64, 2) void stats_kernel(Shape s, LayerInTa
             float x = frag_elem<DT>(vb[i], e);
             ss = fmaf(x, x, ss);
           }
-#pragma unroll
-          for (int sft = PPR / 2; sft >= 1; sft >>= 1) ss += __shfl_xor(ss, sft);
-          if (p % PPR == 0 && p < 32 * PPR && key < Nc) vnorm[key] = sqrtf(ss);
+          // PPR consecutive lanes hold one row: fold them with row shifts, total in the last lane
+          ss = row_scan_incl<WSum>(ss, 0.f);
+          if (PPR == 32) ss += __shfl_up(ss, 16);
+          if (p % PPR == PPR - 1 && p < 32 * PPR && key < Nc) vnorm[key] = sqrtf(ss);
         }
       };
       if (use_v) v_issue(0);
@@ -278,6 +293,14 @@ __global__ __launch_bounds__(WAVES * 64, 2) void stats_kernel(Shape s, LayerInTa
 #pragma unroll 1
       for (int k = 0; k < KT; ++k) {
         const int tb = cbase + k * 32;
+        if (use_v) {
+#pragma unroll
+          for (int i = 0; i < VPT; ++i) vb[i] = vn[i];
+          if (k + 1 < KT) v_issue(k + 1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (has_next) fetch_tile<DT, D, WAVES>(Kb, row_bytes, cbase + CH, k, N, kn, wave, lane);
+        __builtin_amdgcn_sched_barrier(0);
         if (tb < N) {
           Frag kf[NCHK];
 #pragma unroll
@@ -363,10 +386,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void stats_kernel(Shape s, LayerInTa
             }
           }
         }
-        if (use_v) {
-          v_consume(k);
-          if (k + 1 < KT) v_issue(k + 1);
-        }
+        if (use_v) v_consume(k);
       }
     };
     for (int it = 0; it < nit; it += 2) {
@@ -394,72 +414,6 @@ __global__ __launch_bounds__(WAVES * 64, 2) void stats_kernel(Shape s, LayerInTa
 }
 
 // ------------------------------------------------------------------------------------------------
-// finalize_kernel: one workgroup per unit folds the per-run partials of stats_kernel, in run
-// order, into the per-row exponent offsets b_r = max_r + log2(sum_r * G*W), the mean normalised
-// key and the redundancy r (paper Sec. 3.3, Eq. 3-4).  It recomputes the work split of
-// stats_kernel (grid size G over T items) to find the runs of its unit.  A kernel boundary orders
-// it after every workgroup of stats_kernel, so no fences or atomics are needed.
-// ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void finalize_kernel(Shape s, LayerOutTable out, char *ws, Workspace w,
-                                                      int64_t unit0, int nunits, int G, int64_t slot0) {
-  __shared__ double red_s[4];
-  __shared__ int g_lo_s, g_hi_s;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, NT = 256;
-  const int ul = blockIdx.x;
-  const int64_t unit = unit0 + ul;
-  const UnitCoord uc = unit_coord(s, ul);
-  const int QTR = s.QT * 32, D = s.D, N = s.N;
-  const int64_t T = (int64_t)nunits * s.nchunks, first = (int64_t)ul * s.nchunks, last = first + s.nchunks;
-  // The workgroups g_lo..g_hi of stats_kernel are those whose item range meets [first, last);
-  // each wrote one partial for this unit, at slot g + ul.
-  if (tid == 0) {
-    int64_t g = first * G / T;
-    while (g > 0 && wg_first_item(g, G, T) > first) --g;
-    while (wg_first_item(g + 1, G, T) <= first) ++g;
-    g_lo_s = (int)g;
-    while (g + 1 < G && wg_first_item(g + 1, G, T) < last) ++g;
-    g_hi_s = (int)g;
-  }
-  __syncthreads();
-  const int g_lo = g_lo_s, g_hi = g_hi_s;
-  const float2 *all_ml = reinterpret_cast<const float2 *>(ws + w.part_ml) + (slot0 + ul) * QTR;
-  float *brow = reinterpret_cast<float *>(ws + w.brow) + unit * QTR;
-  for (int r = tid; r < QTR; r += NT) {
-    float m = -INFINITY, l = 0.f;
-    for (int g = g_lo; g <= g_hi; ++g) {
-      if (wg_first_item(g + 1, G, T) <= wg_first_item(g, G, T)) continue;     // workgroup without items
-      float2 p = all_ml[(int64_t)g * QTR + r];
-      ml_merge(m, l, p.x, p.y);
-    }
-    brow[r] = (r < s.GW) ? m + log2f(l) + log2f((float)s.GW) : INFINITY;
-  }
-  const float *all_ks = reinterpret_cast<const float *>(ws + w.part_ksum) + (slot0 + ul) * D;
-  float *kbar = reinterpret_cast<float *>(ws + w.kbar) + unit * D;
-  double sq = 0.0;
-  for (int d = tid; d < D; d += NT) {
-    float a = 0.f;
-    for (int g = g_lo; g <= g_hi; ++g) {
-      if (wg_first_item(g + 1, G, T) <= wg_first_item(g, G, T)) continue;
-      a += all_ks[(int64_t)g * D + d];
-    }
-    kbar[d] = a / (float)N;
-    sq += (double)a * (double)a;
-  }
-#pragma unroll
-  for (int sft = 32; sft >= 1; sft >>= 1) sq += __shfl_xor(sq, sft);
-  if (lane == 0) red_s[wave] = sq;
-  __syncthreads();
-  if (tid == 0) {
-    double tot = red_s[0] + red_s[1] + red_s[2] + red_s[3];
-    // Eq. 4: (T^2 |Kbar|^2 - T) / (T (T - 1)) with T^2 |Kbar|^2 = |sum of normalised keys|^2
-    float r = (float)((tot - (double)N) / ((double)N * (double)(N - 1)));
-    reinterpret_cast<float *>(ws + w.rbar)[unit] = r;
-    float *red_out = out.l[uc.layer].redundancy;
-    if (red_out) red_out[uc.b * s.hkv + uc.h] = r;
-  }
-}
-
-// ------------------------------------------------------------------------------------------------
 // attn_kernel: second pass over K.
 //   a_i    = (1 / (G*W)) * sum over window rows of softmax weights on key i   (Sec. 3.2, extrinsic)
 //   kdot_i = K_i . Kbar; the mix kernel turns it into -(K_i . Kbar) / |K_i|   (Sec. 3.2, diversity)
@@ -468,10 +422,16 @@ __global__ __launch_bounds__(256) void finalize_kernel(Shape s, LayerOutTable ou
 // two more "query" rows (hi + lo bf16 halves, so the dot keeps fp32 accuracy).  When the padded
 // query block has a spare tile they sit in its rows 0 and 1 and cost nothing; otherwise every wave
 // applies a separate mean-key tile to every WAVES-th key tile.
+//
+// At the start of a run the workgroup folds the per-run partials that stats_kernel (grid G1) left
+// for its unit, in run order: per-row exponent offsets b_r = max_r + log2(sum_r * G*W), the mean
+// normalised key, and - in the workgroup that owns the unit's first chunk - the redundancy r
+// (paper Sec. 3.3, Eq. 3-4).  The kernel boundary orders this after all of stats_kernel.
 // ------------------------------------------------------------------------------------------------
 template <int DT, int D, int WAVES, int TQ>
-__global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTable in, char *ws, Workspace w,
-                                                            int64_t unit0, int nunits) {
+__global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTable in, LayerOutTable out, char *ws,
+                                                            Workspace w, int64_t unit0, int nunits, int G1,
+                                                            int64_t slot0) {
   constexpr int EB = Tr<DT>::EB, EPC = Tr<DT>::EPC, NCHK = D / (2 * EPC);
   constexpr int NT = WAVES * 64, KT = chunk_tiles(DT, D), CH = KT * 32, FRAGS = KT * NCHK;
   __shared__ uint4 kbuf_a[FRAGS * 64], kbuf_b[FRAGS * 64];   // separate objects, see stats_kernel
@@ -479,6 +439,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
   __shared__ float cs_s[2 * WAVES * CH];                     // [2][WAVES][CH] partial column sums
   __shared__ float nb_s[WAVES * TQ * 32];                    // -b_r per query row (-inf rows give weight 0)
   __shared__ int lim_s[WAVES * TQ * 32];                     // last key each query row attends to
+  __shared__ float kbar_f[D];                                // mean normalised key
+  __shared__ double red_s[WAVES];
+  __shared__ int g_lo_s, g_hi_s;
 
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps its address math scalar
@@ -508,19 +471,78 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
     const int64_t row_bytes = L.sn * EB;
     float *araw = reinterpret_cast<float *>(ws + w.araw) + unit * s.Npad;
     float *kdot = reinterpret_cast<float *>(ws + w.sdiv) + unit * s.Npad;   // K_i . Kbar, not yet normalised
-    const float *brow = reinterpret_cast<const float *>(ws + w.brow) + unit * QTR;
-    const float *kbar = reinterpret_cast<const float *>(ws + w.kbar) + unit * D;
 
     TSTAMP(p0);
     __syncthreads();                                   // the previous run is done with LDS
     fetch_chunk<DT, D, WAVES>(Kb, row_bytes, c0 * CH, N, kbuf_a, wave, lane);
     TSTAMP(p1);
 
+    // ---- fold the partials of stats_kernel for this unit.  Workgroup g of its grid owned the items
+    // [g*T1/G1, (g+1)*T1/G1) and wrote one partial per unit it touched, at slot g + unit_local.
+    if (tid == 0) {
+      const int64_t T1 = (int64_t)nunits * s.nchunks, first = (int64_t)ul * s.nchunks, last = first + s.nchunks;
+      int64_t g = first * G1 / T1;
+      while (g > 0 && wg_first_item(g, G1, T1) > first) --g;
+      while (wg_first_item(g + 1, G1, T1) <= first) ++g;
+      g_lo_s = (int)g;
+      while (g + 1 < G1 && wg_first_item(g + 1, G1, T1) < last) ++g;
+      g_hi_s = (int)g;
+    }
+    __syncthreads();
+    {
+      const int g_lo = g_lo_s, g_hi = g_hi_s;
+      const float2 *all_ml = reinterpret_cast<const float2 *>(ws + w.part_ml) + (slot0 + ul) * QTR;
+      for (int r = tid; r < WAVES * TQ * 32; r += NT) {
+        float b = INFINITY;                            // rows past G*W: weight 0
+        if (r < s.GW) {
+          float m = -INFINITY, l = 0.f;
+          for (int g0 = g_lo; g0 <= g_hi; g0 += 4) {   // batches of four independent loads
+            float2 p[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) p[j] = (g0 + j <= g_hi) ? all_ml[(int64_t)(g0 + j) * QTR + r] : make_float2(-INFINITY, 0.f);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) ml_merge(m, l, p[j].x, p[j].y);
+          }
+          b = m + log2f(l) + log2f((float)s.GW);
+        }
+        nb_s[r] = -b;
+      }
+      const float *all_ks = reinterpret_cast<const float *>(ws + w.part_ksum) + (slot0 + ul) * D;
+      double sq = 0.0;
+      for (int d = tid; d < D; d += NT) {
+        float a = 0.f;
+        for (int g0 = g_lo; g0 <= g_hi; g0 += 4) {
+          float p[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) p[j] = (g0 + j <= g_hi) ? all_ks[(int64_t)(g0 + j) * D + d] : 0.f;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) a += p[j];
+        }
+        kbar_f[d] = a / (float)N;
+        sq += (double)a * (double)a;
+      }
+      if (c0 == 0) {                                   // one workgroup per unit publishes r
+#pragma unroll
+        for (int sft = 32; sft >= 1; sft >>= 1) sq += __shfl_xor(sq, sft);
+        if (lane == 0) red_s[wave] = sq;
+      }
+    }
+    __syncthreads();                                   // kbar_f, nb_s, red_s visible
+    if (c0 == 0 && tid == 0) {
+      double tot = 0.0;
+      for (int wv = 0; wv < WAVES; ++wv) tot += red_s[wv];
+      // Eq. 4: (T^2 |Kbar|^2 - T) / (T (T - 1)) with T^2 |Kbar|^2 = |sum of normalised keys|^2
+      const float r = (float)((tot - (double)N) / ((double)N * (double)(N - 1)));
+      reinterpret_cast<float *>(ws + w.rbar)[unit] = r;
+      float *red_out = out.l[uc.layer].redundancy;
+      if (red_out) red_out[uc.b * s.hkv + uc.h] = r;
+    }
+
     // The mean key as two rows of 16-byte pieces: row 0 carries the mean key (its bf16 head), row 1
     // the bf16 remainder (zero for f32).  Piece (c, half) of row r sits at kbar_s[(c * 2 + half) * 2 + r].
     for (int p = tid; p < NCHK * 4; p += NT) {
       const int row = p & 1, hf = (p >> 1) & 1, c = p >> 2;
-      const float *src = kbar + (2 * c + hf) * EPC;
+      const float *src = kbar_f + (2 * c + hf) * EPC;
       Frag f;
       f.q = make_uint4(0, 0, 0, 0);
       if constexpr (DT == MIXKV_BF16) {
@@ -537,7 +559,6 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
       }
       kbar_s[p] = f.q;
     }
-    for (int r = tid; r < WAVES * TQ * 32; r += NT) nb_s[r] = (r < QTR) ? -brow[r] : -INFINITY;
     TSTAMP(p2);
     __syncthreads();                                   // kbar_s visible
     TSTAMP(p3);
@@ -578,7 +599,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
       TSTAMP(t1);
       __syncthreads();
       TSTAMP(t2);
-      if (it + 1 < nit) fetch_chunk<DT, D, WAVES>(Kb, row_bytes, cbase + CH, N, kn, wave, lane);
+      const bool has_next = it + 1 < nit;
       if (it > 0) flush_colsums(c0 + it - 1, (it - 1) & 1);
       float *cs = cs_s + ((it & 1) * WAVES + wave) * CH;
       TSTAMP(t3);
@@ -590,6 +611,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
 #pragma unroll 1
       for (int k = 0; k < KT; ++k) {
         const int tb = cbase + k * 32;
+        // the next chunk streams in one tile per tile step, so its loads never queue up
+        if (has_next) fetch_tile<DT, D, WAVES>(Kb, row_bytes, cbase + CH, k, N, kn, wave, lane);
+        __builtin_amdgcn_sched_barrier(0);
         f32x16 acc[TQ];
 #pragma unroll
         for (int q = 0; q < TQ; ++q)
@@ -694,10 +718,10 @@ static hipError_t launch_stats_c(const Shape &s, const LayerInTable &in, char *w
 }
 
 template <int DT, int D, int WAVES, int TQ>
-static hipError_t launch_attn_c(const Shape &s, const LayerInTable &in, char *ws, const Workspace &w, int64_t unit0,
-                                int nunits, int grid, hipStream_t st) {
+static hipError_t launch_attn_c(const Shape &s, const LayerInTable &in, const LayerOutTable &out, char *ws,
+                                const Workspace &w, int64_t unit0, int nunits, int grid, int64_t slot0, hipStream_t st) {
   auto kern = attn_kernel<DT, D, WAVES, TQ>;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES * 64), 0, st, s, in, ws, w, unit0, nunits);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES * 64), 0, st, s, in, out, ws, w, unit0, nunits, grid, slot0);
   return hipGetLastError();
 }
 
@@ -712,13 +736,13 @@ static hipError_t launch_stats_t(const Shape &s, const LayerInTable &in, char *w
 }
 
 template <int DT, int D>
-static hipError_t launch_attn_t(const Shape &s, const LayerInTable &in, char *ws, const Workspace &w, int64_t unit0,
-                                int nunits, int grid, hipStream_t st) {
+static hipError_t launch_attn_t(const Shape &s, const LayerInTable &in, const LayerOutTable &out, char *ws,
+                                const Workspace &w, int64_t unit0, int nunits, int grid, int64_t slot0, hipStream_t st) {
   int waves, tq;
   stream_config(s.QT, &waves, &tq);
-  if (waves == 4 && tq == 1) return launch_attn_c<DT, D, 4, 1>(s, in, ws, w, unit0, nunits, grid, st);
-  if (waves == 4) return launch_attn_c<DT, D, 4, 2>(s, in, ws, w, unit0, nunits, grid, st);
-  return launch_attn_c<DT, D, 8, 2>(s, in, ws, w, unit0, nunits, grid, st);
+  if (waves == 4 && tq == 1) return launch_attn_c<DT, D, 4, 1>(s, in, out, ws, w, unit0, nunits, grid, slot0, st);
+  if (waves == 4) return launch_attn_c<DT, D, 4, 2>(s, in, out, ws, w, unit0, nunits, grid, slot0, st);
+  return launch_attn_c<DT, D, 8, 2>(s, in, out, ws, w, unit0, nunits, grid, slot0, st);
 }
 
 hipError_t launch_stats(const Shape &s, int dtype, const LayerInTable &in, char *ws, const Workspace &w, int64_t unit0,
@@ -731,20 +755,16 @@ hipError_t launch_stats(const Shape &s, int dtype, const LayerInTable &in, char 
   return launch_stats_t<MIXKV_F32, 64>(s, in, ws, w, unit0, nunits, grid, slot0, st);
 }
 
-hipError_t launch_finalize(const Shape &s, const LayerOutTable &out, char *ws, const Workspace &w, int64_t unit0,
-                           int nunits, int grid, int64_t slot0, hipStream_t st) {
-  hipLaunchKernelGGL(finalize_kernel, dim3(nunits), dim3(256), 0, st, s, out, ws, w, unit0, nunits, grid, slot0);
-  return hipGetLastError();
-}
-
-hipError_t launch_attn(const Shape &s, int dtype, const LayerInTable &in, char *ws, const Workspace &w, int64_t unit0,
-                       int nunits, int grid, hipStream_t st) {
+// `grid` must be the grid stats_kernel ran with: both kernels split the same items the same way,
+// and attn_kernel uses it to find the partials of its units.
+hipError_t launch_attn(const Shape &s, int dtype, const LayerInTable &in, const LayerOutTable &out, char *ws,
+                       const Workspace &w, int64_t unit0, int nunits, int grid, int64_t slot0, hipStream_t st) {
   if (dtype == MIXKV_BF16) {
-    if (s.D == 128) return launch_attn_t<MIXKV_BF16, 128>(s, in, ws, w, unit0, nunits, grid, st);
-    return launch_attn_t<MIXKV_BF16, 64>(s, in, ws, w, unit0, nunits, grid, st);
+    if (s.D == 128) return launch_attn_t<MIXKV_BF16, 128>(s, in, out, ws, w, unit0, nunits, grid, slot0, st);
+    return launch_attn_t<MIXKV_BF16, 64>(s, in, out, ws, w, unit0, nunits, grid, slot0, st);
   }
-  if (s.D == 128) return launch_attn_t<MIXKV_F32, 128>(s, in, ws, w, unit0, nunits, grid, st);
-  return launch_attn_t<MIXKV_F32, 64>(s, in, ws, w, unit0, nunits, grid, st);
+  if (s.D == 128) return launch_attn_t<MIXKV_F32, 128>(s, in, out, ws, w, unit0, nunits, grid, slot0, st);
+  return launch_attn_t<MIXKV_F32, 64>(s, in, out, ws, w, unit0, nunits, grid, slot0, st);
 }
 
 }  // namespace mixkv
