@@ -282,10 +282,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void stats_kernel(Shape s, LayerInTa
             float x = frag_elem<DT>(vb[i], e);
             ss = fmaf(x, x, ss);
           }
-          // PPR consecutive lanes hold one row: fold them with row shifts, total in the last lane
-          ss = row_scan_incl<WSum>(ss, 0.f);
-          if (PPR == 32) ss += __shfl_up(ss, 16);
-          if (p % PPR == PPR - 1 && p < 32 * PPR && key < Nc) vnorm[key] = sqrtf(ss);
+          ss = seg_sum<PPR>(ss);                       // PPR consecutive lanes hold one row
+          if (p % PPR == 0 && p < 32 * PPR && key < Nc) vnorm[key] = sqrtf(ss);
         }
       };
       if (use_v) v_issue(0);
@@ -612,7 +610,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
       for (int k = 0; k < KT; ++k) {
         const int tb = cbase + k * 32;
         // the next chunk streams in one tile per tile step, so its loads never queue up
+#ifndef MIXKV_NODMA   // developer switch: time the arithmetic alone (results are then meaningless)
         if (has_next) fetch_tile<DT, D, WAVES>(Kb, row_bytes, cbase + CH, k, N, kn, wave, lane);
+#endif
         __builtin_amdgcn_sched_barrier(0);
         f32x16 acc[TQ];
 #pragma unroll
@@ -674,9 +674,84 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
       TSTAMP(t4);
       TACC(3, t3, t4);
     };
+    // Fast path for chunks that no row has to mask (everything before the window): the work is cut
+    // into blocks (key tile k, query tile q); the MFMA chain of block j+1 is issued interleaved with
+    // the exp2/sum arithmetic on the finished block j, so the matrix core and the vector ALU of the
+    // SIMD run at the same time.  Two accumulators alternate; the fragments of the next key tile
+    // replace the current ones as soon as the tile's last chain has consumed them.
+    auto do_chunk_fast = [&](int it, const uint4 *kb, uint4 *kn) {
+      constexpr int NB = KT * TQ;
+      const int cbase = (c0 + it) * CH;
+      __builtin_amdgcn_s_waitcnt(0);
+      __syncthreads();
+      const bool has_next = it + 1 < nit;
+      if (it > 0) flush_colsums(c0 + it - 1, (it - 1) & 1);
+      float *cs = cs_s + ((it & 1) * WAVES + wave) * CH;
+
+      Frag kf[NCHK];
+#pragma unroll
+      for (int c = 0; c < NCHK; ++c) kf[c].q = read_key_frag<DT, D>(kb, 0, c, l32, half);
+      f32x16 acc[2];
+      auto chain = [&](int j) {                         // MFMA chain of block j, and the fragment hand-over
+        const int k = j / TQ, q = j % TQ;
+        f32x16 a;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) a[i] = 0.f;
+#pragma unroll
+        for (int c = 0; c < NCHK; ++c) {
+          a = mma<DT>(qf[q][c], kf[c], a);
+          if (q == TQ - 1 && k + 1 < KT) kf[c].q = read_key_frag<DT, D>(kb, k + 1, c, l32, half);
+        }
+        acc[j & 1] = a;
+      };
+      chain(0);
+      float colsum = 0.f, kdv[KT];
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        const int k = j / TQ, q = j % TQ;
+        if (q == 0) {
+#ifndef MIXKV_NODMA
+          if (has_next) fetch_tile<DT, D, WAVES>(Kb, row_bytes, cbase + CH, k, N, kn, wave, lane);
+#endif
+          colsum = 0.f;
+        }
+        // block j is complete: its mean-key rows (0 and 1 of the spare tile, half 0) first
+        if (q == kb_q) kdv[k] = acc[j & 1][0] + acc[j & 1][1];
+        if (j + 1 < NB) chain(j + 1);
+#pragma unroll
+        for (int k4 = 0; k4 < 4; ++k4) {
+          const float4 nb = *reinterpret_cast<const float4 *>(&nb_s[(wave * TQ + q) * 32 + 8 * k4 + 4 * half]);
+          const f32x16 &a = acc[j & 1];
+          colsum += fast_exp2(fmaf(a[4 * k4 + 0], c2, nb.x)) + fast_exp2(fmaf(a[4 * k4 + 1], c2, nb.y)) +
+                    fast_exp2(fmaf(a[4 * k4 + 2], c2, nb.z)) + fast_exp2(fmaf(a[4 * k4 + 3], c2, nb.w));
+        }
+        if (j + 1 < NB) {
+#pragma unroll
+          for (int c = 0; c < NCHK; ++c) {               // one MFMA, then its share of the vector work
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 48 / NCHK, 0);
+          }
+        }
+        if (q == TQ - 1) {
+          colsum += __shfl_xor(colsum, 32);
+          if (half == 0) cs[k * 32 + l32] = colsum;
+        }
+      }
+      if (wave == kb_wave && half == 0) {
+#pragma unroll
+        for (int k = 0; k < KT; ++k) kdot[cbase + k * 32 + l32] = kdv[k];
+      }
+    };
+
     for (int it = 0; it < nit; it += 2) {
-      do_chunk(it, kbuf_a, kbuf_b);
-      if (it + 1 < nit) do_chunk(it + 1, kbuf_b, kbuf_a);
+      // a chunk is "free" when even its last key is visible to every row and the mean key rides
+      // in a spare tile; the general path handles the rest
+      const bool free_a = spare && (c0 + it + 1) * CH - 1 <= free_limit;
+      if (free_a) do_chunk_fast(it, kbuf_a, kbuf_b); else do_chunk(it, kbuf_a, kbuf_b);
+      if (it + 1 < nit) {
+        const bool free_b = spare && (c0 + it + 2) * CH - 1 <= free_limit;
+        if (free_b) do_chunk_fast(it + 1, kbuf_b, kbuf_a); else do_chunk(it + 1, kbuf_b, kbuf_a);
+      }
     }
     __syncthreads();
     flush_colsums(c0 + nit - 1, (nit - 1) & 1);

@@ -51,6 +51,19 @@ __device__ __forceinline__ T wave_reduce(T x, T id) {
 template <class Op, class T>
 __device__ __forceinline__ T row_reduce_to_lane15(T x, T id) { return row_scan_incl<Op>(x, id); }
 
+// Sum over aligned segments of SEG consecutive lanes (SEG = 8, 16 or 32); every lane of a
+// segment receives its total.  Butterfly of DPP lane permutations, so the order is fixed.
+template <int SEG>
+__device__ __forceinline__ float seg_sum(float x) {
+  static_assert(SEG == 8 || SEG == 16 || SEG == 32, "segment width");
+  x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xf, 0xf, true));    // quad_perm [1,0,3,2]
+  x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xf, 0xf, true));    // quad_perm [2,3,0,1]
+  x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x141, 0xf, 0xf, true));   // row_half_mirror
+  if (SEG >= 16) x += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x140, 0xf, 0xf, true));  // row_mirror
+  if (SEG >= 32) x += __shfl_xor(x, 16);
+  return x;
+}
+
 // Inclusive prefix sum over the 64 lanes of a wave; *total receives the wave sum.
 __device__ __forceinline__ int wave_scan_incl_add(int x, int *total) {
   x = row_scan_incl<WSum>(x, 0);
