@@ -87,6 +87,9 @@ def main():
     ap.add_argument("--copies", type=int, default=3, help="distinct device copies of the cache, used round-robin")
     ap.add_argument("--cpu-layers", type=int, default=28, help="layers the oracle baseline runs (0 = skip)")
     ap.add_argument("--no-parity", action="store_true")
+    ap.add_argument("--calibrate-copy-mib", type=int, default=0,
+                    help="also launch an elementwise copy kernel that reads and writes this many MiB: a kernel of "
+                         "known traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path has no cross-GPU step); use --gpus 1",
@@ -124,6 +127,14 @@ def main():
     ws = B.alloc_workspace(p, len(layers), dev)
     calls = [B.PreparedCall(p, [x[0] for x in c], [x[1] for x in c], [x[2] for x in c], outs, ws) for c in copies]
     stream = torch.cuda.current_stream()
+
+    if args.calibrate_copy_mib > 0:
+        src = torch.ones(args.calibrate_copy_mib * (1 << 18), dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)           # one vectorised elementwise kernel: reads and writes the size once
+        torch.cuda.synchronize()
+        del src, dst
 
     for i in range(args.warmup):
         calls[i % len(calls)].compress(stream)

@@ -80,6 +80,36 @@ __device__ __forceinline__ float frag_elem(const Frag &f, int j) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Sum of squares of the elements of one 16-byte piece (bf16: four two-element dot products).
+template <int DT>
+__device__ __forceinline__ float piece_sumsq(const Frag &f) {
+  float ss = 0.f;
+  if constexpr (DT == MIXKV_BF16) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const bf16x2 v = __builtin_bit_cast(bf16x2, f.u[j]);
+      ss = __builtin_amdgcn_fdot2_f32_bf16(v, v, ss, false);
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) ss = fmaf(f.f[j], f.f[j], ss);
+  }
+  return ss;
+}
+
+// 1 / max(sqrt(ss), 1e-30): the hardware reciprocal square root (one Newton step on top for f32
+// inputs), with the exact expression for the (wave-uniformly detected) tiny and zero norms.
+template <int DT>
+__device__ __forceinline__ float inv_norm(float ss) {
+  float y = __builtin_amdgcn_rsqf(ss);
+  if constexpr (DT == MIXKV_F32) y = y * fmaf(-0.5f * ss, y * y, 1.5f);
+  if (__builtin_amdgcn_ballot_w64(!(ss >= 1e-30f)) != 0) {
+    if (!(ss >= 1e-30f)) y = 1.f / fmaxf(sqrtf(ss), 1e-30f);
+  }
+  return y;
+}
+
 // Merge two running (max, sum) pairs of a softmax row (log2 domain).  A pair that has seen no
 // key is (-inf, 0).
 __device__ __forceinline__ void ml_merge(float &m, float &l, float m2, float l2) {
@@ -132,48 +162,51 @@ __device__ __forceinline__ int tile_swz(int r) {
   return PPR == 8 ? (r >> 1) & 7 : r & 15;
 }
 
-// Issue the direct-to-LDS loads of key tile k of the chunk that starts at key cbase.  Load j covers
-// slots [64j, 64j+64) of the tile image; lane i fetches the piece that belongs in slot 64j + i.
-// Waves take loads round-robin.  The address is a wave-uniform 64-bit base plus a 32-bit lane
-// offset.  In the last chunk of a sequence, keys past N-1 re-read key N-1 (their results are
-// masked or discarded).
+// Issue the direct-to-LDS loads of the 32-row tile that starts at row tb (keys or values) into the
+// tile image at LDS byte address `img`.  Load j covers slots [64j, 64j+64) of the image; lane i
+// fetches the piece that belongs in slot 64j + i.  Waves take loads round-robin and every wave
+// issues the same number (with fewer loads than waves some are issued twice), so a wave can count
+// its requests in flight.  The address is a wave-uniform 64-bit base plus a 32-bit lane offset.
+// In the last tile of a sequence, rows past N-1 re-read row N-1 (their results are masked or
+// discarded).
+//
+// `img` is an integer on purpose: the destination of the load then carries no object identity, and
+// the compiler does not make later reads of the ring wait for every load in flight - the waits are
+// placed by hand (wait_vm) where the data is needed.
 template <int DT, int D, int WAVES>
-__device__ __forceinline__ void fetch_tile(const char *Kb, int64_t row_bytes, int cbase, int k, int N, uint4 *buf,
-                                           int wave, int lane) {
+__device__ __forceinline__ void fetch_tile(const char *Kb, int64_t row_bytes, int tb, int N, uint32_t img, int wave,
+                                           int lane) {
   constexpr int PPR = D * Tr<DT>::EB / 16, LOADS = 32 * PPR / 64;      // loads per tile
-  constexpr int RPL = 64 / PPR > 0 ? 64 / PPR : 1;                      // rows per load (PPR <= 32)
+  constexpr int RPL = 64 / PPR;                                         // rows per load
   static_assert(PPR <= 64 && 64 % PPR == 0, "row pieces must divide a load");
   const int lrow = lane / PPR, lq = lane % PPR;
   const uint32_t rb = (uint32_t)row_bytes;
-  const int tb = cbase + k * 32;
-  uint4 *tile = buf + k * 32 * PPR;
   if (tb + 32 <= N) {
 #pragma unroll
     for (int jj = 0; jj < (LOADS + WAVES - 1) / WAVES; ++jj) {
-      const int j = jj * WAVES + wave;
-      if (LOADS % WAVES != 0 && j >= LOADS) break;
+      const int j = (jj * WAVES + wave) % LOADS;
       const char *base = Kb + (int64_t)(tb + j * RPL) * row_bytes;               // wave-uniform
       const uint32_t off = (uint32_t)lrow * rb + (uint32_t)((lq ^ tile_swz<DT, D>(j * RPL + lrow)) * 16);
-      __builtin_amdgcn_global_load_lds((glb_void_t *)(base + off), (lds_void_t *)(tile + j * 64), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_void_t *)(base + off), (lds_void_t *)(uintptr_t)(img + j * 1024), 16, 0, 0);
     }
   } else {
 #pragma unroll
     for (int jj = 0; jj < (LOADS + WAVES - 1) / WAVES; ++jj) {
-      const int j = jj * WAVES + wave;
-      if (LOADS % WAVES != 0 && j >= LOADS) break;
+      const int j = (jj * WAVES + wave) % LOADS;
       const int row = j * RPL + lrow;
       const int krow = min(tb + row, N - 1);
       const char *src = Kb + (int64_t)krow * row_bytes + (lq ^ tile_swz<DT, D>(row)) * 16;
-      __builtin_amdgcn_global_load_lds((glb_void_t *)src, (lds_void_t *)(tile + j * 64), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_void_t *)src, (lds_void_t *)(uintptr_t)(img + j * 1024), 16, 0, 0);
     }
   }
 }
 
-template <int DT, int D, int WAVES>
-__device__ __forceinline__ void fetch_chunk(const char *Kb, int64_t row_bytes, int cbase, int N, uint4 *buf, int wave,
-                                            int lane) {
-#pragma unroll
-  for (int k = 0; k < chunk_tiles(DT, D); ++k) fetch_tile<DT, D, WAVES>(Kb, row_bytes, cbase, k, N, buf, wave, lane);
+// LDS byte address of a __shared__ object, laundered through a register so that nothing derived
+// from it is tied to the object (see fetch_tile).
+__device__ __forceinline__ uint32_t lds_base_of(const void *p) {
+  uint32_t a = (uint32_t)(uintptr_t)(lds_void_t *)p;
+  asm volatile("" : "+s"(a));
+  return a;
 }
 
 // Fragment c of key tile k for lane (row l32, half): piece 2c + half of row l32.
@@ -181,6 +214,36 @@ template <int DT, int D>
 __device__ __forceinline__ uint4 read_key_frag(const uint4 *kb, int k, int c, int l32, int half) {
   constexpr int PPR = D * Tr<DT>::EB / 16;
   return kb[(k * 32 + l32) * PPR + ((2 * c + half) ^ tile_swz<DT, D>(l32))];
+}
+
+// ------------------------------------------------------------------------------------------------
+// The tile ring.  Tiles of 32 rows travel global -> LDS through a ring of kRing tile images.  Every
+// request is issued kLead tile steps before its data is used, in every wave, for keys and values
+// alike: the memory counter of a wave retires in order, so a uniform lead means that waiting for
+// the oldest request never waits for a younger one.  One tile step is
+//     wait until this wave's share of tile t has landed; barrier; request tile t + kLead (into the
+//     image of tile t - 1, which every wave has left behind by passing the barrier); work on t.
+// ------------------------------------------------------------------------------------------------
+constexpr int kRing = 4, kLead = 3;
+static_assert((kRing & (kRing - 1)) == 0 && kLead < kRing, "ring slots are taken modulo a power of two");
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() would also drain the memory
+// counter, i.e. wait for every tile in flight and throw the lead away.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// s_waitcnt vmcnt(n) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt and lgkmcnt left open)
+template <int NOUT>
+__device__ __forceinline__ void wait_vm() {
+  static_assert(NOUT >= 0 && NOUT < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt((NOUT & 15) | ((NOUT >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+// Wait for this wave's requests of tile t.  Younger than those are the requests of the kLead - 1
+// tiles after it (PER_TILE each, and any store since) as long as the run still had tiles to
+// request; near the end of a run everything is awaited.
+template <int PER_TILE>
+__device__ __forceinline__ void wait_tile(int t, int nt) {
+  if (t + kLead <= nt) wait_vm<(kLead - 1) * PER_TILE>(); else wait_vm<0>();
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -195,12 +258,11 @@ __device__ __forceinline__ uint4 read_key_frag(const uint4 *kb, int k, int c, in
 template <int DT, int D, int WAVES, int TQ>
 __global__ __launch_bounds__(WAVES * 64, 2) void stats_kernel(Shape s, LayerInTable in, char *ws, Workspace w,
                                                              int64_t unit0, int nunits, int64_t slot0) {
-  constexpr int EB = Tr<DT>::EB, EPC = Tr<DT>::EPC, NCHK = D / (2 * EPC), NE = D / 2, PPR = D * EB / 16;
-  constexpr int NT = WAVES * 64, KT = chunk_tiles(DT, D), CH = KT * 32, FRAGS = KT * NCHK;
-  constexpr int VPT = (32 * PPR + NT - 1) / NT;           // V pieces per thread and key tile
-  // Two separately declared key buffers: the compiler can then tell that reads of one do not
-  // depend on the direct-to-LDS loads in flight into the other.
-  __shared__ uint4 kbuf_a[FRAGS * 64], kbuf_b[FRAGS * 64];
+  constexpr int EB = Tr<DT>::EB, EPC = Tr<DT>::EPC, NCHK = D / (2 * EPC), PPR = D * EB / 16;
+  constexpr int NT = WAVES * 64, KT = chunk_tiles(DT, D), TILE = 32 * PPR;
+  constexpr int VPT = (TILE + NT - 1) / NT;               // V pieces per thread and key tile
+  constexpr int KL = (TILE / 64 + WAVES - 1) / WAVES;     // requests per wave, tile and tensor
+  __shared__ uint4 kring[kRing * TILE], vring[kRing * TILE];
   __shared__ float ks_s[WAVES * D];
 
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
@@ -210,6 +272,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void stats_kernel(Shape s, LayerInTa
   const int free_limit = s.causal ? Nc : N - 1;      // keys <= this are visible to every row
   const int nq = max(0, min(TQ, s.QT - wave * TQ));  // query tiles this wave owns
   const bool use_v = s.intrinsic == MIXKV_INTRINSIC_VNORM;
+  const uint32_t kring_a = lds_base_of(kring), vring_a = lds_base_of(vring);
   const int64_t T = (int64_t)nunits * s.nchunks;
   int64_t item = wg_first_item(blockIdx.x, gridDim.x, T);
   const int64_t item_end = wg_first_item(blockIdx.x + 1, gridDim.x, T);
@@ -227,10 +290,20 @@ __global__ __launch_bounds__(WAVES * 64, 2) void stats_kernel(Shape s, LayerInTa
     const int64_t row_bytes = L.sn * EB;
     float *invnorm = reinterpret_cast<float *>(ws + w.invnorm) + unit * s.Npad;
     float *vnorm = reinterpret_cast<float *>(ws + w.vnorm) + unit * s.Npad;
+    const int key0 = c0 * KT * 32;                                   // first key of the run
+    const int nt = min(nit * KT, (N - key0 + 31) / 32);              // tiles of the run that hold keys
 
-    __syncthreads();                                   // the previous run is done with LDS
-    fetch_chunk<DT, D, WAVES>(Kb, row_bytes, c0 * CH, N, kbuf_a, wave, lane);
-    for (int d = lane; d < D; d += 64) ks_s[wave * D + d] = 0.f;
+    // Request tile tr of the run (keys, and values if they are needed) into its ring image.
+    auto request = [&](int tr) {
+      const int tbr = key0 + tr * 32;
+      const uint32_t off = (uint32_t)(tr & (kRing - 1)) * (TILE * 16);
+      fetch_tile<DT, D, WAVES>(Kb, row_bytes, tbr, N, kring_a + off, wave, lane);
+      if (use_v) fetch_tile<DT, D, WAVES>(Vb, row_bytes, tbr, N, vring_a + off, wave, lane);
+    };
+    lds_barrier();                                     // the previous run is done with LDS
+#pragma unroll
+    for (int j = 0; j < kLead; ++j)
+      if (j < nt) request(j);
 
     // this wave's query tiles, in fragment form, for the whole run (tiles past QT are zero)
     Frag qf[TQ][NCHK];
@@ -250,146 +323,97 @@ __global__ __launch_bounds__(WAVES * 64, 2) void stats_kernel(Shape s, LayerInTa
       m[q] = -INFINITY;
       l[q] = 0.f;
     }
+    // Nothing may be pending when the tile loop is entered: its waits count the requests issued
+    // inside it.
+    wait_vm<0>();
 
-    // one chunk: its keys are in `kb`; the next chunk streams into `kn` meanwhile
-    auto do_chunk = [&](int it, const uint4 *kb, uint4 *kn) {
-      const int cbase = (c0 + it) * CH;
-      __builtin_amdgcn_s_waitcnt(0);                   // this wave's share of the chunk has landed
-      __syncthreads();                                 // ... and everybody else's; the other buffer is free
-      const bool has_next = it + 1 < nit;
+    // Sum of normalised keys: lane (lrow, lq) adds up piece lq (elements [lq*EPC, +EPC)) of the
+    // rows it visits, so nothing crosses lanes before the end of the run.
+    float ksacc[EPC];
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) ksacc[e] = 0.f;
 
-      // |V_i| rides along: the rows of key tile k are requested one tile ahead of their use, and
-      // always *before* the slice of the next chunk's keys issued in the same tile step.  The
-      // memory counter retires in order, so waiting for value rows only ever waits for key loads
-      // that are at least one tile step old.
-      Frag vb[VPT], vn[VPT];                           // rows in use / rows in flight
-      auto v_issue = [&](int k) {
-#pragma unroll
-        for (int i = 0; i < VPT; ++i) {
-          const int p = i * NT + tid, key = cbase + k * 32 + p / PPR;
-          const bool on = p < 32 * PPR && key < Nc;
-          uint4 v = *reinterpret_cast<const uint4 *>(Vb + (int64_t)(on ? key : 0) * row_bytes + (p % PPR) * 16);
-          vn[i].q = on ? v : make_uint4(0, 0, 0, 0);
-        }
-      };
-      auto v_consume = [&](int k) {
-#pragma unroll
-        for (int i = 0; i < VPT; ++i) {
-          const int p = i * NT + tid, key = cbase + k * 32 + p / PPR;
-          float ss = 0.f;
-#pragma unroll
-          for (int e = 0; e < EPC; ++e) {
-            float x = frag_elem<DT>(vb[i], e);
-            ss = fmaf(x, x, ss);
-          }
-          ss = seg_sum<PPR>(ss);                       // PPR consecutive lanes hold one row
-          if (p % PPR == 0 && p < 32 * PPR && key < Nc) vnorm[key] = sqrtf(ss);
-        }
-      };
-      if (use_v) v_issue(0);
+    for (int t = 0; t < nt; ++t) {
+      __builtin_amdgcn_sched_barrier(0);
+      if (use_v) wait_tile<2 * KL>(t, nt); else wait_tile<KL>(t, nt);
+      lds_barrier();
+      if (t + kLead < nt) request(t + kLead);
+      __builtin_amdgcn_sched_barrier(0);
 
-#pragma unroll 1
-      for (int k = 0; k < KT; ++k) {
-        const int tb = cbase + k * 32;
-        if (use_v) {
+      const int tb = key0 + t * 32;
+      const uint4 *img = kring + (t & (kRing - 1)) * TILE;
+      const uint4 *vimg = vring + (t & (kRing - 1)) * TILE;
+      Frag kf[NCHK];
 #pragma unroll
-          for (int i = 0; i < VPT; ++i) vb[i] = vn[i];
-          if (k + 1 < KT) v_issue(k + 1);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        if (has_next) fetch_tile<DT, D, WAVES>(Kb, row_bytes, cbase + CH, k, N, kn, wave, lane);
-        __builtin_amdgcn_sched_barrier(0);
-        if (tb < N) {
-          Frag kf[NCHK];
-#pragma unroll
-          for (int c = 0; c < NCHK; ++c) kf[c].q = read_key_frag<DT, D>(kb, k, c, l32, half);
+      for (int c = 0; c < NCHK; ++c) kf[c].q = read_key_frag<DT, D>(img, 0, c, l32, half);
 
-          // ---- softmax statistics of all TQ tiles; the MFMA chains are independent
-          f32x16 acc[TQ];
+      // ---- softmax statistics of all TQ tiles; the MFMA chains are independent
+      f32x16 acc[TQ];
 #pragma unroll
-          for (int q = 0; q < TQ; ++q)
+      for (int q = 0; q < TQ; ++q)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[q][i] = 0.f;
+        for (int i = 0; i < 16; ++i) acc[q][i] = 0.f;
 #pragma unroll
-          for (int c = 0; c < NCHK; ++c)
+      for (int c = 0; c < NCHK; ++c)
 #pragma unroll
-            for (int q = 0; q < TQ; ++q) acc[q] = mma<DT>(kf[c], qf[q][c], acc[q]);
-          if (tb + 31 > free_limit) {                  // tile reaches into the window or past N: mask
-#pragma unroll
-            for (int q = 0; q < TQ; ++q)
-#pragma unroll
-              for (int i = 0; i < 16; ++i) {
-                int kidx = tb + 8 * (i >> 2) + 4 * half + (i & 3);
-                acc[q][i] = (kidx > lim[q]) ? -INFINITY : acc[q][i];
-              }
-          }
-#pragma unroll
-          for (int q = 0; q < TQ; ++q) {
-            float tmax = fmaxf(acc[q][0], acc[q][1]);
-#pragma unroll
-            for (int i = 2; i < 16; i += 2) tmax = fmaxf(fmaxf(tmax, acc[q][i]), acc[q][i + 1]);
-            const float mn = fmaxf(m[q], tmax * c2);          // c2 > 0: scaling commutes with max
-            const float mu = (mn == -INFINITY) ? 0.f : mn;
-            float sum = 0.f;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(acc[q][i], c2, -mu));
-            l[q] = l[q] * fast_exp2(m[q] - mu) + sum;
-            m[q] = mn;
-          }
+        for (int q = 0; q < TQ; ++q) acc[q] = mma<DT>(kf[c], qf[q][c], acc[q]);
 
-          // ---- key norms and the sum of normalised keys: one wave per tile, round-robin
-          if ((k + it * KT) % WAVES == wave) {
-            const int key = tb + l32;
-            float ss = 0.f;
+      // ---- key norms and the sum of normalised keys (independent of the MFMA results, so it can
+      // fill the vector ALU while the matrix core runs).  The tile image is walked 64 pieces at a
+      // time (RPL whole rows), steps dealt round-robin to the waves; PPR consecutive lanes hold
+      // one key.
+      constexpr int STEPS = TILE / 64, RPL = 64 / PPR;
+      const int lrow = lane / PPR, lq = lane % PPR;
 #pragma unroll
-            for (int c = 0; c < NCHK; ++c)
+      for (int jj = 0; jj < (STEPS + WAVES - 1) / WAVES; ++jj) {
+        const int j = jj * WAVES + wave;
+        if (STEPS % WAVES != 0 && j >= STEPS) break;
+        const int row = j * RPL + lrow, key = tb + row;
+        Frag f;
+        f.q = img[row * PPR + (lq ^ tile_swz<DT, D>(row))];
+        const float ss = seg_sum<PPR>(piece_sumsq<DT>(f));
+        const bool valid = key < N;
+        const float inv = valid ? inv_norm<DT>(ss) : 0.f;
+        if (valid && lq == 0) invnorm[key] = inv;
 #pragma unroll
-              for (int e = 0; e < EPC; ++e) {
-                float v = frag_elem<DT>(kf[c], e);
-                ss = fmaf(v, v, ss);
-              }
-            ss += __shfl_xor(ss, 32);
-            const bool valid = key < N;
-            const float inv = valid ? 1.f / fmaxf(sqrtf(ss), 1e-30f) : 0.f;
-            if (valid && half == 0) invnorm[key] = inv;
-            // Groups of 32 accumulators (to bound register use).  Fixed-order butterfly over the
-            // 32 lanes of a half: every step halves the number of accumulators a lane carries; a
-            // lane ends with one, summed over all 32 keys.
-            constexpr int NG = 32, NGRP = NE / NG, CG = NCHK / NGRP;
-#pragma unroll
-            for (int grp = 0; grp < NGRP; ++grp) {
-              float ks[NG];
-#pragma unroll
-              for (int c = 0; c < CG; ++c)
-#pragma unroll
-                for (int e = 0; e < EPC; ++e) ks[c * EPC + e] = inv * frag_elem<DT>(kf[grp * CG + c], e);
-              int n = NG, start = 0;
-#pragma unroll
-              for (int sft = 16; sft >= 1; sft >>= 1) {
-                const int hn = n >> 1;
-                const bool up = (lane & sft) != 0;
-                const uint32_t um = up ? 0xffffffffu : 0u;    // bit select: keeps the accumulators in registers
-#pragma unroll
-                for (int i = 0; i < hn; ++i) {
-                  const uint32_t lo = __float_as_uint(ks[i]), hi = __float_as_uint(ks[i + hn]);
-                  const float send = __uint_as_float((lo & um) | (hi & ~um));
-                  const float keep = __uint_as_float((hi & um) | (lo & ~um));
-                  ks[i] = keep + __shfl_xor(send, sft);
-                }
-                start += up ? hn : 0;
-                n = hn;
-              }
-              const int c = grp * CG + start / EPC, jj = start % EPC;
-              ks_s[wave * D + (2 * c + half) * EPC + jj] += ks[0];    // this lane owns the slot
-            }
-          }
-        }
-        if (use_v) v_consume(k);
+        for (int e = 0; e < EPC; ++e) ksacc[e] = fmaf(inv, frag_elem<DT>(f, e), ksacc[e]);
       }
-    };
-    for (int it = 0; it < nit; it += 2) {
-      do_chunk(it, kbuf_a, kbuf_b);
-      if (it + 1 < nit) do_chunk(it + 1, kbuf_b, kbuf_a);
+
+      // ---- |V_i|: PPR consecutive lanes hold one row (which piece of the row a lane gets does
+      // not matter for a sum of squares, so the image is read without undoing the rotation)
+      if (use_v) {
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+          const int p = i * NT + tid, key = tb + p / PPR;
+          Frag f;
+          f.q = vimg[p < TILE ? p : 0];
+          const float ss = seg_sum<PPR>(piece_sumsq<DT>(f));
+          if (p % PPR == 0 && p < TILE && key < Nc) vnorm[key] = __builtin_amdgcn_sqrtf(ss);
+        }
+      }
+
+      if (tb + 31 > free_limit) {                  // tile reaches into the window or past N: mask
+#pragma unroll
+        for (int q = 0; q < TQ; ++q)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            int kidx = tb + 8 * (i >> 2) + 4 * half + (i & 3);
+            acc[q][i] = (kidx > lim[q]) ? -INFINITY : acc[q][i];
+          }
+      }
+#pragma unroll
+      for (int q = 0; q < TQ; ++q) {
+        float tmax = fmaxf(acc[q][0], acc[q][1]);
+#pragma unroll
+        for (int i = 2; i < 16; i += 2) tmax = fmaxf(fmaxf(tmax, acc[q][i]), acc[q][i + 1]);
+        const float mn = fmaxf(m[q], tmax * c2);          // c2 > 0: scaling commutes with max
+        const float mu = (mn == -INFINITY) ? 0.f : mn;
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(acc[q][i], c2, -mu));
+        l[q] = l[q] * fast_exp2(m[q] - mu) + sum;
+        m[q] = mn;
+      }
     }
 
     // ---- run partials to global
@@ -400,7 +424,14 @@ __global__ __launch_bounds__(WAVES * 64, 2) void stats_kernel(Shape s, LayerInTa
       ml_merge(m[q], l[q], __shfl_xor(m[q], 32), __shfl_xor(l[q], 32));
       if (q < nq && half == 0) part_ml[(wave * TQ + q) * 32 + l32] = make_float2(m[q], l[q]);
     }
-    __syncthreads();                                   // ks_s complete
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) {
+      float x = ksacc[e];
+#pragma unroll
+      for (int off = PPR; off < 64; off <<= 1) x += __shfl_xor(x, off);   // rows of one step, fixed order
+      if (lane < PPR) ks_s[wave * D + lane * EPC + e] = x;
+    }
+    lds_barrier();                                     // ks_s complete
     float *part_ks = reinterpret_cast<float *>(ws + w.part_ksum) + slot * D;
     for (int d = tid; d < D; d += NT) {
       float a = 0.f;
@@ -430,33 +461,28 @@ template <int DT, int D, int WAVES, int TQ>
 __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTable in, LayerOutTable out, char *ws,
                                                             Workspace w, int64_t unit0, int nunits, int G1,
                                                             int64_t slot0) {
-  constexpr int EB = Tr<DT>::EB, EPC = Tr<DT>::EPC, NCHK = D / (2 * EPC);
-  constexpr int NT = WAVES * 64, KT = chunk_tiles(DT, D), CH = KT * 32, FRAGS = KT * NCHK;
-  __shared__ uint4 kbuf_a[FRAGS * 64], kbuf_b[FRAGS * 64];   // separate objects, see stats_kernel
+  constexpr int EB = Tr<DT>::EB, EPC = Tr<DT>::EPC, NCHK = D / (2 * EPC), PPR = D * EB / 16;
+  constexpr int NT = WAVES * 64, KT = chunk_tiles(DT, D), CH = KT * 32, TILE = 32 * PPR;
+  constexpr int KL = (TILE / 64 + WAVES - 1) / WAVES;        // requests per wave and tile
+  __shared__ uint4 kring[kRing * TILE];
   __shared__ uint4 kbar_s[NCHK * 4];                         // mean-key rows 0/1 x halves, 16-byte pieces
   __shared__ float cs_s[2 * WAVES * CH];                     // [2][WAVES][CH] partial column sums
   __shared__ float nb_s[WAVES * TQ * 32];                    // -b_r per query row (-inf rows give weight 0)
-  __shared__ int lim_s[WAVES * TQ * 32];                     // last key each query row attends to
   __shared__ float kbar_f[D];                                // mean normalised key
   __shared__ double red_s[WAVES];
-  __shared__ int g_lo_s, g_hi_s;
 
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps its address math scalar
   const int N = s.N, Nc = s.Nc, QTR = s.QT * 32;
   const float c2 = s.scale_log2e;
   const int free_limit = s.causal ? Nc : N - 1;
-  for (int r = tid; r < WAVES * TQ * 32; r += NT) lim_s[r] = s.causal ? Nc + r % s.W : N - 1;
   // the mean key rides in rows 0/1 of the first tile past the live rows, if the block has one
   const bool spare = s.QT < WAVES * TQ;
   const int kb_wave = s.QT / TQ, kb_q = s.QT % TQ;
+  const uint32_t kring_a = lds_base_of(kring);
   const int64_t T = (int64_t)nunits * s.nchunks;
   int64_t item = wg_first_item(blockIdx.x, gridDim.x, T);
   const int64_t item_end = wg_first_item(blockIdx.x + 1, gridDim.x, T);
-  TDECL;
-#ifdef MIXKV_TIMING
-  if (threadIdx.x == 0) { mixkv_dbg[blockIdx.x * 16 + 4] = wall_clock64(); mixkv_dbg[blockIdx.x * 16 + 6] = __builtin_readcyclecounter(); }
-#endif
 
   while (item < item_end) {
     const int ul = (int)(item / s.nchunks), c0 = (int)(item - (int64_t)ul * s.nchunks);
@@ -469,26 +495,31 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
     const int64_t row_bytes = L.sn * EB;
     float *araw = reinterpret_cast<float *>(ws + w.araw) + unit * s.Npad;
     float *kdot = reinterpret_cast<float *>(ws + w.sdiv) + unit * s.Npad;   // K_i . Kbar, not yet normalised
+    const int key0 = c0 * CH;                                        // first key of the run
+    const int nt = min(nit * KT, (N - key0 + 31) / 32);              // tiles of the run that hold keys
 
-    TSTAMP(p0);
     __syncthreads();                                   // the previous run is done with LDS
-    fetch_chunk<DT, D, WAVES>(Kb, row_bytes, c0 * CH, N, kbuf_a, wave, lane);
-    TSTAMP(p1);
+#pragma unroll
+    for (int j = 0; j < kLead; ++j)
+      if (j < nt) fetch_tile<DT, D, WAVES>(Kb, row_bytes, key0 + j * 32, N, kring_a + j * (TILE * 16), wave, lane);
+
+    // this wave's query rows, requested now and put into fragment form after the fold below
+    Frag qf[TQ][NCHK];
+#pragma unroll
+    for (int q = 0; q < TQ; ++q) {
+      const int row = (wave * TQ + q) * 32 + l32;
+      const char *qrow = Qb + ((int64_t)(row < s.GW ? row : 0) * D) * EB + half * 16;
+#pragma unroll
+      for (int c = 0; c < NCHK; ++c) qf[q][c].q = *reinterpret_cast<const uint4 *>(qrow + c * 32);
+    }
 
     // ---- fold the partials of stats_kernel for this unit.  Workgroup g of its grid owned the items
     // [g*T1/G1, (g+1)*T1/G1) and wrote one partial per unit it touched, at slot g + unit_local.
-    if (tid == 0) {
-      const int64_t T1 = (int64_t)nunits * s.nchunks, first = (int64_t)ul * s.nchunks, last = first + s.nchunks;
-      int64_t g = first * G1 / T1;
-      while (g > 0 && wg_first_item(g, G1, T1) > first) --g;
-      while (wg_first_item(g + 1, G1, T1) <= first) ++g;
-      g_lo_s = (int)g;
-      while (g + 1 < G1 && wg_first_item(g + 1, G1, T1) < last) ++g;
-      g_hi_s = (int)g;
-    }
-    __syncthreads();
+    // The unit's items are [first, last): the first workgroup touching it is the largest g with
+    // g*T1/G1 <= first, the last one the largest g with g*T1/G1 < last.
     {
-      const int g_lo = g_lo_s, g_hi = g_hi_s;
+      const int64_t T1 = (int64_t)nunits * s.nchunks, first = (int64_t)ul * s.nchunks, last = first + s.nchunks;
+      const int g_lo = (int)(((first + 1) * G1 + T1 - 1) / T1) - 1, g_hi = (int)((last * G1 + T1 - 1) / T1) - 1;
       const float2 *all_ml = reinterpret_cast<const float2 *>(ws + w.part_ml) + (slot0 + ul) * QTR;
       for (int r = tid; r < WAVES * TQ * 32; r += NT) {
         float b = INFINITY;                            // rows past G*W: weight 0
@@ -557,29 +588,28 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
       }
       kbar_s[p] = f.q;
     }
-    TSTAMP(p2);
-    __syncthreads();                                   // kbar_s visible
-    TSTAMP(p3);
+    __syncthreads();                                   // kbar_s visible; every request so far has landed
 
-    // this wave's query tiles, in fragment form, for the whole run (tiles past QT are zero,
-    // except for the two mean-key rows)
-    Frag qf[TQ][NCHK];
+    // query tiles in fragment form (tiles past QT are zero, except for the two mean-key rows), the
+    // exponent offset of each of the lane's 16 rows per tile, and the last key each row attends to
+    float nbv[TQ][16];
 #pragma unroll
     for (int q = 0; q < TQ; ++q) {
       const int row = (wave * TQ + q) * 32 + l32;
       const bool live = row < s.GW;
       const bool mean_rows = spare && wave == kb_wave && q == kb_q && l32 < 2;
-      const char *qrow = Qb + ((int64_t)(live ? row : 0) * D) * EB + half * 16;
 #pragma unroll
       for (int c = 0; c < NCHK; ++c) {
-        uint4 v = *reinterpret_cast<const uint4 *>(qrow + c * 32);
         uint4 mk = kbar_s[(c * 2 + half) * 2 + (l32 & 1)];
-        qf[q][c].q = live ? v : (mean_rows ? mk : make_uint4(0, 0, 0, 0));
+        qf[q][c].q = live ? qf[q][c].q : (mean_rows ? mk : make_uint4(0, 0, 0, 0));
+      }
+#pragma unroll
+      for (int k4 = 0; k4 < 4; ++k4) {
+        const float4 nb = *reinterpret_cast<const float4 *>(&nb_s[(wave * TQ + q) * 32 + 8 * k4 + 4 * half]);
+        nbv[q][4 * k4 + 0] = nb.x; nbv[q][4 * k4 + 1] = nb.y; nbv[q][4 * k4 + 2] = nb.z; nbv[q][4 * k4 + 3] = nb.w;
       }
     }
 
-    TSTAMP(p4);
-    TACC(4, p0, p1); TACC(5, p1, p2); TACC(6, p2, p3); TACC(7, p3, p4);
     // add the waves' partial column sums of chunk `chunk` (buffer pb) in a fixed order
     auto flush_colsums = [&](int chunk, int pb) {
       for (int i = tid; i < CH; i += NT) {
@@ -590,177 +620,80 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
       }
     };
 
-    auto do_chunk = [&](int it, const uint4 *kb, uint4 *kn) {
-      const int cbase = (c0 + it) * CH;
-      TSTAMP(t0);
-      __builtin_amdgcn_s_waitcnt(0);
-      TSTAMP(t1);
-      __syncthreads();
-      TSTAMP(t2);
-      const bool has_next = it + 1 < nit;
-      if (it > 0) flush_colsums(c0 + it - 1, (it - 1) & 1);
-      float *cs = cs_s + ((it & 1) * WAVES + wave) * CH;
-      TSTAMP(t3);
-      TACC(0, t0, t1); TACC(1, t1, t2); TACC(2, t2, t3);
+    for (int t = 0; t < nt; ++t) {
+      __builtin_amdgcn_sched_barrier(0);
+      wait_tile<KL>(t, nt);
+      lds_barrier();
+      if (t + kLead < nt)
+        fetch_tile<DT, D, WAVES>(Kb, row_bytes, key0 + (t + kLead) * 32, N,
+                                 kring_a + (uint32_t)((t + kLead) & (kRing - 1)) * (TILE * 16), wave, lane);
+      __builtin_amdgcn_sched_barrier(0);
+      const int k = t % KT, g = t / KT;                // tile within its chunk, chunk within the run
+      if (k == 0 && g > 0) flush_colsums(c0 + g - 1, (g - 1) & 1);
+      float *cs = cs_s + ((g & 1) * WAVES + wave) * CH;
+      const int tb = key0 + t * 32, key = tb + l32;
+      const uint4 *img = kring + (t & (kRing - 1)) * TILE;
 
       Frag kf[NCHK];
 #pragma unroll
-      for (int c = 0; c < NCHK; ++c) kf[c].q = read_key_frag<DT, D>(kb, 0, c, l32, half);
-#pragma unroll 1
-      for (int k = 0; k < KT; ++k) {
-        const int tb = cbase + k * 32;
-        // the next chunk streams in one tile per tile step, so its loads never queue up
-#ifndef MIXKV_NODMA   // developer switch: time the arithmetic alone (results are then meaningless)
-        if (has_next) fetch_tile<DT, D, WAVES>(Kb, row_bytes, cbase + CH, k, N, kn, wave, lane);
-#endif
-        __builtin_amdgcn_sched_barrier(0);
-        f32x16 acc[TQ];
+      for (int c = 0; c < NCHK; ++c) kf[c].q = read_key_frag<DT, D>(img, 0, c, l32, half);
+      f32x16 acc[TQ];
+#pragma unroll
+      for (int q = 0; q < TQ; ++q)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[q][i] = 0.f;
+#pragma unroll
+      for (int c = 0; c < NCHK; ++c)
+#pragma unroll
+        for (int q = 0; q < TQ; ++q) acc[q] = mma<DT>(qf[q][c], kf[c], acc[q]);
+
+      // ---- K_i . Kbar: rows 0 and 1 (half 0) of the spare tile, or a separate mean-key tile that
+      // the waves apply in turn
+      float kd = 0.f;
+      bool kd_mine;
+      if (spare) {
+        kd = (kb_q == 0 ? acc[0][0] + acc[0][1] : acc[TQ - 1][0] + acc[TQ - 1][1]);
+        kd_mine = wave == kb_wave;
+      } else {
+        kd_mine = t % WAVES == wave;
+        if (kd_mine) {
+          f32x16 acd;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) acd[i] = 0.f;
+#pragma unroll
+          for (int c = 0; c < NCHK; ++c) {
+            Frag kbf;
+            kbf.q = kbar_s[(c * 2 + half) * 2 + (l32 & 1)];
+            if (l32 >= 2) kbf.q = make_uint4(0, 0, 0, 0);
+            acd = mma<DT>(kbf, kf[c], acd);
+          }
+          kd = acd[0] + acd[1];
+        }
+      }
+      if (kd_mine && half == 0 && key < Nc) kdot[key] = kd;
+
+      if (tb + 31 > free_limit) {                      // tile reaches into the window or past N: mask
 #pragma unroll
         for (int q = 0; q < TQ; ++q)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) acc[q][i] = 0.f;
-#pragma unroll
-        for (int c = 0; c < NCHK; ++c)
-#pragma unroll
-          for (int q = 0; q < TQ; ++q) acc[q] = mma<DT>(qf[q][c], kf[c], acc[q]);
-        float kd = 0.f;
-        if (!spare) {
-          // no spare tile: a separate mean-key tile on every WAVES-th key tile
-          if ((k + it * KT) % WAVES == wave) {
-            f32x16 acd;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acd[i] = 0.f;
-#pragma unroll
-            for (int c = 0; c < NCHK; ++c) {
-              Frag kbf;
-              kbf.q = kbar_s[(c * 2 + half) * 2 + (l32 & 1)];
-              if (l32 >= 2) kbf.q = make_uint4(0, 0, 0, 0);
-              acd = mma<DT>(kbf, kf[c], acd);
-            }
-            kd = acd[0] + acd[1];
+          for (int i = 0; i < 16; ++i) {
+            const int row = (wave * TQ + q) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+            const int lim = s.causal ? Nc + row % s.W : N - 1;
+            acc[q][i] = (key <= lim) ? acc[q][i] : -INFINITY;
           }
-        }
-        // the fragments of the next tile travel LDS -> registers under this tile's arithmetic
-        if (k + 1 < KT) {
-#pragma unroll
-          for (int c = 0; c < NCHK; ++c) kf[c].q = read_key_frag<DT, D>(kb, k + 1, c, l32, half);
-        }
-        if (spare) kd = (kb_q == 0 ? acc[0][0] + acc[0][1] : acc[TQ - 1][0] + acc[TQ - 1][1]);   // rows 0, 1: half 0
-        const bool kd_mine = spare ? wave == kb_wave : (k + it * KT) % WAVES == wave;
-        const int key = tb + l32;
-        if (kd_mine && half == 0 && key < Nc) kdot[key] = kd;
-
-        if (tb + 31 > free_limit) {                    // tile reaches into the window or past N: mask
-#pragma unroll
-          for (int q = 0; q < TQ; ++q)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const int row = (wave * TQ + q) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-              acc[q][i] = (key <= lim_s[row]) ? acc[q][i] : -INFINITY;
-            }
-        }
-        float colsum = 0.f;
-#pragma unroll
-        for (int q = 0; q < TQ; ++q)
-#pragma unroll
-          for (int k4 = 0; k4 < 4; ++k4) {
-            const float4 nb = *reinterpret_cast<const float4 *>(&nb_s[(wave * TQ + q) * 32 + 8 * k4 + 4 * half]);
-            colsum += fast_exp2(fmaf(acc[q][4 * k4 + 0], c2, nb.x)) + fast_exp2(fmaf(acc[q][4 * k4 + 1], c2, nb.y)) +
-                      fast_exp2(fmaf(acc[q][4 * k4 + 2], c2, nb.z)) + fast_exp2(fmaf(acc[q][4 * k4 + 3], c2, nb.w));
-          }
-        colsum += __shfl_xor(colsum, 32);
-        if (half == 0) cs[k * 32 + l32] = (tb < N) ? colsum : 0.f;
       }
-      TSTAMP(t4);
-      TACC(3, t3, t4);
-    };
-    // Fast path for chunks that no row has to mask (everything before the window): the work is cut
-    // into blocks (key tile k, query tile q); the MFMA chain of block j+1 is issued interleaved with
-    // the exp2/sum arithmetic on the finished block j, so the matrix core and the vector ALU of the
-    // SIMD run at the same time.  Two accumulators alternate; the fragments of the next key tile
-    // replace the current ones as soon as the tile's last chain has consumed them.
-    auto do_chunk_fast = [&](int it, const uint4 *kb, uint4 *kn) {
-      constexpr int NB = KT * TQ;
-      const int cbase = (c0 + it) * CH;
-      __builtin_amdgcn_s_waitcnt(0);
-      __syncthreads();
-      const bool has_next = it + 1 < nit;
-      if (it > 0) flush_colsums(c0 + it - 1, (it - 1) & 1);
-      float *cs = cs_s + ((it & 1) * WAVES + wave) * CH;
-
-      Frag kf[NCHK];
+      float colsum = 0.f;
 #pragma unroll
-      for (int c = 0; c < NCHK; ++c) kf[c].q = read_key_frag<DT, D>(kb, 0, c, l32, half);
-      f32x16 acc[2];
-      auto chain = [&](int j) {                         // MFMA chain of block j, and the fragment hand-over
-        const int k = j / TQ, q = j % TQ;
-        f32x16 a;
+      for (int q = 0; q < TQ; ++q)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) a[i] = 0.f;
-#pragma unroll
-        for (int c = 0; c < NCHK; ++c) {
-          a = mma<DT>(qf[q][c], kf[c], a);
-          if (q == TQ - 1 && k + 1 < KT) kf[c].q = read_key_frag<DT, D>(kb, k + 1, c, l32, half);
-        }
-        acc[j & 1] = a;
-      };
-      chain(0);
-      float colsum = 0.f, kdv[KT];
-#pragma unroll
-      for (int j = 0; j < NB; ++j) {
-        const int k = j / TQ, q = j % TQ;
-        if (q == 0) {
-#ifndef MIXKV_NODMA
-          if (has_next) fetch_tile<DT, D, WAVES>(Kb, row_bytes, cbase + CH, k, N, kn, wave, lane);
-#endif
-          colsum = 0.f;
-        }
-        // block j is complete: its mean-key rows (0 and 1 of the spare tile, half 0) first
-        if (q == kb_q) kdv[k] = acc[j & 1][0] + acc[j & 1][1];
-        if (j + 1 < NB) chain(j + 1);
-#pragma unroll
-        for (int k4 = 0; k4 < 4; ++k4) {
-          const float4 nb = *reinterpret_cast<const float4 *>(&nb_s[(wave * TQ + q) * 32 + 8 * k4 + 4 * half]);
-          const f32x16 &a = acc[j & 1];
-          colsum += fast_exp2(fmaf(a[4 * k4 + 0], c2, nb.x)) + fast_exp2(fmaf(a[4 * k4 + 1], c2, nb.y)) +
-                    fast_exp2(fmaf(a[4 * k4 + 2], c2, nb.z)) + fast_exp2(fmaf(a[4 * k4 + 3], c2, nb.w));
-        }
-        if (j + 1 < NB) {
-#pragma unroll
-          for (int c = 0; c < NCHK; ++c) {               // one MFMA, then its share of the vector work
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 48 / NCHK, 0);
-          }
-        }
-        if (q == TQ - 1) {
-          colsum += __shfl_xor(colsum, 32);
-          if (half == 0) cs[k * 32 + l32] = colsum;
-        }
-      }
-      if (wave == kb_wave && half == 0) {
-#pragma unroll
-        for (int k = 0; k < KT; ++k) kdot[cbase + k * 32 + l32] = kdv[k];
-      }
-    };
-
-    for (int it = 0; it < nit; it += 2) {
-      // a chunk is "free" when even its last key is visible to every row and the mean key rides
-      // in a spare tile; the general path handles the rest
-      const bool free_a = spare && (c0 + it + 1) * CH - 1 <= free_limit;
-      if (free_a) do_chunk_fast(it, kbuf_a, kbuf_b); else do_chunk(it, kbuf_a, kbuf_b);
-      if (it + 1 < nit) {
-        const bool free_b = spare && (c0 + it + 2) * CH - 1 <= free_limit;
-        if (free_b) do_chunk_fast(it + 1, kbuf_b, kbuf_a); else do_chunk(it + 1, kbuf_b, kbuf_a);
-      }
+        for (int i = 0; i < 16; ++i) colsum += fast_exp2(fmaf(acc[q][i], c2, nbv[q][i]));
+      colsum += __shfl_xor(colsum, 32);
+      if (half == 0) cs[k * 32 + l32] = colsum;
     }
-    __syncthreads();
-    flush_colsums(c0 + nit - 1, (nit - 1) & 1);
+    lds_barrier();
+    flush_colsums(c0 + (nt - 1) / KT, ((nt - 1) / KT) & 1);
     item += nit;
   }
-  TFLUSH;
-#ifdef MIXKV_TIMING
-  if (threadIdx.x == 0) { mixkv_dbg[blockIdx.x * 16 + 5] = wall_clock64(); mixkv_dbg[blockIdx.x * 16 + 7] = __builtin_readcyclecounter(); }
-#endif
 }
 
 // ------------------------------------------------------------------------------------------------
