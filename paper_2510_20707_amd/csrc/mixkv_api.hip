@@ -51,6 +51,7 @@ mixkv_status make_shape(const mixkv_params *p, Shape *s) {
   s->nchunks = (s->N + s->chunk - 1) / s->chunk;
   s->Npad = s->nchunks * s->chunk;
   s->units_per_layer = s->batch * s->hkv;
+  s->nb_rows = (s->QT * 32 + 255) / 256 * 256;
   s->pool = p->pool; s->pool_k = p->pool == MIXKV_POOL_NONE ? 1 : p->pool_kernel;
   s->causal = p->causal_window; s->intrinsic = p->intrinsic;
   s->adaptive = p->budget_mode == MIXKV_BUDGET_HEAD_ADAPTIVE; s->floor_ = s->adaptive ? p->budget_floor : 0;
@@ -69,6 +70,8 @@ void carve_workspace(const Shape &s, int64_t units, Workspace *w) {
   w->part_ml = take(groups * per_group * QTR * 8);
   w->part_ksum = take(groups * per_group * s.D * 4);
   w->rbar = take((size_t)units * 4);
+  w->nb = take((size_t)units * s.nb_rows * 4);
+  w->kbarp = take((size_t)units * 64 * 16);
   // per-key rows; the slack lets 16-byte vector loads of a row's tail run past the last row
   w->invnorm = take((size_t)units * s.Npad * 4 + 256);
   w->vnorm = take((size_t)units * s.Npad * 4 + 256);

@@ -36,6 +36,7 @@ struct Shape {
   int32_t nchunks;       // ceil(N / chunk)
   int32_t Npad;          // nchunks * chunk, row length of the per-unit float arrays
   int32_t units_per_layer;
+  int32_t nb_rows;       // row length of the per-unit exponent offsets: QT*32 rounded up to 256
   int32_t pool, pool_k, causal, intrinsic, adaptive, floor_;
   float scale_log2e;     // softmax_scale * log2(e)
   float eps;
@@ -46,6 +47,8 @@ struct Workspace {
   size_t part_ml;        // float2 [slots][QT*32]            per-run (max, sum) of each softmax row, log2 domain
   size_t part_ksum;      // float  [slots][D]                per-run partial sums of normalised keys
   size_t rbar;           // float  [units]
+  size_t nb;             // float  [units][nb_rows]          -b_r per window-query row (-inf past G*W)
+  size_t kbarp;          // uint4  [units][64]               mean normalised key as MFMA operand pieces
   size_t invnorm;        // float  [units][Npad]             1 / |K_i|
   size_t vnorm;          // float  [units][Npad]             |V_i|
   size_t araw;           // float  [units][Npad]             window/group mean attention before pooling

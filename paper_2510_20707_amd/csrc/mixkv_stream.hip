@@ -98,16 +98,17 @@ __device__ __forceinline__ float piece_sumsq(const Frag &f) {
   return ss;
 }
 
-// 1 / max(sqrt(ss), 1e-30): the hardware reciprocal square root (one Newton step on top for f32
-// inputs), with the exact expression for the (wave-uniformly detected) tiny and zero norms.
+// 1 / max(sqrt(ss), 1e-30) without a branch: the hardware reciprocal square root (one Newton step
+// on top for f32 inputs); sums of squares too small for it are scaled by 2^64 first, and a zero
+// key gets 0 (its normalised key is the zero vector either way).
 template <int DT>
 __device__ __forceinline__ float inv_norm(float ss) {
-  float y = __builtin_amdgcn_rsqf(ss);
-  if constexpr (DT == MIXKV_F32) y = y * fmaf(-0.5f * ss, y * y, 1.5f);
-  if (__builtin_amdgcn_ballot_w64(!(ss >= 1e-30f)) != 0) {
-    if (!(ss >= 1e-30f)) y = 1.f / fmaxf(sqrtf(ss), 1e-30f);
-  }
-  return y;
+  const bool tiny = ss < 1e-30f;
+  const float x = tiny ? ss * 18446744073709551616.f : ss;
+  float y = __builtin_amdgcn_rsqf(x);
+  if constexpr (DT == MIXKV_F32) y = y * fmaf(-0.5f * x, y * y, 1.5f);
+  y = tiny ? y * 4294967296.f : y;
+  return ss > 0.f ? fminf(y, 1e30f) : 0.f;
 }
 
 // Merge two running (max, sum) pairs of a softmax row (log2 domain).  A pair that has seen no
@@ -277,6 +278,10 @@ __global__ __launch_bounds__(WAVES * 64, 2) void stats_kernel(Shape s, LayerInTa
   int64_t item = wg_first_item(blockIdx.x, gridDim.x, T);
   const int64_t item_end = wg_first_item(blockIdx.x + 1, gridDim.x, T);
 
+  TDECL;
+#ifdef MIXKV_TIMING_STATS
+  if (threadIdx.x == 0) { mixkv_dbg[blockIdx.x * 16 + 4] = wall_clock64(); mixkv_dbg[blockIdx.x * 16 + 6] = __builtin_readcyclecounter(); }
+#endif
   while (item < item_end) {
     const int ul = (int)(item / s.nchunks), c0 = (int)(item - (int64_t)ul * s.nchunks);
     const int nit = (int)min((int64_t)(s.nchunks - c0), item_end - item);
@@ -300,6 +305,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void stats_kernel(Shape s, LayerInTa
       fetch_tile<DT, D, WAVES>(Kb, row_bytes, tbr, N, kring_a + off, wave, lane);
       if (use_v) fetch_tile<DT, D, WAVES>(Vb, row_bytes, tbr, N, vring_a + off, wave, lane);
     };
+    TSTAMP(p0);
     lds_barrier();                                     // the previous run is done with LDS
 #pragma unroll
     for (int j = 0; j < kLead; ++j)
@@ -326,6 +332,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void stats_kernel(Shape s, LayerInTa
     // Nothing may be pending when the tile loop is entered: its waits count the requests issued
     // inside it.
     wait_vm<0>();
+    TSTAMP(p1);
+    TACC(4, p0, p1);
 
     // Sum of normalised keys: lane (lrow, lq) adds up piece lq (elements [lq*EPC, +EPC)) of the
     // rows it visits, so nothing crosses lanes before the end of the run.
@@ -335,11 +343,17 @@ __global__ __launch_bounds__(WAVES * 64, 2) void stats_kernel(Shape s, LayerInTa
 
     for (int t = 0; t < nt; ++t) {
       __builtin_amdgcn_sched_barrier(0);
+      TSTAMP(t0);
       if (use_v) wait_tile<2 * KL>(t, nt); else wait_tile<KL>(t, nt);
+      TSTAMP(t1);
       lds_barrier();
+      TSTAMP(t2);
+#ifndef MIXKV_NODMA   // developer switch: time the arithmetic alone (results are then meaningless)
       if (t + kLead < nt) request(t + kLead);
+#endif
       __builtin_amdgcn_sched_barrier(0);
 
+      TSTAMP(t3);
       const int tb = key0 + t * 32;
       const uint4 *img = kring + (t & (kRing - 1)) * TILE;
       const uint4 *vimg = vring + (t & (kRing - 1)) * TILE;
@@ -414,6 +428,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void stats_kernel(Shape s, LayerInTa
         l[q] = l[q] * fast_exp2(m[q] - mu) + sum;
         m[q] = mn;
       }
+      TSTAMP(t4);
+      TACC(0, t0, t1); TACC(1, t1, t2); TACC(2, t2, t3); TACC(3, t3, t4);
     }
 
     // ---- run partials to global
@@ -440,6 +456,103 @@ __global__ __launch_bounds__(WAVES * 64, 2) void stats_kernel(Shape s, LayerInTa
     }
     item += nit;
   }
+#ifdef MIXKV_TIMING_STATS
+  TFLUSH;
+  if (threadIdx.x == 0) { mixkv_dbg[blockIdx.x * 16 + 5] = wall_clock64(); mixkv_dbg[blockIdx.x * 16 + 7] = __builtin_readcyclecounter(); }
+#endif
+}
+
+// ------------------------------------------------------------------------------------------------
+// fold_kernel: one workgroup per unit folds the per-run partials that stats_kernel (grid G1) left
+// for the unit, in run order:
+//   * per window-query row the exponent offset -b_r, b_r = max_r + log2(sum_r * G*W), so that
+//     exp2(x - b_r) is the softmax weight already divided by the number of rows (-inf past G*W);
+//   * the mean normalised key as two rows of 16-byte pieces: row 0 its bf16 head, row 1 the bf16
+//     remainder (zero for f32), piece (c, half) of row r at index (c * 2 + half) * 2 + r;
+//   * the redundancy r (paper Sec. 3.3, Eq. 3-4).
+// Workgroup g of the stats grid owned the items [g*T1/G1, (g+1)*T1/G1) and wrote one partial per
+// unit it touched, at slot g + unit_local.  The unit's items are [first, last): the first workgroup
+// touching it is the largest g with g*T1/G1 <= first, the last one the largest g with g*T1/G1 < last.
+// ------------------------------------------------------------------------------------------------
+constexpr int kFoldThreads = 256;
+
+template <int DT, int D>
+__global__ __launch_bounds__(kFoldThreads) void fold_kernel(Shape s, LayerOutTable out, char *ws, Workspace w,
+                                                            int64_t unit0, int nunits, int G1, int64_t slot0) {
+  constexpr int EPC = Tr<DT>::EPC, NCHK = D / (2 * EPC), NW = kFoldThreads / 64;
+  __shared__ float kbar_f[D];
+  __shared__ double red_s[NW];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, ul = blockIdx.x;
+  const int64_t unit = unit0 + ul;
+  const UnitCoord uc = unit_coord(s, ul);
+  const int N = s.N, QTR = s.QT * 32;
+  const int64_t T1 = (int64_t)nunits * s.nchunks, first = (int64_t)ul * s.nchunks, last = first + s.nchunks;
+  const int g_lo = (int)(((first + 1) * G1 + T1 - 1) / T1) - 1, g_hi = (int)((last * G1 + T1 - 1) / T1) - 1;
+
+  const float2 *all_ml = reinterpret_cast<const float2 *>(ws + w.part_ml) + (slot0 + ul) * QTR;
+  float *nb = reinterpret_cast<float *>(ws + w.nb) + unit * s.nb_rows;
+  for (int r = tid; r < s.nb_rows; r += kFoldThreads) {
+    float b = INFINITY;                                // rows past G*W: weight 0
+    if (r < s.GW) {
+      float m = -INFINITY, l = 0.f;
+      for (int g0 = g_lo; g0 <= g_hi; g0 += 8) {       // batches of eight independent loads
+        float2 p[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) p[j] = (g0 + j <= g_hi) ? all_ml[(int64_t)(g0 + j) * QTR + r] : make_float2(-INFINITY, 0.f);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) ml_merge(m, l, p[j].x, p[j].y);
+      }
+      b = m + log2f(l) + log2f((float)s.GW);
+    }
+    nb[r] = -b;
+  }
+  const float *all_ks = reinterpret_cast<const float *>(ws + w.part_ksum) + (slot0 + ul) * D;
+  double sq = 0.0;
+  for (int d = tid; d < D; d += kFoldThreads) {
+    float a = 0.f;
+    for (int g0 = g_lo; g0 <= g_hi; g0 += 8) {
+      float p[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) p[j] = (g0 + j <= g_hi) ? all_ks[(int64_t)(g0 + j) * D + d] : 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) a += p[j];
+    }
+    kbar_f[d] = a / (float)N;
+    sq += (double)a * (double)a;
+  }
+#pragma unroll
+  for (int sft = 32; sft >= 1; sft >>= 1) sq += __shfl_xor(sq, sft);
+  if (lane == 0) red_s[wave] = sq;
+  __syncthreads();
+  if (tid == 0) {
+    double tot = 0.0;
+    for (int wv = 0; wv < NW; ++wv) tot += red_s[wv];
+    // Eq. 4: (T^2 |Kbar|^2 - T) / (T (T - 1)) with T^2 |Kbar|^2 = |sum of normalised keys|^2
+    const float r = (float)((tot - (double)N) / ((double)N * (double)(N - 1)));
+    reinterpret_cast<float *>(ws + w.rbar)[unit] = r;
+    float *red_out = out.l[uc.layer].redundancy;
+    if (red_out) red_out[uc.b * s.hkv + uc.h] = r;
+  }
+  uint4 *kbarp = reinterpret_cast<uint4 *>(ws + w.kbarp) + unit * (NCHK * 4);
+  for (int p = tid; p < NCHK * 4; p += kFoldThreads) {
+    const int row = p & 1, hf = (p >> 1) & 1, c = p >> 2;
+    const float *src = kbar_f + (2 * c + hf) * EPC;
+    Frag f;
+    f.q = make_uint4(0, 0, 0, 0);
+    if constexpr (DT == MIXKV_BF16) {
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) {
+        float v = src[e];
+        uint16_t hi = f32_to_bf16_rne(v);
+        uint16_t bits = hi;
+        if (row == 1) bits = f32_to_bf16_rne(v - __uint_as_float((uint32_t)hi << 16));
+        f.u[e >> 1] |= (uint32_t)bits << ((e & 1) * 16);
+      }
+    } else {
+      if (row == 0) f.q = *reinterpret_cast<const uint4 *>(src);
+    }
+    kbarp[p] = f.q;
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -452,38 +565,38 @@ __global__ __launch_bounds__(WAVES * 64, 2) void stats_kernel(Shape s, LayerInTa
 // query block has a spare tile they sit in its rows 0 and 1 and cost nothing; otherwise every wave
 // applies a separate mean-key tile to every WAVES-th key tile.
 //
-// At the start of a run the workgroup folds the per-run partials that stats_kernel (grid G1) left
-// for its unit, in run order: per-row exponent offsets b_r = max_r + log2(sum_r * G*W), the mean
-// normalised key, and - in the workgroup that owns the unit's first chunk - the redundancy r
-// (paper Sec. 3.3, Eq. 3-4).  The kernel boundary orders this after all of stats_kernel.
+// The exponent offsets and the mean key come from fold_kernel.  The fragments of the next key tile
+// are read from LDS into a second set of registers while the current tile is being worked on.
 // ------------------------------------------------------------------------------------------------
 template <int DT, int D, int WAVES, int TQ>
 __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTable in, LayerOutTable out, char *ws,
-                                                            Workspace w, int64_t unit0, int nunits, int G1,
-                                                            int64_t slot0) {
+                                                            Workspace w, int64_t unit0, int nunits) {
   constexpr int EB = Tr<DT>::EB, EPC = Tr<DT>::EPC, NCHK = D / (2 * EPC), PPR = D * EB / 16;
   constexpr int NT = WAVES * 64, KT = chunk_tiles(DT, D), CH = KT * 32, TILE = 32 * PPR;
   constexpr int KL = (TILE / 64 + WAVES - 1) / WAVES;        // requests per wave and tile
   __shared__ uint4 kring[kRing * TILE];
   __shared__ uint4 kbar_s[NCHK * 4];                         // mean-key rows 0/1 x halves, 16-byte pieces
   __shared__ float cs_s[2 * WAVES * CH];                     // [2][WAVES][CH] partial column sums
-  __shared__ float nb_s[WAVES * TQ * 32];                    // -b_r per query row (-inf rows give weight 0)
-  __shared__ float kbar_f[D];                                // mean normalised key
-  __shared__ double red_s[WAVES];
+  __shared__ int lim_s[WAVES * TQ * 32];                     // last key each query row attends to
 
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps its address math scalar
-  const int N = s.N, Nc = s.Nc, QTR = s.QT * 32;
+  const int N = s.N, Nc = s.Nc;
   const float c2 = s.scale_log2e;
   const int free_limit = s.causal ? Nc : N - 1;
   // the mean key rides in rows 0/1 of the first tile past the live rows, if the block has one
   const bool spare = s.QT < WAVES * TQ;
   const int kb_wave = s.QT / TQ, kb_q = s.QT % TQ;
   const uint32_t kring_a = lds_base_of(kring);
+  for (int r = tid; r < WAVES * TQ * 32; r += NT) lim_s[r] = s.causal ? Nc + r % s.W : N - 1;
   const int64_t T = (int64_t)nunits * s.nchunks;
   int64_t item = wg_first_item(blockIdx.x, gridDim.x, T);
   const int64_t item_end = wg_first_item(blockIdx.x + 1, gridDim.x, T);
 
+  TDECL;
+#if defined(MIXKV_TIMING) && !defined(MIXKV_TIMING_STATS)
+  if (threadIdx.x == 0) { mixkv_dbg[blockIdx.x * 16 + 4] = wall_clock64(); mixkv_dbg[blockIdx.x * 16 + 6] = __builtin_readcyclecounter(); }
+#endif
   while (item < item_end) {
     const int ul = (int)(item / s.nchunks), c0 = (int)(item - (int64_t)ul * s.nchunks);
     const int nit = (int)min((int64_t)(s.nchunks - c0), item_end - item);
@@ -495,120 +608,52 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
     const int64_t row_bytes = L.sn * EB;
     float *araw = reinterpret_cast<float *>(ws + w.araw) + unit * s.Npad;
     float *kdot = reinterpret_cast<float *>(ws + w.sdiv) + unit * s.Npad;   // K_i . Kbar, not yet normalised
+    const float *nb = reinterpret_cast<const float *>(ws + w.nb) + unit * s.nb_rows;
+    const uint4 *kbarp = reinterpret_cast<const uint4 *>(ws + w.kbarp) + unit * (NCHK * 4);
     const int key0 = c0 * CH;                                        // first key of the run
     const int nt = min(nit * KT, (N - key0 + 31) / 32);              // tiles of the run that hold keys
 
-    __syncthreads();                                   // the previous run is done with LDS
+    auto request = [&](int tr) {
+      fetch_tile<DT, D, WAVES>(Kb, row_bytes, key0 + tr * 32, N, kring_a + (uint32_t)(tr & (kRing - 1)) * (TILE * 16),
+                               wave, lane);
+    };
+    TSTAMP(p0);
+    lds_barrier();                                     // the previous run is done with LDS
+    TSTAMP(p1);
 #pragma unroll
-    for (int j = 0; j < kLead; ++j)
-      if (j < nt) fetch_tile<DT, D, WAVES>(Kb, row_bytes, key0 + j * 32, N, kring_a + j * (TILE * 16), wave, lane);
+    for (int j = 0; j <= kLead; ++j)
+      if (j < nt) request(j);
 
-    // this wave's query rows, requested now and put into fragment form after the fold below
+    // query tiles in fragment form (tiles past QT are zero, except for the two mean-key rows) and
+    // the exponent offset of each of the lane's 16 rows per tile
     Frag qf[TQ][NCHK];
-#pragma unroll
-    for (int q = 0; q < TQ; ++q) {
-      const int row = (wave * TQ + q) * 32 + l32;
-      const char *qrow = Qb + ((int64_t)(row < s.GW ? row : 0) * D) * EB + half * 16;
-#pragma unroll
-      for (int c = 0; c < NCHK; ++c) qf[q][c].q = *reinterpret_cast<const uint4 *>(qrow + c * 32);
-    }
-
-    // ---- fold the partials of stats_kernel for this unit.  Workgroup g of its grid owned the items
-    // [g*T1/G1, (g+1)*T1/G1) and wrote one partial per unit it touched, at slot g + unit_local.
-    // The unit's items are [first, last): the first workgroup touching it is the largest g with
-    // g*T1/G1 <= first, the last one the largest g with g*T1/G1 < last.
-    {
-      const int64_t T1 = (int64_t)nunits * s.nchunks, first = (int64_t)ul * s.nchunks, last = first + s.nchunks;
-      const int g_lo = (int)(((first + 1) * G1 + T1 - 1) / T1) - 1, g_hi = (int)((last * G1 + T1 - 1) / T1) - 1;
-      const float2 *all_ml = reinterpret_cast<const float2 *>(ws + w.part_ml) + (slot0 + ul) * QTR;
-      for (int r = tid; r < WAVES * TQ * 32; r += NT) {
-        float b = INFINITY;                            // rows past G*W: weight 0
-        if (r < s.GW) {
-          float m = -INFINITY, l = 0.f;
-          for (int g0 = g_lo; g0 <= g_hi; g0 += 4) {   // batches of four independent loads
-            float2 p[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) p[j] = (g0 + j <= g_hi) ? all_ml[(int64_t)(g0 + j) * QTR + r] : make_float2(-INFINITY, 0.f);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) ml_merge(m, l, p[j].x, p[j].y);
-          }
-          b = m + log2f(l) + log2f((float)s.GW);
-        }
-        nb_s[r] = -b;
-      }
-      const float *all_ks = reinterpret_cast<const float *>(ws + w.part_ksum) + (slot0 + ul) * D;
-      double sq = 0.0;
-      for (int d = tid; d < D; d += NT) {
-        float a = 0.f;
-        for (int g0 = g_lo; g0 <= g_hi; g0 += 4) {
-          float p[4];
-#pragma unroll
-          for (int j = 0; j < 4; ++j) p[j] = (g0 + j <= g_hi) ? all_ks[(int64_t)(g0 + j) * D + d] : 0.f;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) a += p[j];
-        }
-        kbar_f[d] = a / (float)N;
-        sq += (double)a * (double)a;
-      }
-      if (c0 == 0) {                                   // one workgroup per unit publishes r
-#pragma unroll
-        for (int sft = 32; sft >= 1; sft >>= 1) sq += __shfl_xor(sq, sft);
-        if (lane == 0) red_s[wave] = sq;
-      }
-    }
-    __syncthreads();                                   // kbar_f, nb_s, red_s visible
-    if (c0 == 0 && tid == 0) {
-      double tot = 0.0;
-      for (int wv = 0; wv < WAVES; ++wv) tot += red_s[wv];
-      // Eq. 4: (T^2 |Kbar|^2 - T) / (T (T - 1)) with T^2 |Kbar|^2 = |sum of normalised keys|^2
-      const float r = (float)((tot - (double)N) / ((double)N * (double)(N - 1)));
-      reinterpret_cast<float *>(ws + w.rbar)[unit] = r;
-      float *red_out = out.l[uc.layer].redundancy;
-      if (red_out) red_out[uc.b * s.hkv + uc.h] = r;
-    }
-
-    // The mean key as two rows of 16-byte pieces: row 0 carries the mean key (its bf16 head), row 1
-    // the bf16 remainder (zero for f32).  Piece (c, half) of row r sits at kbar_s[(c * 2 + half) * 2 + r].
-    for (int p = tid; p < NCHK * 4; p += NT) {
-      const int row = p & 1, hf = (p >> 1) & 1, c = p >> 2;
-      const float *src = kbar_f + (2 * c + hf) * EPC;
-      Frag f;
-      f.q = make_uint4(0, 0, 0, 0);
-      if constexpr (DT == MIXKV_BF16) {
-#pragma unroll
-        for (int e = 0; e < EPC; ++e) {
-          float v = src[e];
-          uint16_t hi = f32_to_bf16_rne(v);
-          uint16_t bits = hi;
-          if (row == 1) bits = f32_to_bf16_rne(v - __uint_as_float((uint32_t)hi << 16));
-          f.u[e >> 1] |= (uint32_t)bits << ((e & 1) * 16);
-        }
-      } else {
-        if (row == 0) f.q = *reinterpret_cast<const uint4 *>(src);
-      }
-      kbar_s[p] = f.q;
-    }
-    __syncthreads();                                   // kbar_s visible; every request so far has landed
-
-    // query tiles in fragment form (tiles past QT are zero, except for the two mean-key rows), the
-    // exponent offset of each of the lane's 16 rows per tile, and the last key each row attends to
     float nbv[TQ][16];
 #pragma unroll
     for (int q = 0; q < TQ; ++q) {
       const int row = (wave * TQ + q) * 32 + l32;
       const bool live = row < s.GW;
       const bool mean_rows = spare && wave == kb_wave && q == kb_q && l32 < 2;
+      const char *qrow = Qb + ((int64_t)(live ? row : 0) * D) * EB + half * 16;
 #pragma unroll
       for (int c = 0; c < NCHK; ++c) {
-        uint4 mk = kbar_s[(c * 2 + half) * 2 + (l32 & 1)];
-        qf[q][c].q = live ? qf[q][c].q : (mean_rows ? mk : make_uint4(0, 0, 0, 0));
+        const uint4 *src = live ? reinterpret_cast<const uint4 *>(qrow + c * 32) : kbarp + (c * 2 + half) * 2 + (l32 & 1);
+        const uint4 v = *src;
+        qf[q][c].q = (live || mean_rows) ? v : make_uint4(0, 0, 0, 0);
       }
 #pragma unroll
       for (int k4 = 0; k4 < 4; ++k4) {
-        const float4 nb = *reinterpret_cast<const float4 *>(&nb_s[(wave * TQ + q) * 32 + 8 * k4 + 4 * half]);
-        nbv[q][4 * k4 + 0] = nb.x; nbv[q][4 * k4 + 1] = nb.y; nbv[q][4 * k4 + 2] = nb.z; nbv[q][4 * k4 + 3] = nb.w;
+        const float4 v = *reinterpret_cast<const float4 *>(nb + (wave * TQ + q) * 32 + 8 * k4 + 4 * half);
+        nbv[q][4 * k4 + 0] = v.x; nbv[q][4 * k4 + 1] = v.y; nbv[q][4 * k4 + 2] = v.z; nbv[q][4 * k4 + 3] = v.w;
       }
     }
+    if (!spare)
+      for (int p = tid; p < NCHK * 4; p += NT) kbar_s[p] = kbarp[p];
+    // Nothing may be pending when the tile loop is entered: its waits count the requests issued
+    // inside it.
+    wait_vm<0>();
+    lds_barrier();                                     // tiles 0 .. kLead of the run (and kbar_s) are visible
+    TSTAMP(p2);
+    TACC(4, p0, p1); TACC(5, p1, p2);
 
     // add the waves' partial column sums of chunk `chunk` (buffer pb) in a fixed order
     auto flush_colsums = [&](int chunk, int pb) {
@@ -620,23 +665,32 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
       }
     };
 
-    for (int t = 0; t < nt; ++t) {
+    // One tile step.  At its start the images of tiles <= t + 1 are visible to every wave; the
+    // fragments of tile t are already in registers (kf), those of tile t + 1 are read into kfn
+    // under this tile's arithmetic, and tile t + 1 + kLead is requested into the image of tile t,
+    // which nobody reads any more.
+    auto step = [&](int t, Frag (&kf)[NCHK], Frag (&kfn)[NCHK]) {
       __builtin_amdgcn_sched_barrier(0);
-      wait_tile<KL>(t, nt);
-      lds_barrier();
-      if (t + kLead < nt)
-        fetch_tile<DT, D, WAVES>(Kb, row_bytes, key0 + (t + kLead) * 32, N,
-                                 kring_a + (uint32_t)((t + kLead) & (kRing - 1)) * (TILE * 16), wave, lane);
+      TSTAMP(t0);
+      wait_tile<KL>(t + 1, nt);
+      TSTAMP(t1);
+      lds_barrier();                                   // every wave holds the fragments of tile t: its image is free
+      TSTAMP(t2);
+#ifndef MIXKV_NODMA   // developer switch: time the arithmetic alone (results are then meaningless)
+      if (t + 1 + kLead < nt) request(t + 1 + kLead);
+#endif
+      if (t + 1 < nt) {
+        const uint4 *imgn = kring + ((t + 1) & (kRing - 1)) * TILE;
+#pragma unroll
+        for (int c = 0; c < NCHK; ++c) kfn[c].q = read_key_frag<DT, D>(imgn, 0, c, l32, half);
+      }
       __builtin_amdgcn_sched_barrier(0);
+      TSTAMP(t3);
       const int k = t % KT, g = t / KT;                // tile within its chunk, chunk within the run
       if (k == 0 && g > 0) flush_colsums(c0 + g - 1, (g - 1) & 1);
       float *cs = cs_s + ((g & 1) * WAVES + wave) * CH;
       const int tb = key0 + t * 32, key = tb + l32;
-      const uint4 *img = kring + (t & (kRing - 1)) * TILE;
 
-      Frag kf[NCHK];
-#pragma unroll
-      for (int c = 0; c < NCHK; ++c) kf[c].q = read_key_frag<DT, D>(img, 0, c, l32, half);
       f32x16 acc[TQ];
 #pragma unroll
       for (int q = 0; q < TQ; ++q)
@@ -678,22 +732,39 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
             const int row = (wave * TQ + q) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-            const int lim = s.causal ? Nc + row % s.W : N - 1;
-            acc[q][i] = (key <= lim) ? acc[q][i] : -INFINITY;
+            acc[q][i] = (key <= lim_s[row]) ? acc[q][i] : -INFINITY;
           }
       }
-      float colsum = 0.f;
+      float cs4[4] = {0.f, 0.f, 0.f, 0.f};             // four chains: the adds do not wait on each other
 #pragma unroll
       for (int q = 0; q < TQ; ++q)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) colsum += fast_exp2(fmaf(acc[q][i], c2, nbv[q][i]));
+        for (int i = 0; i < 16; ++i) cs4[i & 3] += fast_exp2(fmaf(acc[q][i], c2, nbv[q][i]));
+      float colsum = (cs4[0] + cs4[1]) + (cs4[2] + cs4[3]);
       colsum += __shfl_xor(colsum, 32);
       if (half == 0) cs[k * 32 + l32] = colsum;
+      TSTAMP(t4);
+      TACC(0, t0, t1); TACC(1, t1, t2); TACC(2, t2, t3); TACC(3, t3, t4);
+    };
+
+    Frag kfa[NCHK], kfb[NCHK];
+#pragma unroll
+    for (int c = 0; c < NCHK; ++c) kfa[c].q = read_key_frag<DT, D>(kring, 0, c, l32, half);   // tile 0
+    for (int t = 0; t < nt; t += 2) {
+      step(t, kfa, kfb);
+      if (t + 1 < nt) step(t + 1, kfb, kfa);
     }
+    TSTAMP(e0);
     lds_barrier();
     flush_colsums(c0 + (nt - 1) / KT, ((nt - 1) / KT) & 1);
+    TSTAMP(e1);
+    TACC(6, e0, e1);
     item += nit;
   }
+#if defined(MIXKV_TIMING) && !defined(MIXKV_TIMING_STATS)
+  TFLUSH;
+  if (threadIdx.x == 0) { mixkv_dbg[blockIdx.x * 16 + 5] = wall_clock64(); mixkv_dbg[blockIdx.x * 16 + 7] = __builtin_readcyclecounter(); }
+#endif
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -728,8 +799,12 @@ static hipError_t launch_stats_c(const Shape &s, const LayerInTable &in, char *w
 template <int DT, int D, int WAVES, int TQ>
 static hipError_t launch_attn_c(const Shape &s, const LayerInTable &in, const LayerOutTable &out, char *ws,
                                 const Workspace &w, int64_t unit0, int nunits, int grid, int64_t slot0, hipStream_t st) {
+  auto fold = fold_kernel<DT, D>;
+  hipLaunchKernelGGL(fold, dim3(nunits), dim3(kFoldThreads), 0, st, s, out, ws, w, unit0, nunits, grid, slot0);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
   auto kern = attn_kernel<DT, D, WAVES, TQ>;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES * 64), 0, st, s, in, out, ws, w, unit0, nunits, grid, slot0);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES * 64), 0, st, s, in, out, ws, w, unit0, nunits);
   return hipGetLastError();
 }
 
