@@ -10,7 +10,7 @@ int stream_chunk_keys(int dtype, int D);
 int max_adaptive_heads();
 bool mixsel_supported(const Shape &s);
 hipError_t launch_mixsel(const Shape &s, bool select, const LayerOutTable &out, char *ws, const Workspace &w,
-                         int64_t unit0, int nunits, hipStream_t st);
+                         int64_t unit0, int nunits, const LayerInTable &in, int gather_eb, hipStream_t st);
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -179,6 +179,7 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
     // only if somebody reads them (the caller, or the separate selection kernels).
     const bool fused = (stages & kScore) && mixsel_supported(s);
     const bool fused_select = fused && (stages & kSelect) && !s.adaptive;
+    const bool fused_gather = fused_select && (stages & kGather);   // the selecting workgroup also copies its rows
     for (int l = 0; l < nl; ++l) {
       if (in) {
         const mixkv_layer_in &li = in[l0 + l];
@@ -197,13 +198,13 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
       ok(timed(0, [&] { return launch_stats(s, params->dtype, ti, ws, w, unit0, nunits, grid, slot0, stream); })) &&
           ok(timed(1, [&] { return launch_attn(s, params->dtype, ti, to, ws, w, unit0, nunits, grid, slot0, stream); })) &&
           ok(timed(2, [&] {
-            return fused ? launch_mixsel(s, fused_select, to, ws, w, unit0, nunits, stream)
+            return fused ? launch_mixsel(s, fused_select, to, ws, w, unit0, nunits, ti, fused_gather ? eb : 0, stream)
                          : launch_mix(s, to, ws, w, unit0, nunits, stream);
           }));
     }
     if (result == MIXKV_OK && (stages & kSelect) && !fused_select)
       ok(timed(3, [&] { return launch_select(s, to, nl, stream); }));
-    if (result == MIXKV_OK && (stages & kGather))
+    if (result == MIXKV_OK && (stages & kGather) && !fused_gather)
       ok(timed(4, [&] { return launch_gather(s, params->dtype, ti, to, nl, stream); }));
     if (result != MIXKV_OK) break;
   }

@@ -118,7 +118,7 @@ __device__ __forceinline__ void hist_add(int *hist, int bin, bool on) {
 
 template <int THREADS, int EPT, bool SELECT>
 __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable out, char *ws, Workspace w,
-                                                           int64_t unit0) {
+                                                           int64_t unit0, LayerInTable in, int gather_eb) {
   constexpr int NW = THREADS / 64;
   extern __shared__ float a_s[];                        // [Nc] raw window attention of this head
   __shared__ MsScratch sc;
@@ -335,12 +335,33 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
   }
   MS_STAMP(6);
   for (int wv = tid; wv < s.W; wv += THREADS) idx[Bp + wv] = Nc + wv;
+  const int h = bh % s.hkv, b = bh / s.hkv;
   if (tid == 0) {
-    const int h = bh % s.hkv, b = bh / s.hkv;
     O.counts[bh] = s.B;
     if (O.offsets) {
       O.offsets[b * (s.hkv + 1) + h] = h * s.B;
       if (h == s.hkv - 1) O.offsets[b * (s.hkv + 1) + s.hkv] = s.hkv * s.B;
+    }
+  }
+  // ---- gather of the kept rows (Sec. 3.1, the compacted cache), if asked for: gather_eb is the
+  // element size in bytes, 0 to skip.  16 bytes per thread and step; the head's indices are read
+  // back after a workgroup barrier (same compute unit, so they are visible).
+  if (gather_eb > 0) {
+    __syncthreads();
+    const LayerIn L = in.l[layer];
+    const int ppr = s.D * gather_eb / 16;
+    const char *Kh = reinterpret_cast<const char *>(L.K) + ((int64_t)b * L.sb + (int64_t)h * L.sh) * gather_eb;
+    const char *Vh = reinterpret_cast<const char *>(L.V) + ((int64_t)b * L.sb + (int64_t)h * L.sh) * gather_eb;
+    char *Ko = reinterpret_cast<char *>(O.K_out) + (int64_t)bh * s.B * s.D * gather_eb;
+    char *Vo = reinterpret_cast<char *>(O.V_out) + (int64_t)bh * s.B * s.D * gather_eb;
+    for (int p = tid; p < s.B * ppr; p += THREADS) {
+      const int row = p / ppr, piece = p - row * ppr;
+      const int src = min(max(idx[row], 0), N - 1);    // indices come from the selection above; the clamp only guards the load
+      const int64_t so = (int64_t)src * L.sn * gather_eb + piece * 16;
+      const uint4 kv = *reinterpret_cast<const uint4 *>(Kh + so);
+      const uint4 vv = *reinterpret_cast<const uint4 *>(Vh + so);
+      *reinterpret_cast<uint4 *>(Ko + (int64_t)p * 16) = kv;
+      *reinterpret_cast<uint4 *>(Vo + (int64_t)p * 16) = vv;
     }
   }
 }
@@ -351,32 +372,33 @@ bool mixsel_supported(const Shape &s) { return s.Nc <= kMsMaxThreads * 32 && (si
 
 template <int THREADS, int EPT>
 static hipError_t launch_mixsel_e(const Shape &s, bool select, const LayerOutTable &out, char *ws, const Workspace &w,
-                                  int64_t unit0, int nunits, hipStream_t st) {
+                                  int64_t unit0, int nunits, const LayerInTable &in, int gather_eb, hipStream_t st) {
   const size_t lds = (size_t)(s.Nc + s.Nc / 32 + 1) * 4;
   if (select) {
     auto kern = mixsel_kernel<THREADS, EPT, true>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(nunits), dim3(THREADS), lds, st, s, out, ws, w, unit0);
+    hipLaunchKernelGGL(kern, dim3(nunits), dim3(THREADS), lds, st, s, out, ws, w, unit0, in, gather_eb);
   } else {
     auto kern = mixsel_kernel<THREADS, EPT, false>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(nunits), dim3(THREADS), lds, st, s, out, ws, w, unit0);
+    hipLaunchKernelGGL(kern, dim3(nunits), dim3(THREADS), lds, st, s, out, ws, w, unit0, in, 0);
   }
   return hipGetLastError();
 }
 
-// Mix (and, with `select`, fixed-budget selection) for `nunits` units starting at unit0.  Few
-// waves per workgroup keep the many block-wide steps cheap; long heads get more threads.
+// Mix (and, with `select`, fixed-budget selection; with `gather_eb` > 0 also the gather of the
+// kept rows, gather_eb being the element size) for `nunits` units starting at unit0.  Few waves per
+// workgroup keep the many block-wide steps cheap; long heads get more threads.
 hipError_t launch_mixsel(const Shape &s, bool select, const LayerOutTable &out, char *ws, const Workspace &w,
-                         int64_t unit0, int nunits, hipStream_t st) {
+                         int64_t unit0, int nunits, const LayerInTable &in, int gather_eb, hipStream_t st) {
   const int nc = s.Nc;
-  if (nc <= 256 * 8) return launch_mixsel_e<256, 8>(s, select, out, ws, w, unit0, nunits, st);
-  if (nc <= 512 * 8) return launch_mixsel_e<512, 8>(s, select, out, ws, w, unit0, nunits, st);
-  if (nc <= 1024 * 8) return launch_mixsel_e<1024, 8>(s, select, out, ws, w, unit0, nunits, st);
-  if (nc <= 1024 * 16) return launch_mixsel_e<1024, 16>(s, select, out, ws, w, unit0, nunits, st);
-  return launch_mixsel_e<1024, 32>(s, select, out, ws, w, unit0, nunits, st);
+  if (nc <= 256 * 8) return launch_mixsel_e<256, 8>(s, select, out, ws, w, unit0, nunits, in, gather_eb, st);
+  if (nc <= 512 * 8) return launch_mixsel_e<512, 8>(s, select, out, ws, w, unit0, nunits, in, gather_eb, st);
+  if (nc <= 1024 * 8) return launch_mixsel_e<1024, 8>(s, select, out, ws, w, unit0, nunits, in, gather_eb, st);
+  if (nc <= 1024 * 16) return launch_mixsel_e<1024, 16>(s, select, out, ws, w, unit0, nunits, in, gather_eb, st);
+  return launch_mixsel_e<1024, 32>(s, select, out, ws, w, unit0, nunits, in, gather_eb, st);
 }
 
 }  // namespace mixkv
