@@ -10,7 +10,7 @@ int stream_chunk_keys(int dtype, int D);
 int max_adaptive_heads();
 bool mixsel_supported(const Shape &s);
 hipError_t launch_mixsel(const Shape &s, bool select, const LayerOutTable &out, char *ws, const Workspace &w,
-                         int64_t unit0, int nunits, const LayerInTable &in, int gather_eb, hipStream_t st);
+                         int64_t unit0, int nunits, const LayerInTable &in, int gather_eb, int cand_m, hipStream_t st);
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -77,6 +77,8 @@ void carve_workspace(const Shape &s, int64_t units, Workspace *w) {
   w->vnorm = take((size_t)units * s.Npad * 4 + 256);
   w->araw = take((size_t)units * s.Npad * 4 + 256);
   w->sdiv = take((size_t)units * s.Npad * 4 + 256);
+  w->cand_idx = take(s.adaptive ? (size_t)units * kMaxCandPerHead * 4 : 0);
+  w->cand_key = take(s.adaptive ? (size_t)units * kMaxCandPerHead * 4 : 0);
   w->scores = take((size_t)units * s.N * 4);
   w->total = off;
 }
@@ -180,6 +182,8 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
     const bool fused = (stages & kScore) && mixsel_supported(s);
     const bool fused_select = fused && (stages & kSelect) && !s.adaptive;
     const bool fused_gather = fused_select && (stages & kGather);   // the selecting workgroup also copies its rows
+    // head-adaptive mode: the fused kernel hands every head's best candidates to a small split kernel
+    const int cand_m = (fused && (stages & kSelect) && s.adaptive) ? adaptive_candidates(s) : 0;
     for (int l = 0; l < nl; ++l) {
       if (in) {
         const mixkv_layer_in &li = in[l0 + l];
@@ -187,7 +191,7 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
       }
       const mixkv_layer_out &lo = out[l0 + l];
       float *scores = lo.scores;
-      if (!scores && !fused_select)
+      if (!scores && !fused_select && cand_m == 0)
         scores = reinterpret_cast<float *>(ws + w.scores) + (unit0 + (int64_t)l * s.units_per_layer) * s.N;
       to.l[l] = LayerOut{scores, lo.redundancy, lo.indices, lo.counts, lo.offsets, lo.K_out, lo.V_out};
     }
@@ -198,12 +202,15 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
       ok(timed(0, [&] { return launch_stats(s, params->dtype, ti, ws, w, unit0, nunits, grid, slot0, stream); })) &&
           ok(timed(1, [&] { return launch_attn(s, params->dtype, ti, to, ws, w, unit0, nunits, grid, slot0, stream); })) &&
           ok(timed(2, [&] {
-            return fused ? launch_mixsel(s, fused_select, to, ws, w, unit0, nunits, ti, fused_gather ? eb : 0, stream)
+            return fused ? launch_mixsel(s, fused_select || cand_m > 0, to, ws, w, unit0, nunits, ti,
+                                         fused_gather ? eb : 0, cand_m, stream)
                          : launch_mix(s, to, ws, w, unit0, nunits, stream);
           }));
     }
     if (result == MIXKV_OK && (stages & kSelect) && !fused_select)
-      ok(timed(3, [&] { return launch_select(s, to, nl, stream); }));
+      ok(timed(3, [&] {
+        return cand_m > 0 ? launch_select_candidates(s, to, ws, w, unit0, nl, cand_m, stream) : launch_select(s, to, nl, stream);
+      }));
     if (result == MIXKV_OK && (stages & kGather) && !fused_gather)
       ok(timed(4, [&] { return launch_gather(s, params->dtype, ti, to, nl, stream); }));
     if (result != MIXKV_OK) break;

@@ -10,6 +10,8 @@ constexpr int kWave = 64;
 constexpr int kTileKeys = 32;          // keys per MFMA tile
 constexpr int kLayersPerLaunch = 32;   // pointer-table entries that fit in one kernel-argument block
 constexpr int kSelectThreads = 1024;
+constexpr int kMaxCandPerHead = 1024;   // head-adaptive budgets: candidates a head hands to the budget split
+constexpr int kMaxCandPerGroup = 4096;  // ... and all heads of one (layer, batch item) together
 constexpr int kMaxStreamGrid = 1024;    // upper bound on the workgroups of a streaming kernel launch
 
 // Per-layer device pointers handed to the kernels by value.
@@ -53,6 +55,8 @@ struct Workspace {
   size_t vnorm;          // float  [units][Npad]             |V_i|
   size_t araw;           // float  [units][Npad]             window/group mean attention before pooling
   size_t sdiv;           // float  [units][Npad]             K_i . Kbar (the mix kernel applies -1/|K_i|)
+  size_t cand_idx;       // int32  [units][kMaxCandPerHead]  adaptive mode: every head's best candidates, ascending
+  size_t cand_key;       // uint32 [units][kMaxCandPerHead]  ... and their order-preserving keys
   size_t scores;         // float  [units][N]                used when the caller passes no scores buffer
   size_t total;
 };
@@ -72,6 +76,10 @@ hipError_t launch_attn(const Shape &s, int dtype, const LayerInTable &in, const 
 hipError_t launch_mix(const Shape &s, const LayerOutTable &out, char *ws, const Workspace &w, int64_t unit0,
                       int nunits, hipStream_t st);
 hipError_t launch_select(const Shape &s, const LayerOutTable &out, int nlayers, hipStream_t st);
+// Head-adaptive budget split from the per-head candidate lists (cand_m entries each) in the workspace.
+int adaptive_candidates(const Shape &s);   // cand_m, or 0 if the lists would be too long
+hipError_t launch_select_candidates(const Shape &s, const LayerOutTable &out, char *ws, const Workspace &w, int64_t unit0,
+                                    int nlayers, int cand_m, hipStream_t st);
 hipError_t launch_gather(const Shape &s, int dtype, const LayerInTable &in, const LayerOutTable &out, int nlayers,
                          hipStream_t st);
 

@@ -118,7 +118,7 @@ __device__ __forceinline__ void hist_add(int *hist, int bin, bool on) {
 
 template <int THREADS, int EPT, bool SELECT>
 __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable out, char *ws, Workspace w,
-                                                           int64_t unit0, LayerInTable in, int gather_eb) {
+                                                           int64_t unit0, LayerInTable in, int gather_eb, int cand_m) {
   constexpr int NW = THREADS / 64;
   extern __shared__ float a_s[];                        // [Nc] raw window attention of this head
   __shared__ MsScratch sc;
@@ -253,9 +253,15 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
   }
   if constexpr (!SELECT) return;
 
-  // ---- fixed-budget TopB': the B' candidates with the largest s_comp, ties to the smaller index
-  int32_t *idx = O.indices + (int64_t)bh * s.B;
-  const int Bp = s.Bp;
+  // ---- TopB': the B' candidates with the largest s_comp, ties to the smaller index.  In fixed
+  // budget mode B' = B - W and the indices are the head's final ones.  With cand_m > 0 (head-adaptive
+  // mode) the head's best cand_m candidates go to the workspace with their keys instead: no head
+  // can end up keeping more than that, so the budget split only has to look at those.
+  const bool cand = cand_m > 0;
+  int32_t *idx = cand ? reinterpret_cast<int32_t *>(ws + w.cand_idx) + unit * kMaxCandPerHead
+                      : O.indices + (int64_t)bh * s.B;
+  uint32_t *ckey = reinterpret_cast<uint32_t *>(ws + w.cand_key) + unit * kMaxCandPerHead;
+  const int Bp = cand ? cand_m : s.Bp;
   if (Bp > 0) {
     uint32_t key[EPT];
     uint32_t kmin = 0xffffffffu, kmax = 0;
@@ -327,13 +333,17 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
         bool sel = key[e] > tau;
         if (key[e] == tau) sel = seen++ < k;
         if (sel) {
-          if (pos < Bp) idx[pos] = base + e;
+          if (pos < Bp) {
+            idx[pos] = base + e;
+            if (cand) ckey[pos] = key[e];
+          }
           ++pos;
         }
       }
     }
   }
   MS_STAMP(6);
+  if (cand) return;
   for (int wv = tid; wv < s.W; wv += THREADS) idx[Bp + wv] = Nc + wv;
   const int h = bh % s.hkv, b = bh / s.hkv;
   if (tid == 0) {
@@ -372,33 +382,35 @@ bool mixsel_supported(const Shape &s) { return s.Nc <= kMsMaxThreads * 32 && (si
 
 template <int THREADS, int EPT>
 static hipError_t launch_mixsel_e(const Shape &s, bool select, const LayerOutTable &out, char *ws, const Workspace &w,
-                                  int64_t unit0, int nunits, const LayerInTable &in, int gather_eb, hipStream_t st) {
+                                  int64_t unit0, int nunits, const LayerInTable &in, int gather_eb, int cand_m,
+                                  hipStream_t st) {
   const size_t lds = (size_t)(s.Nc + s.Nc / 32 + 1) * 4;
   if (select) {
     auto kern = mixsel_kernel<THREADS, EPT, true>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(nunits), dim3(THREADS), lds, st, s, out, ws, w, unit0, in, gather_eb);
+    hipLaunchKernelGGL(kern, dim3(nunits), dim3(THREADS), lds, st, s, out, ws, w, unit0, in, gather_eb, cand_m);
   } else {
     auto kern = mixsel_kernel<THREADS, EPT, false>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(nunits), dim3(THREADS), lds, st, s, out, ws, w, unit0, in, 0);
+    hipLaunchKernelGGL(kern, dim3(nunits), dim3(THREADS), lds, st, s, out, ws, w, unit0, in, 0, 0);
   }
   return hipGetLastError();
 }
 
-// Mix (and, with `select`, fixed-budget selection; with `gather_eb` > 0 also the gather of the
+// Mix (and, with `select`, selection: the final fixed-budget one, or with cand_m > 0 every head's
+// best cand_m candidates for the head-adaptive split; with `gather_eb` > 0 also the gather of the
 // kept rows, gather_eb being the element size) for `nunits` units starting at unit0.  Few waves per
 // workgroup keep the many block-wide steps cheap; long heads get more threads.
 hipError_t launch_mixsel(const Shape &s, bool select, const LayerOutTable &out, char *ws, const Workspace &w,
-                         int64_t unit0, int nunits, const LayerInTable &in, int gather_eb, hipStream_t st) {
+                         int64_t unit0, int nunits, const LayerInTable &in, int gather_eb, int cand_m, hipStream_t st) {
   const int nc = s.Nc;
-  if (nc <= 256 * 8) return launch_mixsel_e<256, 8>(s, select, out, ws, w, unit0, nunits, in, gather_eb, st);
-  if (nc <= 512 * 8) return launch_mixsel_e<512, 8>(s, select, out, ws, w, unit0, nunits, in, gather_eb, st);
-  if (nc <= 1024 * 8) return launch_mixsel_e<1024, 8>(s, select, out, ws, w, unit0, nunits, in, gather_eb, st);
-  if (nc <= 1024 * 16) return launch_mixsel_e<1024, 16>(s, select, out, ws, w, unit0, nunits, in, gather_eb, st);
-  return launch_mixsel_e<1024, 32>(s, select, out, ws, w, unit0, nunits, in, gather_eb, st);
+  if (nc <= 256 * 8) return launch_mixsel_e<256, 8>(s, select, out, ws, w, unit0, nunits, in, gather_eb, cand_m, st);
+  if (nc <= 512 * 8) return launch_mixsel_e<512, 8>(s, select, out, ws, w, unit0, nunits, in, gather_eb, cand_m, st);
+  if (nc <= 1024 * 8) return launch_mixsel_e<1024, 8>(s, select, out, ws, w, unit0, nunits, in, gather_eb, cand_m, st);
+  if (nc <= 1024 * 16) return launch_mixsel_e<1024, 16>(s, select, out, ws, w, unit0, nunits, in, gather_eb, cand_m, st);
+  return launch_mixsel_e<1024, 32>(s, select, out, ws, w, unit0, nunits, in, gather_eb, cand_m, st);
 }
 
 }  // namespace mixkv

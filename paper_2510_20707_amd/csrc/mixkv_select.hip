@@ -66,19 +66,43 @@ struct SelectScratch {
   int bin, krem, cut;
 };
 
-// k-th largest key among the valid elements idx in [0, n): returns the threshold key and how many
-// elements equal to it are still needed (need >= 1).  Requires 1 <= k <= number of valid elements.
-// KeyFn: (int idx, uint32_t &key) -> bool valid.
+// One count into a shared histogram bin per lane, with the lanes that share the wave's most common
+// bin (as seen from its first active lane) merged into a single atomic: scores of one head often
+// agree in their leading bits, and 64 atomics on one LDS word would run one after the other.
+__device__ __forceinline__ void hist_add_merged(int *hist, int bin, bool on) {
+  const unsigned long long act = __ballot(on);
+  if (act == 0) return;
+  const int first = __ffsll((long long)act) - 1;                  // wave-uniform
+  const int b0 = __builtin_amdgcn_readlane(bin, first);
+  const unsigned long long same = __ballot(on && bin == b0);
+  if ((int)(threadIdx.x & 63) == first) atomicAdd(&hist[b0], __popcll(same));
+  if (on && bin != b0) atomicAdd(&hist[bin], 1);
+}
+
+// k-th largest key among the valid elements (r, i), r in [0, rows), i in [0, n), ranked by key
+// (rows exist so that a caller with several heads needs no division per element): returns the
+// threshold key and how many elements equal to it are still needed (need >= 1).  Requires
+// 1 <= k <= number of valid elements.  KeyFn: (int r, int i, uint32_t &key) -> bool valid.
 template <class KeyFn>
-__device__ void radix_select(int n, int k, KeyFn keyfn, SelectScratch &sc, uint32_t *tau, int *need) {
+__device__ void radix_select(int rows, int n, int k, KeyFn keyfn, SelectScratch &sc, uint32_t *tau, int *need) {
   uint32_t prefix = 0, mask = 0;
   for (int shift = 24; shift >= 0; shift -= 8) {
     for (int i = threadIdx.x; i < 256; i += blockDim.x) sc.hist[i] = 0;
     __syncthreads();
-    for (int i = threadIdx.x; i < n; i += blockDim.x) {
-      uint32_t key;
-      if (keyfn(i, key) && (key & mask) == prefix) atomicAdd(&sc.hist[(key >> shift) & 0xff], 1);
-    }
+    constexpr int U = 8;                                        // loads in flight per thread
+    for (int r = 0; r < rows; ++r)
+      for (int i0 = 0; i0 < n; i0 += U * blockDim.x) {          // whole waves stay in the loop: the merge uses ballots
+        uint32_t key[U];
+        bool on[U];
+#pragma unroll
+        for (int j = 0; j < U; ++j) {
+          const int i = i0 + j * blockDim.x + threadIdx.x;
+          key[j] = 0;
+          on[j] = i < n && keyfn(r, i, key[j]) && (key[j] & mask) == prefix;
+        }
+#pragma unroll
+        for (int j = 0; j < U; ++j) hist_add_merged(sc.hist, (int)((key[j] >> shift) & 0xff), on[j]);
+      }
     __syncthreads();
     // scan the bins from the top: thread t looks at bin 255 - t
     int cnt = (threadIdx.x < 256) ? sc.hist[255 - threadIdx.x] : 0;
@@ -98,24 +122,73 @@ __device__ void radix_select(int n, int k, KeyFn keyfn, SelectScratch &sc, uint3
   *need = k;
 }
 
-// Index of the `need`-th (1-based) valid element with key == tau, in index order.
-template <class KeyFn>
-__device__ int kth_equal_index(int n, uint32_t tau, int need, KeyFn keyfn, SelectScratch &sc) {
-  const int per = (n + blockDim.x - 1) / blockDim.x;
-  const int lo = min(n, (int)threadIdx.x * per), hi = min(n, lo + per);
-  int cnt = 0;
-  for (int i = lo; i < hi; ++i) {
-    uint32_t key;
-    if (keyfn(i, key) && key == tau) ++cnt;
+// Ownership for ordered passes over n elements: wave w owns the contiguous segment
+// [w * seg, (w + 1) * seg) with seg a multiple of 64, and visits it 64 consecutive elements at a
+// time (element = segment start + c * 64 + lane), so every load is one contiguous 256-byte run.
+// The order of elements is (wave, c, lane) = ascending index.
+struct WaveSeg {
+  int lo, hi, lane, wave, nw;
+  __device__ WaveSeg(int n) {
+    lane = threadIdx.x & 63; wave = threadIdx.x >> 6; nw = blockDim.x >> 6;
+    const int seg = ((n + nw - 1) / nw + 63) / 64 * 64;
+    lo = min(n, wave * seg); hi = min(n, lo + seg);
   }
-  int total;
-  int excl = block_exclusive_scan(cnt, sc.iscr, &total);
-  if (excl < need && need <= excl + cnt) {
-    int seen = excl;
-    for (int i = lo; i < hi; ++i) {
-      uint32_t key;
-      if (keyfn(i, key) && key == tau && ++seen == need) { sc.cut = i; break; }
+};
+__device__ __forceinline__ int lanes_below(unsigned long long m) {   // set bits of m at lanes below this one
+  return __popcll(m & ((1ull << (threadIdx.x & 63)) - 1ull));
+}
+
+// Exclusive prefix over the waves of one int per wave (the same value in all its lanes); *total
+// receives the block sum.
+__device__ int wave_totals_scan(int wtot, SelectScratch &sc, int *total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  __syncthreads();
+  if (lane == 0) sc.iscr[wave] = wtot;
+  __syncthreads();
+  int before = 0, all = 0;
+  for (int i = 0; i < nw; ++i) { const int t = sc.iscr[i]; before += i < wave ? t : 0; all += t; }
+  *total = all;
+  return before;
+}
+
+// Position r * n + i of the `need`-th (1-based) valid element with key == tau, in (row, index)
+// order.
+template <class KeyFn>
+__device__ int kth_equal_index(int rows, int n, uint32_t tau, int need, KeyFn keyfn, SelectScratch &sc) {
+  constexpr int U = 4;
+  const WaveSeg g(n);
+  if (threadIdx.x == 0) sc.cut = -1;
+  for (int r = 0; r < rows; ++r) {
+    int wtot = 0;
+    for (int c0 = g.lo; c0 < g.hi; c0 += 64 * U) {
+      bool eq[U];
+#pragma unroll
+      for (int j = 0; j < U; ++j) {
+        const int i = c0 + j * 64 + g.lane;
+        uint32_t key = 0;
+        eq[j] = i < g.hi && keyfn(r, i, key) && key == tau;
+      }
+#pragma unroll
+      for (int j = 0; j < U; ++j) wtot += __popcll(__ballot(eq[j]));
     }
+    int total;
+    const int before = wave_totals_scan(wtot, sc, &total);
+    if (need <= total) {                               // block-uniform: the element is in this row
+      if (before < need && need <= before + wtot) {    // wave-uniform: and in this wave's segment
+        int seen = before;
+        for (int c0 = g.lo; c0 < g.hi; c0 += 64) {
+          const int i = c0 + g.lane;
+          uint32_t key = 0;
+          const bool eq = i < g.hi && keyfn(r, i, key) && key == tau;
+          const unsigned long long m = __ballot(eq);
+          if (eq && seen + lanes_below(m) + 1 == need) sc.cut = r * n + i;
+          seen += __popcll(m);
+          if (seen >= need) break;
+        }
+      }
+      break;
+    }
+    need -= total;
   }
   __syncthreads();
   int cut = sc.cut;
@@ -123,21 +196,42 @@ __device__ int kth_equal_index(int n, uint32_t tau, int need, KeyFn keyfn, Selec
   return cut;
 }
 
-// Ordered compaction: writes the indices i in [0, n) with pred(i), ascending, to dst (at most `cap`
-// of them, the size of the destination); returns the count.
+// Ordered compaction: writes the indices i in [0, n) with pred(i, scores[i]), ascending, to dst
+// (at most `cap` of them, the size of the destination); returns the count.
 template <class Pred>
-__device__ int compact_ascending(int n, Pred pred, int32_t *dst, int cap, SelectScratch &sc) {
-  const int per = (n + blockDim.x - 1) / blockDim.x;
-  const int lo = min(n, (int)threadIdx.x * per), hi = min(n, lo + per);
-  int cnt = 0;
-  for (int i = lo; i < hi; ++i) cnt += pred(i) ? 1 : 0;
-  int total;
-  int pos = block_exclusive_scan(cnt, sc.iscr, &total);
-  for (int i = lo; i < hi; ++i)
-    if (pred(i)) {
-      if (pos < cap) dst[pos] = i;
-      ++pos;
+__device__ int compact_ascending(int n, const float *scores, Pred pred, int32_t *dst, int cap, SelectScratch &sc) {
+  constexpr int U = 4;
+  const WaveSeg g(n);
+  int wtot = 0;
+  for (int c0 = g.lo; c0 < g.hi; c0 += 64 * U) {
+    bool in[U];
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+      const int i = c0 + j * 64 + g.lane;
+      const float v = i < g.hi ? scores[i] : 0.f;
+      in[j] = i < g.hi && pred(i, v);
     }
+#pragma unroll
+    for (int j = 0; j < U; ++j) wtot += __popcll(__ballot(in[j]));
+  }
+  int total;
+  int pos = wave_totals_scan(wtot, sc, &total);
+  for (int c0 = g.lo; c0 < g.hi; c0 += 64 * U) {
+    bool in[U];
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+      const int i = c0 + j * 64 + g.lane;
+      const float v = i < g.hi ? scores[i] : 0.f;
+      in[j] = i < g.hi && pred(i, v);
+    }
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+      const unsigned long long m = __ballot(in[j]);
+      const int at = pos + lanes_below(m);
+      if (in[j] && at < cap) dst[at] = c0 + j * 64 + g.lane;
+      pos += __popcll(m);
+    }
+  }
   return min(total, cap);
 }
 
@@ -236,9 +330,9 @@ __global__ __launch_bounds__(kSelectThreads) void select_fixed_kernel(Shape s, L
   if (s.Bp > 0) {
     uint32_t tau;
     int need;
-    radix_select(s.Nc, s.Bp, keyfn, sc, &tau, &need);
-    const int cut = kth_equal_index(s.Nc, tau, need, keyfn, sc);
-    compact_ascending(s.Nc, [&](int i) { uint32_t k = order_key(scores[i]); return k > tau || (k == tau && i <= cut); },
+    radix_select(1, s.Nc, s.Bp, [&](int, int i, uint32_t &key) { return keyfn(i, key); }, sc, &tau, &need);
+    const int cut = kth_equal_index(1, s.Nc, tau, need, [&](int, int i, uint32_t &key) { return keyfn(i, key); }, sc);
+    compact_ascending(s.Nc, scores, [&](int i, float v) { uint32_t k = order_key(v); return k > tau || (k == tau && i <= cut); },
                       idx, s.Bp, sc);
   }
   for (int wv = threadIdx.x; wv < s.W; wv += blockDim.x) idx[s.Bp + wv] = s.Nc + wv;
@@ -272,8 +366,8 @@ __global__ __launch_bounds__(kSelectThreads) void select_adaptive_kernel(Shape s
     if (f > 0) {
       auto keyfn = [&](int i, uint32_t &key) { key = order_key(sh[i]); return true; };
       int need;
-      radix_select(Nc, f, keyfn, sc, &tau, &need);
-      cut = kth_equal_index(Nc, tau, need, keyfn, sc);
+      radix_select(1, Nc, f, [&](int, int i, uint32_t &key) { return keyfn(i, key); }, sc, &tau, &need);
+      cut = kth_equal_index(1, Nc, tau, need, [&](int, int i, uint32_t &key) { return keyfn(i, key); }, sc);
     }
     if (threadIdx.x == 0) { tauF[h] = tau; cutF[h] = cut; }
     __syncthreads();
@@ -285,26 +379,25 @@ __global__ __launch_bounds__(kSelectThreads) void select_adaptive_kernel(Shape s
   uint32_t tauR = 0xffffffffu;
   int cutR = -1;
   if (rest > 0) {
-    auto keyfn = [&](int fi, uint32_t &key) {
-      const int h = fi / Nc, i = fi - h * Nc;
+    auto keyfn = [&](int h, int i, uint32_t &key) {
       key = order_key(scores[(int64_t)h * s.N + i]);
       return !in_floor(h, i, key);
     };
     int need;
-    radix_select(H * Nc, rest, keyfn, sc, &tauR, &need);
-    cutR = kth_equal_index(H * Nc, tauR, need, keyfn, sc);
+    radix_select(H, Nc, rest, keyfn, sc, &tauR, &need);
+    cutR = kth_equal_index(H, Nc, tauR, need, keyfn, sc);
   }
 
   // 3. per head: ordered compaction of floor set + share of the pool, then the window
   int base = 0;
   for (int h = 0; h < H; ++h) {
     const float *sh = scores + (int64_t)h * s.N;
-    auto pred = [&](int i) {
-      uint32_t key = order_key(sh[i]);
+    auto pred = [&](int i, float v) {
+      uint32_t key = order_key(v);
       if (in_floor(h, i, key)) return true;
       return rest > 0 && (key > tauR || (key == tauR && h * Nc + i <= cutR));
     };
-    const int cnt = compact_ascending(Nc, pred, idx + base, H * s.B - base - s.W * (H - h), sc);
+    const int cnt = compact_ascending(Nc, sh, pred, idx + base, H * s.B - base - s.W * (H - h), sc);
     for (int wv = threadIdx.x; wv < s.W; wv += blockDim.x) idx[base + cnt + wv] = Nc + wv;
     if (threadIdx.x == 0) {
       O.counts[b * H + h] = cnt + s.W;
@@ -316,6 +409,92 @@ __global__ __launch_bounds__(kSelectThreads) void select_adaptive_kernel(Shape s
   if (threadIdx.x == 0) {
     offs[H] = base;
     for (int h = 0; h <= H; ++h) O.offsets[b * (H + 1) + h] = offs[h];
+  }
+}
+
+// Head-adaptive budgets from candidate lists: one workgroup per (layer, batch item).  Every head
+// brings its best M candidates (ascending positions, with keys); a head keeps its floor, i.e. its
+// f best, and the rest of the pool goes to the best remaining candidates of all heads together.
+// A head can keep at most f + H * (B' - f) <= M candidates, so the lists contain every candidate
+// that can be kept and the result is the same as ranking all of them.
+__global__ __launch_bounds__(kSelectThreads) void select_candidates_kernel(Shape s, LayerOutTable out, char *ws,
+                                                                          Workspace w, int64_t unit0, int M) {
+  __shared__ uint32_t key_s[kMaxCandPerGroup];
+  __shared__ int32_t pos_s[kMaxCandPerGroup];
+  __shared__ uint8_t floor_s[kMaxCandPerGroup], keep_s[kMaxCandPerGroup];
+  __shared__ int offs[kMaxAdaptiveHeads + 1];
+  __shared__ SelectScratch sc;
+  const int lb = blockIdx.x, layer = lb / s.batch, b = lb - layer * s.batch;
+  const LayerOut O = out.l[layer];
+  const int Nc = s.Nc, H = s.hkv, f = s.floor_, n = H * M;
+  const int rest = H * (s.Bp - f);
+  const int64_t unit = unit0 + (int64_t)lb * H;                 // first head of this (layer, batch item)
+  const int32_t *cidx = reinterpret_cast<const int32_t *>(ws + w.cand_idx) + unit * kMaxCandPerHead;
+  const uint32_t *ckey = reinterpret_cast<const uint32_t *>(ws + w.cand_key) + unit * kMaxCandPerHead;
+  int32_t *idx = O.indices + (int64_t)b * H * s.B;
+  for (int e = threadIdx.x; e < n; e += blockDim.x) {
+    const int h = e / M, j = e - h * M;
+    key_s[e] = ckey[(int64_t)h * kMaxCandPerHead + j];
+    pos_s[e] = cidx[(int64_t)h * kMaxCandPerHead + j];
+  }
+  __syncthreads();
+  // floor: rank inside the head by (key descending, position ascending)
+  for (int e = threadIdx.x; e < n; e += blockDim.x) {
+    const int h = e / M;
+    const uint32_t k = key_s[e];
+    const int p = pos_s[e];
+    int better = 0;
+    for (int o = h * M; o < (h + 1) * M; ++o) better += (key_s[o] > k || (key_s[o] == k && pos_s[o] < p)) ? 1 : 0;
+    floor_s[e] = better < f;
+  }
+  __syncthreads();
+  // pool: the `rest` best candidates outside the floors by (key descending, head, position
+  // ascending); list order (head, entry) is that tie order, since every list is ascending
+  uint32_t tauR = 0xffffffffu;
+  int cutR = -1;
+  if (rest > 0) {
+    auto keyfn = [&](int h, int j, uint32_t &key) {
+      key = key_s[h * M + j];
+      return floor_s[h * M + j] == 0;
+    };
+    int need;
+    radix_select(H, M, rest, keyfn, sc, &tauR, &need);
+    cutR = kth_equal_index(H, M, tauR, need, keyfn, sc);
+  }
+  for (int e = threadIdx.x; e < n; e += blockDim.x)
+    keep_s[e] = floor_s[e] || (rest > 0 && (key_s[e] > tauR || (key_s[e] == tauR && e <= cutR)));
+  __syncthreads();
+  // per head: the kept candidates are already in ascending position order; then the window
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
+  for (int h = wave; h < H; h += nw) {               // one wave per head counts its kept candidates
+    int cnt = 0;
+    for (int j0 = 0; j0 < M; j0 += 64) cnt += __popcll(__ballot(j0 + lane < M && keep_s[h * M + j0 + lane]));
+    if (lane == 0) offs[h + 1] = cnt;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int base = 0;
+    for (int h = 0; h < H; ++h) {
+      const int cnt = offs[h + 1];
+      offs[h] = base;
+      O.counts[b * H + h] = cnt + s.W;
+      O.offsets[b * (H + 1) + h] = base;
+      base += cnt + s.W;
+    }
+    offs[H] = base;
+    O.offsets[b * (H + 1) + H] = base;
+  }
+  __syncthreads();
+  for (int h = wave; h < H; h += nw) {               // one wave per head walks its list in order
+    int at = offs[h];
+    for (int j0 = 0; j0 < M; j0 += 64) {
+      const int j = j0 + lane;
+      const bool k = j < M && keep_s[h * M + j];
+      const unsigned long long m = __ballot(k);
+      if (k) idx[at + __popcll(m & ((1ull << lane) - 1ull))] = pos_s[h * M + j];
+      at += __popcll(m);
+    }
+    for (int wv = lane; wv < s.W; wv += 64) idx[at + wv] = Nc + wv;
   }
 }
 
@@ -374,6 +553,21 @@ hipError_t launch_gather(const Shape &s, int dtype, const LayerInTable &in, cons
   const int total = s.hkv * s.B;
   dim3 grid((total + rows_per_block - 1) / rows_per_block, nlayers * s.batch);
   hipLaunchKernelGGL(gather_kernel, grid, dim3(256), 0, st, s, eb, in, out);
+  return hipGetLastError();
+}
+
+// Candidates a head has to hand to the budget split: its floor plus the whole shared pool; 0 if
+// that does not shorten the lists enough for the small kernel.
+int adaptive_candidates(const Shape &s) {
+  const int64_t M = (int64_t)s.floor_ + (int64_t)s.hkv * (s.Bp - s.floor_);
+  if (M < 1 || M > s.Nc || M > kMaxCandPerHead || M * s.hkv > kMaxCandPerGroup) return 0;
+  return (int)M;
+}
+
+hipError_t launch_select_candidates(const Shape &s, const LayerOutTable &out, char *ws, const Workspace &w, int64_t unit0,
+                                    int nlayers, int cand_m, hipStream_t st) {
+  hipLaunchKernelGGL(select_candidates_kernel, dim3(nlayers * s.batch), dim3(kSelectThreads), 0, st, s, out, ws, w, unit0,
+                     cand_m);
   return hipGetLastError();
 }
 
