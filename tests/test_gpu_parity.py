@@ -125,6 +125,8 @@ def test_adaptive_small_all_units():
     _run_and_check(wl, n_layers=2)
     _run_and_check(wl, n_layers=1, budget_floor=0)
     _run_and_check(wl, n_layers=1, budget_floor=64)     # floor == B': nothing left to pool
+    # a pool too large for per-head candidate lists: the split ranks all candidates of all heads
+    _run_and_check(wl, n_layers=1, budget=400)
 
 
 def test_more_layers_than_one_launch_group():
