@@ -19,6 +19,7 @@
 // with b_r = max_r + log2(sum_r * G*W), so one fused multiply-add and one v_exp_f32 per element
 // give the weight already divided by the row sum and by the number of rows
 // (paper Sec. 3.2, extrinsic importance: mean over the window queries of the attention weights).
+#include <cstdlib>
 #include "mixkv_internal.h"
 #include "mixkv_wave.h"
 
@@ -257,7 +258,7 @@ __device__ __forceinline__ void wait_tile(int t, int nt) {
 // Per-run partials go to the workspace; attn_kernel folds them at the start of its runs.
 // ------------------------------------------------------------------------------------------------
 template <int DT, int D, int WAVES, int TQ>
-__global__ __launch_bounds__(WAVES * 64, 2) void stats_kernel(Shape s, LayerInTable in, char *ws, Workspace w,
+__global__ __launch_bounds__(WAVES * 64, (WAVES == 8 && TQ == 1) ? 4 : 2) void stats_kernel(Shape s, LayerInTable in, char *ws, Workspace w,
                                                              int64_t unit0, int nunits, int64_t slot0) {
   constexpr int EB = Tr<DT>::EB, EPC = Tr<DT>::EPC, NCHK = D / (2 * EPC), PPR = D * EB / 16;
   constexpr int NT = WAVES * 64, KT = chunk_tiles(DT, D), TILE = 32 * PPR;
@@ -777,6 +778,12 @@ static void stream_config(int QT, int *waves, int *tq) {
   *waves = QT <= 8 ? 4 : 8;
   *tq = QT <= 4 ? 1 : 2;
 }
+// stats_kernel needs fewer registers per query tile than attn_kernel: with 5 to 8 query tiles it
+// runs eight waves of one tile each, four waves per SIMD, which hides more of its latencies.
+static void stats_config(int QT, int *waves, int *tq) {
+  stream_config(QT, waves, tq);
+  if (QT > 4 && QT <= 8 && !getenv("MIXKV_STATS42")) { *waves = 8; *tq = 1; }
+}
 
 // Grid of the two streaming kernels: enough workgroups to fill the chip once, never more than items.
 int stream_grid(const Shape &s, int nunits, int num_cus) {
@@ -812,9 +819,10 @@ template <int DT, int D>
 static hipError_t launch_stats_t(const Shape &s, const LayerInTable &in, char *ws, const Workspace &w, int64_t unit0,
                                  int nunits, int grid, int64_t slot0, hipStream_t st) {
   int waves, tq;
-  stream_config(s.QT, &waves, &tq);
+  stats_config(s.QT, &waves, &tq);
   if (waves == 4 && tq == 1) return launch_stats_c<DT, D, 4, 1>(s, in, ws, w, unit0, nunits, grid, slot0, st);
   if (waves == 4) return launch_stats_c<DT, D, 4, 2>(s, in, ws, w, unit0, nunits, grid, slot0, st);
+  if (tq == 1) return launch_stats_c<DT, D, 8, 1>(s, in, ws, w, unit0, nunits, grid, slot0, st);
   return launch_stats_c<DT, D, 8, 2>(s, in, ws, w, unit0, nunits, grid, slot0, st);
 }
 
