@@ -30,6 +30,10 @@ from paper_2510_20707_amd import synth  # noqa: E402
 
 HBM_PEAK = 8.0e12
 MFMA_BF16_PEAK = 2.5e15
+# HBM bytes per launch (fetched + written) of the two streaming kernels on the default workload, from
+# rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this command scaled by a 1 GiB copy kernel (the summary
+# with the commands is under profiles/).  Other workloads report no measured traffic.
+MEASURED_TRAFFIC = {("c3", 28, "stats"): 513.5e6, ("c3", 28, "attn"): 281.6e6}
 
 _LAYERS = None
 _WL = None
@@ -197,7 +201,9 @@ def main():
         "stage_ms": {k: round(v, 5) for k, v in stage_ms.items()},
         "mfma_tflops": {k: gemm_flops / (stage_ms[k] * 1e-3) / 1e12 for k in ("stats", "attn") if stage_ms.get(k)},
         "roofline": {"bound": "hbm", "kernel": dom + "_kernel", "achieved": dom_bytes / dom_s / 1e9,
-                     "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": dom_bytes / dom_s / HBM_PEAK, "traffic": None},
+                     "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": dom_bytes / dom_s / HBM_PEAK,
+                     "algorithmic_bytes": dom_bytes, "avg_launch_us": dom_s * 1e6,
+                     "traffic": MEASURED_TRAFFIC.get((wl.name, wl.n_layers, dom))},
         "cpu_baseline": cpu,
         "parity_vs_oracle": parity,
         "host_gen_s": round(t_gen, 2),
