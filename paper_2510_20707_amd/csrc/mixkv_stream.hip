@@ -175,31 +175,41 @@ __device__ __forceinline__ int tile_swz(int r) {
 // `img` is an integer on purpose: the destination of the load then carries no object identity, and
 // the compiler does not make later reads of the ring wait for every load in flight - the waits are
 // placed by hand (wait_vm) where the data is needed.
+// The last tile of a sequence, where rows past N-1 re-read row N-1 (kept out of line so that the
+// common path below stays a scalar base plus a fixed lane offset).
+template <int DT, int D, int WAVES>
+__device__ __attribute__((noinline)) void fetch_tile_clamped(const char *Kb, int64_t row_bytes, int tb, int N, uint32_t img,
+                                                             int wave, int lane) {
+  constexpr int PPR = D * Tr<DT>::EB / 16, LOADS = 32 * PPR / 64, RPL = 64 / PPR;
+  const int lrow = lane / PPR, lq = lane % PPR;
+#pragma unroll
+  for (int jj = 0; jj < (LOADS + WAVES - 1) / WAVES; ++jj) {
+    const int j = (jj * WAVES + wave) % LOADS;
+    const int row = j * RPL + lrow;
+    const int krow = min(tb + row, N - 1);
+    const char *src = Kb + (int64_t)krow * row_bytes + (lq ^ tile_swz<DT, D>(row)) * 16;
+    __builtin_amdgcn_global_load_lds((glb_void_t *)src, (lds_void_t *)(uintptr_t)(img + j * 1024), 16, 0, 0);
+  }
+}
+
 template <int DT, int D, int WAVES>
 __device__ __forceinline__ void fetch_tile(const char *Kb, int64_t row_bytes, int tb, int N, uint32_t img, int wave,
                                            int lane) {
   constexpr int PPR = D * Tr<DT>::EB / 16, LOADS = 32 * PPR / 64;      // loads per tile
   constexpr int RPL = 64 / PPR;                                         // rows per load
   static_assert(PPR <= 64 && 64 % PPR == 0, "row pieces must divide a load");
-  const int lrow = lane / PPR, lq = lane % PPR;
-  const uint32_t rb = (uint32_t)row_bytes;
   if (tb + 32 <= N) {
+    const int lrow = lane / PPR, lq = lane % PPR;
+    const uint32_t rb = (uint32_t)row_bytes;
 #pragma unroll
     for (int jj = 0; jj < (LOADS + WAVES - 1) / WAVES; ++jj) {
       const int j = (jj * WAVES + wave) % LOADS;
       const char *base = Kb + (int64_t)(tb + j * RPL) * row_bytes;               // wave-uniform
-      const uint32_t off = (uint32_t)lrow * rb + (uint32_t)((lq ^ tile_swz<DT, D>(j * RPL + lrow)) * 16);
+      const uint32_t off = (uint32_t)lrow * rb + (uint32_t)((lq ^ tile_swz<DT, D>(j * RPL + lrow)) * 16);   // loop-invariant
       __builtin_amdgcn_global_load_lds((glb_void_t *)(base + off), (lds_void_t *)(uintptr_t)(img + j * 1024), 16, 0, 0);
     }
   } else {
-#pragma unroll
-    for (int jj = 0; jj < (LOADS + WAVES - 1) / WAVES; ++jj) {
-      const int j = (jj * WAVES + wave) % LOADS;
-      const int row = j * RPL + lrow;
-      const int krow = min(tb + row, N - 1);
-      const char *src = Kb + (int64_t)krow * row_bytes + (lq ^ tile_swz<DT, D>(row)) * 16;
-      __builtin_amdgcn_global_load_lds((glb_void_t *)src, (lds_void_t *)(uintptr_t)(img + j * 1024), 16, 0, 0);
-    }
+    fetch_tile_clamped<DT, D, WAVES>(Kb, row_bytes, tb, N, img, wave, lane);
   }
 }
 
