@@ -431,13 +431,20 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 && TQ == 1) ? 4 : 2) void s
         float tmax = fmaxf(acc[q][0], acc[q][1]);
 #pragma unroll
         for (int i = 2; i < 16; i += 2) tmax = fmaxf(fmaxf(tmax, acc[q][i]), acc[q][i + 1]);
-        const float mn = fmaxf(m[q], tmax * c2);          // c2 > 0: scaling commutes with max
-        const float mu = (mn == -INFINITY) ? 0.f : mn;
-        float sum = 0.f;
+        // The running offset m only has to be an upper bound of what was seen: it moves (and the
+        // sum is rescaled) only in the steps where some row of the wave sees a new maximum.
+        const float tm = tmax * c2;                       // c2 > 0: scaling commutes with max
+        if (__builtin_amdgcn_ballot_w64(tm > m[q]) != 0) {
+          const float mn = fmaxf(m[q], tm);
+          const float mu = (mn == -INFINITY) ? 0.f : mn;
+          l[q] = l[q] * fast_exp2(m[q] - mu);
+          m[q] = mn;
+        }
+        const float nmu = (m[q] == -INFINITY) ? 0.f : -m[q];
+        float sum[4] = {0.f, 0.f, 0.f, 0.f};              // four chains: the adds do not wait on each other
 #pragma unroll
-        for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(acc[q][i], c2, -mu));
-        l[q] = l[q] * fast_exp2(m[q] - mu) + sum;
-        m[q] = mn;
+        for (int i = 0; i < 16; ++i) sum[i & 3] += fast_exp2(fmaf(acc[q][i], c2, nmu));
+        l[q] += (sum[0] + sum[1]) + (sum[2] + sum[3]);
       }
       TSTAMP(t4);
       TACC(0, t0, t1); TACC(1, t1, t2); TACC(2, t2, t3); TACC(3, t3, t4);
