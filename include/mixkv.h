@@ -99,9 +99,9 @@ typedef struct {
 } mixkv_layer_out;
 
 /*
- * Bytes of device workspace any of the three entry points needs for `n_layers`
- * layers of this shape.  Host only; touches no GPU.  The workspace needs no
- * initialisation and 256-byte alignment.
+ * Bytes of device workspace mixkv_score / mixkv_compress need for `n_layers`
+ * layers of this shape (mixkv_select needs none and accepts NULL).  Host only;
+ * touches no GPU.  The workspace needs no initialisation and 256-byte alignment.
  */
 mixkv_status mixkv_workspace_size(const mixkv_params *params, int32_t n_layers, size_t *bytes);
 
