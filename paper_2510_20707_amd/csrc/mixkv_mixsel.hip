@@ -12,16 +12,6 @@
 #include "mixkv_internal.h"
 #include "mixkv_wave.h"
 
-#ifdef MIXKV_TIMING
-__device__ unsigned long long mixsel_dbg[1024 * 8];
-#define MS_STAMP(i) do { if (threadIdx.x == 0) mixsel_dbg[blockIdx.x * 8 + (i)] = __builtin_readcyclecounter(); } while (0)
-extern "C" int mixsel_debug_read(unsigned long long *host) {
-  return hipMemcpyFromSymbol(host, HIP_SYMBOL(mixsel_dbg), sizeof(mixsel_dbg)) != hipSuccess;
-}
-#else
-#define MS_STAMP(i)
-#endif
-
 namespace mixkv {
 
 constexpr int kMsMaxThreads = 1024, kMsMaxWaves = kMsMaxThreads / 64;
@@ -135,7 +125,6 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
   const bool use_v = s.intrinsic == MIXKV_INTRINSIC_VNORM;
   const float inv_n = 1.f / (float)Nc;
 
-  MS_STAMP(0);
   // ---- load: EPT consecutive candidates per thread (the per-unit rows are padded past Nc)
   float a[EPT], v[EPT], d[EPT];
 #pragma unroll
@@ -159,7 +148,6 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
   for (int e = 0; e < EPT; ++e)
     if (base + e < Nc) a_s[slot(base + e)] = a[e];
   __syncthreads();
-  MS_STAMP(1);
 
   // ---- pooled attention (candidates only) and the first round of statistics
   if (s.pool != MIXKV_POOL_NONE && s.pool_k > 1) {
@@ -227,9 +215,7 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
       st[3] = fminf(st[3], v[e]); st[4] = fminf(st[4], d[e]);
       st[5] = fmaxf(st[5], v[e]); st[6] = fmaxf(st[6], d[e]);
     }
-  MS_STAMP(2);
   block_reduce_mixed<NW, 3, 2, 2>(st, sc);
-  MS_STAMP(3);
   const float mean_ex = st[0] * inv_n;
   const float vmin = st[3], dmin = st[4];
   const float rvden = 1.f / (st[5] - vmin + s.eps), rdden = 1.f / (st[6] - dmin + s.eps);
@@ -271,7 +257,6 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
       if (base + e < Nc) { kmin = min(kmin, key[e]); kmax = max(kmax, key[e]); }
     }
     block_minmax_u32<NW>(kmin, kmax, sc);
-    MS_STAMP(4);
     // bits at and above `undecided` are common to all keys; digits of up to kDigit bits from there down
     int undecided = kmin == kmax ? 0 : 32 - __clz((int)(kmin ^ kmax));
     uint32_t prefix = undecided >= 32 ? 0u : (kmax >> undecided) << undecided;
@@ -313,7 +298,6 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
       undecided = shift;
       __syncthreads();
     }
-    MS_STAMP(5);
     const uint32_t tau = prefix;       // the B'-th largest key; k of the keys equal to it are still needed
     // one scan carries both counts: keys above tau (low half) and keys equal to tau (high half)
     int ngt = 0, neq = 0;
@@ -342,7 +326,6 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
       }
     }
   }
-  MS_STAMP(6);
   if (cand) return;
   for (int wv = tid; wv < s.W; wv += THREADS) idx[Bp + wv] = Nc + wv;
   const int h = bh % s.hkv, b = bh / s.hkv;

@@ -4,8 +4,8 @@
 // Both are MFMA kernels built the same way.  A workgroup walks runs of consecutive key chunks of
 // one unit (one layer, batch item and KV head).  The G*W window-query rows are split into tiles of
 // 32 and every wave keeps its TQ tiles in registers for the whole run ("query-stationary"); the
-// keys stream through LDS: each chunk is fetched with direct global->LDS loads (whole rows,
-// bank-rotated) into one of two buffers while the other is being consumed by all waves.
+// keys (and values) stream through LDS: tiles of 32 rows are fetched with direct global->LDS loads
+// (whole rows, bank-rotated) into a ring of tile images, a few tile steps ahead of their use.
 //
 // Fragment form.  The contraction index d of Q.K^T may be visited in any order as long as both
 // operands agree, so a lane (key or row = lane % 32, half = lane / 32) simply owns every other
@@ -19,28 +19,8 @@
 // with b_r = max_r + log2(sum_r * G*W), so one fused multiply-add and one v_exp_f32 per element
 // give the weight already divided by the row sum and by the number of rows
 // (paper Sec. 3.2, extrinsic importance: mean over the window queries of the attention weights).
-#include <cstdlib>
 #include "mixkv_internal.h"
 #include "mixkv_wave.h"
-
-#ifdef MIXKV_TIMING
-// Developer aid, compiled out by default: cycle totals of wave 0 of every workgroup of attn_kernel.
-__device__ unsigned long long mixkv_dbg[1024 * 16];
-#define TSTAMP(v) unsigned long long v = __builtin_readcyclecounter()
-#define TACC(slot, a, b) tacc[slot] += (b) - (a)
-#define TDECL unsigned long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0}
-#define TFLUSH do { if (threadIdx.x == 0) for (int i_ = 0; i_ < 8; ++i_) mixkv_dbg[blockIdx.x * 16 + 8 + i_] = tacc[i_]; } while (0)
-extern "C" int mixkv_debug_read(unsigned long long *host, int clear) {
-  if (hipMemcpyFromSymbol(host, HIP_SYMBOL(mixkv_dbg), sizeof(mixkv_dbg)) != hipSuccess) return 1;
-  if (clear) { static unsigned long long z[1024 * 16]; return hipMemcpyToSymbol(HIP_SYMBOL(mixkv_dbg), z, sizeof(z)) != hipSuccess; }
-  return 0;
-}
-#else
-#define TSTAMP(v)
-#define TACC(slot, a, b)
-#define TDECL
-#define TFLUSH
-#endif
 
 namespace mixkv {
 
@@ -141,8 +121,8 @@ __device__ __forceinline__ UnitCoord unit_coord(const Shape &s, int ul) {
 typedef __attribute__((address_space(3))) void lds_void_t;
 typedef __attribute__((address_space(1))) const void glb_void_t;
 
-// Key tiles per chunk: at most four, and few enough that two workgroups (two key buffers, the
-// mean-key tile and the column-sum scratch each) fit in the 160 KB of LDS of a CU.
+// Key tiles per chunk.  A chunk is the unit of the work split between workgroups and of the
+// column-sum hand-over in attn_kernel; wide f32 tiles get one tile per chunk.
 __host__ __device__ constexpr int chunk_tiles(int dtype, int D) {
   const int tile_bytes = D * (dtype == MIXKV_BF16 ? 2 : 4) * 32;
   return tile_bytes <= 8192 ? 4 : 1;
@@ -175,8 +155,9 @@ __device__ __forceinline__ int tile_swz(int r) {
 // `img` is an integer on purpose: the destination of the load then carries no object identity, and
 // the compiler does not make later reads of the ring wait for every load in flight - the waits are
 // placed by hand (wait_vm) where the data is needed.
-// The last tile of a sequence, where rows past N-1 re-read row N-1 (kept out of line so that the
-// common path below stays a scalar base plus a fixed lane offset).
+//
+// fetch_tile_clamped is the last tile of a sequence, kept out of line so that the common path stays
+// a scalar base plus a fixed lane offset.
 template <int DT, int D, int WAVES>
 __device__ __attribute__((noinline)) void fetch_tile_clamped(const char *Kb, int64_t row_bytes, int tb, int N, uint32_t img,
                                                              int wave, int lane) {
@@ -265,11 +246,11 @@ __device__ __forceinline__ void wait_tile(int t, int nt) {
 //   * 1/|K_i| and the partial sum of the normalised keys (paper Sec. 3.2 diversity metrics,
 //     Sec. 3.3 Eq. 3-4: only the sum of normalised keys is needed, never the T x T matrix);
 //   * |V_i| (Sec. 3.2, VNorm intrinsic importance).
-// Per-run partials go to the workspace; attn_kernel folds them at the start of its runs.
+// Per-run partials go to the workspace; fold_kernel folds them per unit.
 // ------------------------------------------------------------------------------------------------
 template <int DT, int D, int WAVES, int TQ>
-__global__ __launch_bounds__(WAVES * 64, (WAVES == 8 && TQ == 1) ? 4 : 2) void stats_kernel(Shape s, LayerInTable in, char *ws, Workspace w,
-                                                             int64_t unit0, int nunits, int64_t slot0) {
+__global__ __launch_bounds__(WAVES * 64, (WAVES == 8 && TQ == 1) ? 4 : 2) void stats_kernel(
+    Shape s, LayerInTable in, char *ws, Workspace w, int64_t unit0, int nunits, int64_t slot0) {
   constexpr int EB = Tr<DT>::EB, EPC = Tr<DT>::EPC, NCHK = D / (2 * EPC), PPR = D * EB / 16;
   constexpr int NT = WAVES * 64, KT = chunk_tiles(DT, D), TILE = 32 * PPR;
   constexpr int VPT = (TILE + NT - 1) / NT;               // V pieces per thread and key tile
@@ -289,10 +270,6 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 && TQ == 1) ? 4 : 2) void s
   int64_t item = wg_first_item(blockIdx.x, gridDim.x, T);
   const int64_t item_end = wg_first_item(blockIdx.x + 1, gridDim.x, T);
 
-  TDECL;
-#ifdef MIXKV_TIMING_STATS
-  if (threadIdx.x == 0) { mixkv_dbg[blockIdx.x * 16 + 4] = wall_clock64(); mixkv_dbg[blockIdx.x * 16 + 6] = __builtin_readcyclecounter(); }
-#endif
   while (item < item_end) {
     const int ul = (int)(item / s.nchunks), c0 = (int)(item - (int64_t)ul * s.nchunks);
     const int nit = (int)min((int64_t)(s.nchunks - c0), item_end - item);
@@ -316,7 +293,6 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 && TQ == 1) ? 4 : 2) void s
       fetch_tile<DT, D, WAVES>(Kb, row_bytes, tbr, N, kring_a + off, wave, lane);
       if (use_v) fetch_tile<DT, D, WAVES>(Vb, row_bytes, tbr, N, vring_a + off, wave, lane);
     };
-    TSTAMP(p0);
     lds_barrier();                                     // the previous run is done with LDS
 #pragma unroll
     for (int j = 0; j < kLead; ++j)
@@ -343,8 +319,6 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 && TQ == 1) ? 4 : 2) void s
     // Nothing may be pending when the tile loop is entered: its waits count the requests issued
     // inside it.
     wait_vm<0>();
-    TSTAMP(p1);
-    TACC(4, p0, p1);
 
     // Sum of normalised keys: lane (lrow, lq) adds up piece lq (elements [lq*EPC, +EPC)) of the
     // rows it visits, so nothing crosses lanes before the end of the run.
@@ -354,17 +328,13 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 && TQ == 1) ? 4 : 2) void s
 
     for (int t = 0; t < nt; ++t) {
       __builtin_amdgcn_sched_barrier(0);
-      TSTAMP(t0);
       if (use_v) wait_tile<2 * KL>(t, nt); else wait_tile<KL>(t, nt);
-      TSTAMP(t1);
       lds_barrier();
-      TSTAMP(t2);
 #ifndef MIXKV_NODMA   // developer switch: time the arithmetic alone (results are then meaningless)
       if (t + kLead < nt) request(t + kLead);
 #endif
       __builtin_amdgcn_sched_barrier(0);
 
-      TSTAMP(t3);
       const int tb = key0 + t * 32;
       const uint4 *img = kring + (t & (kRing - 1)) * TILE;
       const uint4 *vimg = vring + (t & (kRing - 1)) * TILE;
@@ -446,8 +416,6 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 && TQ == 1) ? 4 : 2) void s
         for (int i = 0; i < 16; ++i) sum[i & 3] += fast_exp2(fmaf(acc[q][i], c2, nmu));
         l[q] += (sum[0] + sum[1]) + (sum[2] + sum[3]);
       }
-      TSTAMP(t4);
-      TACC(0, t0, t1); TACC(1, t1, t2); TACC(2, t2, t3); TACC(3, t3, t4);
     }
 
     // ---- run partials to global
@@ -474,10 +442,6 @@ __global__ __launch_bounds__(WAVES * 64, (WAVES == 8 && TQ == 1) ? 4 : 2) void s
     }
     item += nit;
   }
-#ifdef MIXKV_TIMING_STATS
-  TFLUSH;
-  if (threadIdx.x == 0) { mixkv_dbg[blockIdx.x * 16 + 5] = wall_clock64(); mixkv_dbg[blockIdx.x * 16 + 7] = __builtin_readcyclecounter(); }
-#endif
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -611,10 +575,6 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
   int64_t item = wg_first_item(blockIdx.x, gridDim.x, T);
   const int64_t item_end = wg_first_item(blockIdx.x + 1, gridDim.x, T);
 
-  TDECL;
-#if defined(MIXKV_TIMING) && !defined(MIXKV_TIMING_STATS)
-  if (threadIdx.x == 0) { mixkv_dbg[blockIdx.x * 16 + 4] = wall_clock64(); mixkv_dbg[blockIdx.x * 16 + 6] = __builtin_readcyclecounter(); }
-#endif
   while (item < item_end) {
     const int ul = (int)(item / s.nchunks), c0 = (int)(item - (int64_t)ul * s.nchunks);
     const int nit = (int)min((int64_t)(s.nchunks - c0), item_end - item);
@@ -635,9 +595,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
       fetch_tile<DT, D, WAVES>(Kb, row_bytes, key0 + tr * 32, N, kring_a + (uint32_t)(tr & (kRing - 1)) * (TILE * 16),
                                wave, lane);
     };
-    TSTAMP(p0);
     lds_barrier();                                     // the previous run is done with LDS
-    TSTAMP(p1);
 #pragma unroll
     for (int j = 0; j <= kLead; ++j)
       if (j < nt) request(j);
@@ -670,8 +628,6 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
     // inside it.
     wait_vm<0>();
     lds_barrier();                                     // tiles 0 .. kLead of the run (and kbar_s) are visible
-    TSTAMP(p2);
-    TACC(4, p0, p1); TACC(5, p1, p2);
 
     // add the waves' partial column sums of chunk `chunk` (buffer pb) in a fixed order
     auto flush_colsums = [&](int chunk, int pb) {
@@ -689,11 +645,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
     // which nobody reads any more.
     auto step = [&](int t, Frag (&kf)[NCHK], Frag (&kfn)[NCHK]) {
       __builtin_amdgcn_sched_barrier(0);
-      TSTAMP(t0);
       wait_tile<KL>(t + 1, nt);
-      TSTAMP(t1);
       lds_barrier();                                   // every wave holds the fragments of tile t: its image is free
-      TSTAMP(t2);
 #ifndef MIXKV_NODMA   // developer switch: time the arithmetic alone (results are then meaningless)
       if (t + 1 + kLead < nt) request(t + 1 + kLead);
 #endif
@@ -703,7 +656,6 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
         for (int c = 0; c < NCHK; ++c) kfn[c].q = read_key_frag<DT, D>(imgn, 0, c, l32, half);
       }
       __builtin_amdgcn_sched_barrier(0);
-      TSTAMP(t3);
       const int k = t % KT, g = t / KT;                // tile within its chunk, chunk within the run
       if (k == 0 && g > 0) flush_colsums(c0 + g - 1, (g - 1) & 1);
       float *cs = cs_s + ((g & 1) * WAVES + wave) * CH;
@@ -761,8 +713,6 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
       float colsum = (cs4[0] + cs4[1]) + (cs4[2] + cs4[3]);
       colsum += __shfl_xor(colsum, 32);
       if (half == 0) cs[k * 32 + l32] = colsum;
-      TSTAMP(t4);
-      TACC(0, t0, t1); TACC(1, t1, t2); TACC(2, t2, t3); TACC(3, t3, t4);
     };
 
     Frag kfa[NCHK], kfb[NCHK];
@@ -772,17 +722,10 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
       step(t, kfa, kfb);
       if (t + 1 < nt) step(t + 1, kfb, kfa);
     }
-    TSTAMP(e0);
     lds_barrier();
     flush_colsums(c0 + (nt - 1) / KT, ((nt - 1) / KT) & 1);
-    TSTAMP(e1);
-    TACC(6, e0, e1);
     item += nit;
   }
-#if defined(MIXKV_TIMING) && !defined(MIXKV_TIMING_STATS)
-  TFLUSH;
-  if (threadIdx.x == 0) { mixkv_dbg[blockIdx.x * 16 + 5] = wall_clock64(); mixkv_dbg[blockIdx.x * 16 + 7] = __builtin_readcyclecounter(); }
-#endif
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -799,7 +742,7 @@ static void stream_config(int QT, int *waves, int *tq) {
 // runs eight waves of one tile each, four waves per SIMD, which hides more of its latencies.
 static void stats_config(int QT, int *waves, int *tq) {
   stream_config(QT, waves, tq);
-  if (QT > 4 && QT <= 8 && !getenv("MIXKV_STATS42")) { *waves = 8; *tq = 1; }
+  if (QT > 4 && QT <= 8) { *waves = 8; *tq = 1; }
 }
 
 // Grid of the two streaming kernels: enough workgroups to fill the chip once, never more than items.
