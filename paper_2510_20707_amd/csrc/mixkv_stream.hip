@@ -248,8 +248,16 @@ __device__ __forceinline__ void wait_tile(int t, int nt) {
 //   * |V_i| (Sec. 3.2, VNorm intrinsic importance).
 // Per-run partials go to the workspace; fold_kernel folds them per unit.
 // ------------------------------------------------------------------------------------------------
+// Waves per SIMD the register allocation of stats_kernel aims at: two workgroups per compute unit
+// where their two rings fit in LDS together (tiles of up to 8 KB), one otherwise.
+__host__ __device__ constexpr int stats_waves_per_simd(int dtype, int D, int waves, int tq) {
+  const int tile_bytes = D * (dtype == MIXKV_BF16 ? 2 : 4) * 32;
+  const int wgs = (tile_bytes <= 8192 && !(waves == 8 && tq == 2)) ? 2 : 1;   // 8 waves x 2 tiles need 256 registers
+  return waves / 4 * wgs;
+}
+
 template <int DT, int D, int WAVES, int TQ>
-__global__ __launch_bounds__(WAVES * 64, (WAVES == 8 && TQ == 1) ? 4 : 2) void stats_kernel(
+__global__ __launch_bounds__(WAVES * 64, stats_waves_per_simd(DT, D, WAVES, TQ)) void stats_kernel(
     Shape s, LayerInTable in, char *ws, Workspace w, int64_t unit0, int nunits, int64_t slot0) {
   constexpr int EB = Tr<DT>::EB, EPC = Tr<DT>::EPC, NCHK = D / (2 * EPC), PPR = D * EB / 16;
   constexpr int NT = WAVES * 64, KT = chunk_tiles(DT, D), TILE = 32 * PPR;
