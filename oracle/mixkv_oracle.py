@@ -30,7 +30,13 @@ constant):
   * a key of norm below 1e-30 normalises to the zero vector;
   * the redundancy is not clamped;
   * ties in TopB go to the smaller index; kept rows are in ascending position
-    order with the window rows last.
+    order with the window rows last;
+  * the ablation's scoring variants (Sec. 4.3, Table 4): the KNorm intrinsic
+    score -||K_i|| (Sec. 3.2) goes through the same min-max and mean matching
+    as VNorm; the un-weighted row "s_imp + s_div" adds the scaled diversity
+    (the one Eq. 5 mixes), "s_div only" ranks by that scaled diversity alone,
+    "importance only" by s_imp alone; the offline head weights of Table 4 are a
+    caller-given r per unit that replaces Eq. 4's value in Eq. 5.
 
 Every function is pinned by tests/test_oracle_*.py against brute force, closed
 forms and library routines; the whole path against the authors' own code is
@@ -57,7 +63,8 @@ class Params:
     causal_window: bool = True
     softmax_scale: float = 1.0
     eps: float = 1e-6
-    intrinsic: str = "vnorm"       # "none" | "vnorm"
+    intrinsic: str = "vnorm"       # "none" | "vnorm" | "knorm"
+    mix: str = "head_adaptive"     # "head_adaptive" | "sum" | "div_only" | "imp_only" | "given_r"
     budget_mode: str = "fixed"     # "fixed" | "adaptive"
     budget_floor: int = 0
 
@@ -147,8 +154,12 @@ def diversity(Khat: np.ndarray) -> np.ndarray:
     return -(Khat @ kbar)
 
 
-def score_unit(K: np.ndarray, V: np.ndarray, Qg: np.ndarray, p: Params) -> Dict[str, np.ndarray]:
-    """All scores of one unit.  K, V [N, D]; Qg [G, W, D].  Arrays over the Nc candidates."""
+def score_unit(K: np.ndarray, V: np.ndarray, Qg: np.ndarray, p: Params,
+               r_given: float | None = None) -> Dict[str, np.ndarray]:
+    """All scores of one unit.  K, V [N, D]; Qg [G, W, D].  Arrays over the Nc candidates.
+
+    `r_given` is the caller's head weight for mix "given_r" (Table 4, offline W^head).
+    """
     K = np.asarray(K, dtype=np.float64)
     V = np.asarray(V, dtype=np.float64)
     N = K.shape[0]
@@ -156,9 +167,12 @@ def score_unit(K: np.ndarray, V: np.ndarray, Qg: np.ndarray, p: Params) -> Dict[
     Nc = N - W
     assert N >= 2 and Nc >= 1
     s_ex = extrinsic_importance(K, Qg, p)
-    if p.intrinsic == "vnorm":
-        vn = np.sqrt((V[:Nc] * V[:Nc]).sum(axis=1))
-        s_in_norm = minmax(vn, p.eps)
+    if p.intrinsic in ("vnorm", "knorm"):
+        if p.intrinsic == "vnorm":
+            s_in = np.sqrt((V[:Nc] * V[:Nc]).sum(axis=1))     # VNorm: ||V_i||
+        else:
+            s_in = -np.sqrt((K[:Nc] * K[:Nc]).sum(axis=1))    # KNorm: -||K_i||
+        s_in_norm = minmax(s_in, p.eps)
         s_in_scaled = scale_to_mean(s_in_norm, s_ex.mean(), p.eps)
         s_imp = s_ex + s_in_scaled                       # Eq. 2
     elif p.intrinsic == "none":
@@ -171,7 +185,19 @@ def score_unit(K: np.ndarray, V: np.ndarray, Qg: np.ndarray, p: Params) -> Dict[
     s_div = diversity(Khat)[:Nc]
     s_div_norm = minmax(s_div, p.eps)
     s_div_scaled = scale_to_mean(s_div_norm, s_imp.mean(), p.eps)
-    s_comp = (1.0 - r) * s_imp + r * s_div_scaled         # Eq. 5
+    if p.mix == "head_adaptive":
+        s_comp = (1.0 - r) * s_imp + r * s_div_scaled     # Eq. 5
+    elif p.mix == "given_r":
+        assert r_given is not None
+        s_comp = (1.0 - r_given) * s_imp + r_given * s_div_scaled
+    elif p.mix == "sum":
+        s_comp = s_imp + s_div_scaled
+    elif p.mix == "div_only":
+        s_comp = s_div_scaled.copy()
+    elif p.mix == "imp_only":
+        s_comp = s_imp.copy()
+    else:
+        raise ValueError(p.mix)
     return dict(s_ex=s_ex, s_in_scaled=s_in_scaled, s_imp=s_imp, s_div=s_div,
                 s_div_scaled=s_div_scaled, r=np.float64(r), s_comp=s_comp)
 
@@ -218,10 +244,11 @@ def select_unit(s_comp: np.ndarray, b_prime: int, N: int, W: int) -> np.ndarray:
 
 # --------------------------------------------------------------------------- whole layer
 
-def compress_layer(K: np.ndarray, V: np.ndarray, Q: np.ndarray, p: Params) -> Dict[str, object]:
+def compress_layer(K: np.ndarray, V: np.ndarray, Q: np.ndarray, p: Params,
+                   r_given: np.ndarray | None = None) -> Dict[str, object]:
     """Algorithm 1 for every (batch item, KV head) of one layer.
 
-    K, V [Bt, Hkv, N, D]; Q [Bt, Hq, W, D].  Returns
+    K, V [Bt, Hkv, N, D]; Q [Bt, Hq, W, D]; r_given [Bt, Hkv] for mix "given_r".  Returns
       scores [Bt, Hkv, N] (s_comp at candidates, +inf at window slots),
       redundancy [Bt, Hkv], counts [Bt, Hkv], offsets [Bt, Hkv+1],
       indices: list over batch of list over heads of int64 arrays,
@@ -241,7 +268,8 @@ def compress_layer(K: np.ndarray, V: np.ndarray, Q: np.ndarray, p: Params) -> Di
     V_out: List[List[np.ndarray]] = []
     for b in range(Bt):
         for h in range(Hkv):
-            u = score_unit(K[b, h], V[b, h], Q[b, h * G:(h + 1) * G], p)
+            u = score_unit(K[b, h], V[b, h], Q[b, h * G:(h + 1) * G], p,
+                           None if r_given is None else float(r_given[b, h]))
             scores[b, h, :Nc] = u["s_comp"]
             red[b, h] = u["r"]
         if p.budget_mode == "fixed":

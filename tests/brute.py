@@ -65,21 +65,31 @@ def topk_sorted(s, b):
     return sorted(order[:b])
 
 
-def mixkv_scores(K, V, Qg, scale, causal, pool_mode, pool_k, eps, use_vnorm=True):
+def mixkv_scores(K, V, Qg, scale, causal, pool_mode, pool_k, eps, use_vnorm=True, intrinsic=None,
+                 mix="head_adaptive", r_given=None):
     """s_comp over the candidates and the redundancy, through the explicit T x T cosine matrix.
 
     Follows Algorithm 1 step by step with plain loops; the diversity term uses
     Khat_i . Kbar = (1/T) * sum_j R_ij (row mean of the cosine matrix, diagonal
     included) and the redundancy the off-diagonal mean of R, i.e. the quadratic
-    forms that Eq. 3-4 of the paper collapse.
+    forms that Eq. 3-4 of the paper collapse.  `intrinsic` ("vnorm" | "knorm" |
+    "none", default from use_vnorm) and `mix` pick the ablation's variants
+    (Table 4): KNorm scores a key by minus its norm; "sum" adds importance and
+    scaled diversity without weights; "div_only" / "imp_only" keep one of them;
+    "given_r" mixes with the caller's weight.
     """
+    if intrinsic is None:
+        intrinsic = "vnorm" if use_vnorm else "none"
     N, W = len(K), len(Qg[0])
     Nc = N - W
     a = window_mean_attention(K, Qg, scale, causal)[:Nc]
     s_ex = pool(a, pool_mode, pool_k) if pool_mode != "none" else a
     mean = lambda x: sum(x) / len(x)
-    if use_vnorm:
-        vn = [math.sqrt(dot(v, v)) for v in V[:Nc]]
+    if intrinsic != "none":
+        if intrinsic == "vnorm":
+            vn = [math.sqrt(dot(v, v)) for v in V[:Nc]]
+        else:
+            vn = [-math.sqrt(dot(k, k)) for k in K[:Nc]]
         lo, hi = min(vn), max(vn)
         s_in = [(x - lo) / (hi - lo + eps) for x in vn]
         f = mean(s_ex) / (mean(s_in) + eps)
@@ -92,4 +102,8 @@ def mixkv_scores(K, V, Qg, scale, causal, pool_mode, pool_k, eps, use_vnorm=True
     lo, hi = min(s_div), max(s_div)
     dn = [(x - lo) / (hi - lo + eps) for x in s_div]
     f = mean(s_imp) / (mean(dn) + eps)
-    return [(1 - r) * si + r * f * d for si, d in zip(s_imp, dn)], r
+    wi, wd = {"head_adaptive": (1 - r, r), "sum": (1.0, 1.0), "div_only": (0.0, 1.0), "imp_only": (1.0, 0.0),
+              "given_r": (None, None)}[mix]
+    if mix == "given_r":
+        wi, wd = 1 - r_given, r_given
+    return [wi * si + wd * f * d for si, d in zip(s_imp, dn)], r

@@ -355,3 +355,84 @@ def test_score_unit_matches_brute_force_chain(seed, pool, causal, vnorm):
     assert abs(float(u["r"]) - r) < 1e-13
     np.testing.assert_allclose(u["s_comp"], want, rtol=1e-10, atol=1e-16)
     np.testing.assert_array_equal(O.select_unit(u["s_comp"], 6, 28, 3)[:6], brute.topk_sorted(want, 6))
+
+
+# ------------------------------------------------------------------ ablation variants (Sec. 4.3, Table 4)
+
+@pytest.mark.parametrize("intrinsic", ["vnorm", "knorm", "none"])
+@pytest.mark.parametrize("mix,rg", [("sum", None), ("div_only", None), ("imp_only", None), ("given_r", 0.37),
+                                    ("head_adaptive", None)])
+def test_variants_match_brute_force_chain(intrinsic, mix, rg):
+    K, V, Q = _rand_unit(31, N=26, D=6, G=2, W=3, offset=0.6)
+    K *= np.linspace(0.5, 2.0, 26)[:, None]              # spread the key norms
+    p = _params(B=9, pool="max", pool_kernel=3, softmax_scale=0.7, intrinsic=intrinsic, mix=mix)
+    want, r = brute.mixkv_scores(K.tolist(), V.tolist(), Q.tolist(), 0.7, True, "max", 3, p.eps,
+                                 intrinsic=intrinsic, mix=mix, r_given=rg)
+    u = O.score_unit(K, V, Q, p, rg)
+    assert abs(float(u["r"]) - r) < 1e-13                # the head's own redundancy is reported in every mode
+    np.testing.assert_allclose(u["s_comp"], want, rtol=1e-10, atol=1e-16)
+
+
+def test_given_r_limits_and_sum_decomposition():
+    K, V, Q = _rand_unit(32, N=30, D=8, G=2, W=3, offset=0.5)
+    base = dict(B=9, pool="avg", pool_kernel=3)
+    ha = O.score_unit(K, V, Q, _params(**base))
+    imp = O.score_unit(K, V, Q, _params(mix="imp_only", **base))["s_comp"]
+    div = O.score_unit(K, V, Q, _params(mix="div_only", **base))["s_comp"]
+    tot = O.score_unit(K, V, Q, _params(mix="sum", **base))["s_comp"]
+    g = _params(mix="given_r", **base)
+    np.testing.assert_array_equal(O.score_unit(K, V, Q, g, 0.0)["s_comp"], imp)
+    np.testing.assert_array_equal(O.score_unit(K, V, Q, g, 1.0)["s_comp"], div)
+    np.testing.assert_array_equal(O.score_unit(K, V, Q, g, float(ha["r"]))["s_comp"], ha["s_comp"])
+    np.testing.assert_allclose(tot, imp + div, rtol=1e-15)
+    np.testing.assert_array_equal(imp, ha["s_imp"])
+    # diversity alone: mean matched to the importance, smallest exactly zero, ranking that of s_div
+    np.testing.assert_allclose(div.mean(), imp.mean(), rtol=1e-4)
+    assert div.min() == 0.0
+    np.testing.assert_array_equal(np.argsort(-div, kind="stable"), np.argsort(-ha["s_div"], kind="stable"))
+    # importance alone with the intrinsic score off is the pooled window attention
+    ex = O.score_unit(K, V, Q, _params(mix="imp_only", intrinsic="none", **base))
+    np.testing.assert_array_equal(ex["s_comp"], ex["s_ex"])
+
+
+def test_knorm_equals_vnorm_on_values_with_mirrored_norms():
+    # min-max of -||K_i|| equals min-max of C - ||K_i||: feed the VNorm path values whose norms are
+    # C - ||K_i|| and both intrinsic terms must agree.
+    K, V, Q = _rand_unit(33, N=28, D=8, G=2, W=3)
+    K *= np.linspace(0.3, 3.0, 28)[:, None]
+    kn = np.sqrt((K * K).sum(axis=1))
+    C = kn.max() + 1.0
+    Vm = np.zeros_like(V)
+    Vm[:, 2] = C - kn
+    p = _params(B=9, pool="max", pool_kernel=3)
+    a = O.score_unit(K, V, Q, _params(B=9, pool="max", pool_kernel=3, intrinsic="knorm"))
+    b = O.score_unit(K, Vm, Q, p)
+    np.testing.assert_allclose(a["s_in_scaled"], b["s_in_scaled"], rtol=1e-12, atol=1e-18)
+    np.testing.assert_allclose(a["s_comp"], b["s_comp"], rtol=1e-12, atol=1e-18)
+    # the longest candidate key gets no intrinsic credit, the shortest the most
+    Nc = 25
+    assert a["s_in_scaled"][np.argmax(kn[:Nc])] == 0.0
+    assert np.argmax(a["s_in_scaled"]) == np.argmin(kn[:Nc])
+    # scaling all keys by c > 0 changes neither the cosine terms nor (up to eps) the KNorm term;
+    # the attention does change, so compare the intrinsic term relative to its own mean
+    a2 = O.score_unit(2.0 * K, V, Q, _params(B=9, pool="max", pool_kernel=3, intrinsic="knorm"))
+    np.testing.assert_allclose(a2["s_in_scaled"] / a2["s_ex"].mean(), a["s_in_scaled"] / a["s_ex"].mean(), rtol=1e-5)
+    np.testing.assert_allclose(a2["s_div"], a["s_div"], rtol=1e-12)
+
+
+def test_compress_layer_passes_given_r_per_unit():
+    rng = np.random.default_rng(34)
+    Bt, Hq, Hkv, N, D, W, B = 2, 4, 2, 24, 8, 3, 8
+    K = rng.standard_normal((Bt, Hkv, N, D)) + 0.5
+    V = rng.standard_normal((Bt, Hkv, N, D))
+    Q = rng.standard_normal((Bt, Hq, W, D))
+    rg = rng.uniform(0, 1, (Bt, Hkv))
+    p = O.Params(Hq, Hkv, W, B, pool="max", pool_kernel=3, mix="given_r")
+    out = O.compress_layer(K, V, Q, p, rg)
+    for b in range(Bt):
+        for h in range(Hkv):
+            want, r = brute.mixkv_scores(K[b, h].tolist(), V[b, h].tolist(), Q[b, 2 * h:2 * h + 2].tolist(), 1.0, True,
+                                         "max", 3, p.eps, mix="given_r", r_given=float(rg[b, h]))
+            np.testing.assert_allclose(out["scores"][b, h, :N - W], want, rtol=1e-10, atol=1e-16)
+            assert abs(out["redundancy"][b, h] - r) < 1e-13
+            np.testing.assert_array_equal(out["indices"][b][h][:B - W], brute.topk_sorted(want, B - W))
