@@ -38,22 +38,25 @@ MEASURED_TRAFFIC = {("c3", 28, "stats"): 513.5e6, ("c3", 28, "attn"): 281.6e6}
 _LAYERS = None
 _WL = None
 _BUDGET = None
+_VARIANT = ("vnorm", "head_adaptive")
+_RGIVEN = None
 
 
 def _oracle_layer(l):
     from oracle import mixkv_oracle as O
     wl = _WL
     p = O.Params(wl.n_q_heads, wl.n_kv_heads, wl.window, _BUDGET, pool=wl.pool, pool_kernel=wl.pool_kernel,
-                 softmax_scale=wl.softmax_scale, eps=wl.eps, budget_mode=wl.budget_mode, budget_floor=wl.budget_floor)
-    out = O.compress_layer(_LAYERS[l].K, _LAYERS[l].V, _LAYERS[l].Q, p)
+                 softmax_scale=wl.softmax_scale, eps=wl.eps, budget_mode=wl.budget_mode, budget_floor=wl.budget_floor,
+                 intrinsic=_VARIANT[0], mix=_VARIANT[1])
+    out = O.compress_layer(_LAYERS[l].K, _LAYERS[l].V, _LAYERS[l].Q, p, None if _RGIVEN is None else _RGIVEN[l])
     return l, [[i.astype(np.int32) for i in row] for row in out["indices"]], out["scores"].astype(np.float32)
 
 
-def cpu_baseline(wl, layers, budget, max_layers):
+def cpu_baseline(wl, layers, budget, max_layers, variant, r_given):
     """Time the oracle as it stands on a bounded sample (the first `max_layers` layers)."""
     import multiprocessing as mp
-    global _LAYERS, _WL, _BUDGET
-    _LAYERS, _WL, _BUDGET = layers, wl, budget
+    global _LAYERS, _WL, _BUDGET, _VARIANT, _RGIVEN
+    _LAYERS, _WL, _BUDGET, _VARIANT, _RGIVEN = layers, wl, budget, variant, r_given
     n = min(max_layers, len(layers))
     workers = max(1, min(n, len(os.sched_getaffinity(0)), int(os.environ.get("MIXKV_BENCH_WORKERS", "16"))))
     ctx = mp.get_context("fork")                   # children inherit the generated layers; no GPU state exists yet
@@ -69,12 +72,13 @@ def cpu_baseline(wl, layers, budget, max_layers):
                        f"process pool of {workers}, 1 BLAS thread each; scaled by {len(layers)}/{n}"), {r[0]: r for r in res}
 
 
-def algorithmic_bytes(wl, budget, scores_out):
-    """Bytes the method itself must move per unit: K once, V once, the window queries, the kept rows
-    read and written, the indices; optionally the N-long score vector."""
+def algorithmic_bytes(wl, budget, scores_out, reads_v=True):
+    """Bytes the method itself must move per unit: K once, V once (only when the value norm is
+    scored), the window queries, the kept rows read and written, the indices; optionally the N-long
+    score vector."""
     e = 2 if wl.dtype == "bf16" else 4
     n, d = wl.seq_len, wl.head_dim
-    per_unit = n * d * e * 2 + wl.group * wl.window * d * e + 4 * budget * d * e + 4 * budget
+    per_unit = n * d * e * (2 if reads_v else 1) + wl.group * wl.window * d * e + 4 * budget * d * e + 4 * budget
     if scores_out:
         per_unit += 4 * n
     return per_unit
@@ -91,6 +95,10 @@ def main():
     ap.add_argument("--copies", type=int, default=3, help="distinct device copies of the cache, used round-robin")
     ap.add_argument("--cpu-layers", type=int, default=28, help="layers the oracle baseline runs (0 = skip)")
     ap.add_argument("--no-parity", action="store_true")
+    ap.add_argument("--intrinsic", default="vnorm", choices=["none", "vnorm", "knorm"],
+                    help="intrinsic importance; anything but vnorm is an ablation variant, not the headline")
+    ap.add_argument("--mix", default="head_adaptive", choices=["head_adaptive", "sum", "div_only", "imp_only", "given_r"],
+                    help="score mix; anything but head_adaptive is an ablation variant, not the headline")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="also launch an elementwise copy kernel that reads and writes this many MiB: a kernel of "
                          "known traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
@@ -108,9 +116,13 @@ def main():
     layers = [synth.make_layer(wl, l) for l in range(wl.n_layers)]
     t_gen = time.perf_counter() - t0
 
+    r_given = None
+    if args.mix == "given_r":       # seeded stand-in for head weights measured offline
+        r_given = [np.random.default_rng([977, wl.cfg_id, l]).uniform(0, 1, (wl.batch, wl.n_kv_heads)).astype(np.float32)
+                   for l in range(wl.n_layers)]
     cpu, oracle_res = (None, {})
     if args.cpu_layers > 0:
-        cpu, oracle_res = cpu_baseline(wl, layers, budget, args.cpu_layers)
+        cpu, oracle_res = cpu_baseline(wl, layers, budget, args.cpu_layers, (args.intrinsic, args.mix), r_given)
 
     import torch
     from paper_2510_20707_amd import binding as B
@@ -118,7 +130,7 @@ def main():
     torch.cuda.set_device(dev)
     p = B.make_params(wl.dtype, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.seq_len, wl.window, budget,
                       pool=wl.pool, pool_kernel=wl.pool_kernel, softmax_scale=wl.softmax_scale, eps=wl.eps,
-                      budget_mode=wl.budget_mode, budget_floor=wl.budget_floor)
+                      budget_mode=wl.budget_mode, budget_floor=wl.budget_floor, intrinsic=args.intrinsic, mix=args.mix)
 
     def up(a):
         if wl.dtype == "bf16":
@@ -129,7 +141,9 @@ def main():
     copies = [base] + [[(k.clone(), v.clone(), q.clone()) for k, v, q in base] for _ in range(max(0, args.copies - 1))]
     outs = [B.alloc_layer_out(p, dev, scores=False, redundancy=True) for _ in layers]
     ws = B.alloc_workspace(p, len(layers), dev)
-    calls = [B.PreparedCall(p, [x[0] for x in c], [x[1] for x in c], [x[2] for x in c], outs, ws) for c in copies]
+    rg_dev = None if r_given is None else [torch.from_numpy(r).to(dev) for r in r_given]
+    calls = [B.PreparedCall(p, [x[0] for x in c], [x[1] for x in c], [x[2] for x in c], outs, ws, rg_dev)
+             for c in copies]
     stream = torch.cuda.current_stream()
 
     if args.calibrate_copy_mib > 0:
@@ -177,11 +191,12 @@ def main():
 
     units = wl.n_units
     e = 2 if wl.dtype == "bf16" else 4
-    bytes_step = algorithmic_bytes(wl, budget, scores_out=False) * units
+    reads_v = args.intrinsic == "vnorm"
+    bytes_step = algorithmic_bytes(wl, budget, scores_out=False, reads_v=reads_v) * units
     dom = max(("stats", "attn"), key=lambda k: stage_ms.get(k, 0.0))
     kv_bytes = wl.seq_len * wl.head_dim * e
     q_bytes = wl.group * wl.window * wl.head_dim * e
-    dom_bytes = ((2 * kv_bytes if dom == "stats" else kv_bytes) + q_bytes) * units      # per launch
+    dom_bytes = ((2 * kv_bytes if dom == "stats" and reads_v else kv_bytes) + q_bytes) * units      # per launch
     dom_s = stage_ms[dom] * 1e-3
     gemm_flops = 2.0 * wl.group * wl.window * wl.seq_len * wl.head_dim * units             # one pass
     out = {
@@ -193,7 +208,7 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.n_layers} layers x {wl.n_q_heads}Q/{wl.n_kv_heads}KV heads, D={wl.head_dim}, "
                                f"N={wl.seq_len}, W={wl.window}, B={budget}, batch={wl.batch}, {wl.budget_mode} budgets, "
-                               f"pool=max{wl.pool_kernel}, VNorm on",
+                               f"pool=max{wl.pool_kernel}, intrinsic={args.intrinsic}, mix={args.mix}",
                    "units": units, "input_copies_round_robin": len(copies)},
         "hbm_frac_end_to_end": bytes_step / (dt / args.steps) / HBM_PEAK,
         "algorithmic_bytes_per_step": bytes_step,
@@ -203,7 +218,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": dom + "_kernel", "achieved": dom_bytes / dom_s / 1e9,
                      "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": dom_bytes / dom_s / HBM_PEAK,
                      "algorithmic_bytes": dom_bytes, "avg_launch_us": dom_s * 1e6,
-                     "traffic": MEASURED_TRAFFIC.get((wl.name, wl.n_layers, dom))},
+                     "traffic": MEASURED_TRAFFIC.get((wl.name, wl.n_layers, dom)) if reads_v else None},
         "cpu_baseline": cpu,
         "parity_vs_oracle": parity,
         "host_gen_s": round(t_gen, 2),

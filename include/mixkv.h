@@ -39,7 +39,7 @@
 extern "C" {
 #endif
 
-#define MIXKV_VERSION 1
+#define MIXKV_VERSION 2
 #define MIXKV_MAX_LAYERS 128      /* layers per call */
 #define MIXKV_MAX_WINDOW 64
 #define MIXKV_MAX_GROUP_ROWS 512  /* G * W */
@@ -55,8 +55,20 @@ typedef enum {
 typedef enum { MIXKV_F32 = 0, MIXKV_BF16 = 1 } mixkv_dtype;
 typedef enum { MIXKV_POOL_NONE = 0, MIXKV_POOL_AVG = 1, MIXKV_POOL_MAX = 2 } mixkv_pool;
 typedef enum { MIXKV_BUDGET_FIXED = 0, MIXKV_BUDGET_HEAD_ADAPTIVE = 1 } mixkv_budget_mode;
-typedef enum { MIXKV_INTRINSIC_NONE = 0, MIXKV_INTRINSIC_VNORM = 1 } mixkv_intrinsic;
-typedef enum { MIXKV_MIX_HEAD_ADAPTIVE = 0 } mixkv_mix;
+/* Intrinsic importance (Sec. 3.2): none, the value norm |V_i| (the method's choice), or the negative
+ * key norm -|K_i| (the KNorm alternative of the ablation, Sec. 4.3 / Table 4). */
+typedef enum { MIXKV_INTRINSIC_NONE = 0, MIXKV_INTRINSIC_VNORM = 1, MIXKV_INTRINSIC_KNORM = 2 } mixkv_intrinsic;
+/* How importance and diversity are combined into s_comp (Sec. 3.3, Eq. 5 and the ablation rows of
+ * Table 4).  s_div_scaled is the diversity after min-max and mean matching in every mode.
+ *   HEAD_ADAPTIVE  (1 - r) s_imp + r s_div_scaled with the head's own redundancy r (Eq. 4, Eq. 5)
+ *   SUM            s_imp + s_div_scaled, no head weights
+ *   DIV_ONLY       s_div_scaled
+ *   IMP_ONLY       s_imp
+ *   GIVEN_R        Eq. 5 with the caller's weight mixkv_layer_in.r_given in place of r (head weights
+ *                  measured offline and shared by all samples) */
+typedef enum {
+  MIXKV_MIX_HEAD_ADAPTIVE = 0, MIXKV_MIX_SUM = 1, MIXKV_MIX_DIV_ONLY = 2, MIXKV_MIX_IMP_ONLY = 3, MIXKV_MIX_GIVEN_R = 4
+} mixkv_mix;
 
 typedef struct {
   mixkv_dtype dtype;         /* element type of K, V, Qwin and of K_out, V_out */
@@ -72,8 +84,8 @@ typedef struct {
   int32_t causal_window;     /* 1: window query w (position Nc+w) attends to keys 0..Nc+w; 0: to all N keys */
   float softmax_scale;       /* multiplies Q.K before the softmax; the library never rescales Q itself */
   float eps;                 /* the epsilon of the paper's min-max and mean-matching formulas, > 0 */
-  mixkv_intrinsic intrinsic; /* VNORM: importance = attention + scaled value norm (Sec. 3.2, Eq. 2) */
-  mixkv_mix mix;             /* HEAD_ADAPTIVE: (1 - r) * importance + r * diversity (Sec. 3.3, Eq. 5) */
+  mixkv_intrinsic intrinsic; /* VNORM: importance = attention + scaled value norm (Sec. 3.2, Eq. 2); see the enum */
+  mixkv_mix mix;             /* HEAD_ADAPTIVE: (1 - r) * importance + r * diversity (Sec. 3.3, Eq. 5); see the enum */
   mixkv_budget_mode budget_mode;
   int32_t budget_floor;      /* adaptive mode: minimum non-window rows per head, 0 <= floor <= B - W */
 } mixkv_params;
@@ -84,6 +96,8 @@ typedef struct {
   const void *V;             /* same shape and strides as K */
   int64_t kv_stride_b, kv_stride_h, kv_stride_n;   /* in elements; kv_stride_n >= D */
   const void *Qwin;          /* [batch, n_q_heads, W, D] contiguous, post-RoPE observation-window queries */
+  const float *r_given;      /* [batch, n_kv_heads] head weights for MIXKV_MIX_GIVEN_R, finite; ignored (may be
+                                NULL) in every other mix mode */
 } mixkv_layer_in;
 
 /* Outputs for one layer.  Which members are required is stated per entry point. */
@@ -115,8 +129,11 @@ mixkv_status mixkv_workspace_size(const mixkv_params *params, int32_t n_layers, 
  *          (Sec. 3.2, diversity metrics), min-max normalised and scaled to mean(s_imp) (Sec. 3.3);
  *   r      (N^2 |mean Khat|^2 - N) / (N (N-1))   (Sec. 3.3, Eq. 3-4);
  *   s_comp (1 - r) s_imp + r s_div_scaled         (Sec. 3.3, Eq. 5).
- * All minima, maxima and means are over the Nc candidates.
- * Writes out[l].scores (required) and out[l].redundancy (optional, may be NULL).
+ * All minima, maxima and means are over the Nc candidates.  params->intrinsic and params->mix
+ * switch to the ablation's variants (Sec. 4.3, Table 4): with KNORM, -|K_i| takes the place of
+ * |V_i| in s_imp; the mix modes change the last line only.
+ * Writes out[l].scores (required) and out[l].redundancy (optional, may be NULL; always the head's
+ * own r of Eq. 4, whatever the mix mode).
  */
 mixkv_status mixkv_score(const mixkv_params *params, const mixkv_layer_in *in, mixkv_layer_out *out,
                          int32_t n_layers, void *workspace, size_t workspace_bytes, void *hip_stream);

@@ -21,7 +21,8 @@ MIXKV_OK, MIXKV_ERR_INVALID_ARG, MIXKV_ERR_UNSUPPORTED, MIXKV_ERR_WORKSPACE_TOO_
 DTYPE = {"f32": 0, "bf16": 1}
 POOL = {"none": 0, "avg": 1, "max": 2}
 BUDGET_MODE = {"fixed": 0, "adaptive": 1}
-INTRINSIC = {"none": 0, "vnorm": 1}
+INTRINSIC = {"none": 0, "vnorm": 1, "knorm": 2}
+MIX = {"head_adaptive": 0, "sum": 1, "div_only": 2, "imp_only": 3, "given_r": 4}
 TORCH_DTYPE = {0: torch.float32, 1: torch.bfloat16}
 N_STAGES = 5
 
@@ -38,7 +39,7 @@ class MixkvParams(C.Structure):
 
 class MixkvLayerIn(C.Structure):
     _fields_ = [("K", C.c_void_p), ("V", C.c_void_p), ("kv_stride_b", C.c_int64), ("kv_stride_h", C.c_int64),
-                ("kv_stride_n", C.c_int64), ("Qwin", C.c_void_p)]
+                ("kv_stride_n", C.c_int64), ("Qwin", C.c_void_p), ("r_given", C.c_void_p)]
 
 
 class MixkvLayerOut(C.Structure):
@@ -91,9 +92,9 @@ def status_string(status: int) -> str:
 def make_params(dtype: str, batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, seq_len: int, window: int,
                 budget: int, pool: str = "max", pool_kernel: int = 7, causal_window: bool = True,
                 softmax_scale: float = 1.0, eps: float = 1e-6, intrinsic: str = "vnorm",
-                budget_mode: str = "fixed", budget_floor: int = 0) -> MixkvParams:
+                budget_mode: str = "fixed", budget_floor: int = 0, mix: str = "head_adaptive") -> MixkvParams:
     return MixkvParams(DTYPE[dtype], batch, n_q_heads, n_kv_heads, head_dim, seq_len, window, budget, POOL[pool],
-                       pool_kernel, int(causal_window), softmax_scale, eps, INTRINSIC[intrinsic], 0,
+                       pool_kernel, int(causal_window), softmax_scale, eps, INTRINSIC[intrinsic], MIX[mix],
                        BUDGET_MODE[budget_mode], budget_floor)
 
 
@@ -131,14 +132,17 @@ def _ptr(t: Optional[torch.Tensor]):
     return None if t is None else C.c_void_p(t.data_ptr())
 
 
-def _in_array(Ks, Vs, Qs):
+def _in_array(Ks, Vs, Qs, r_given=None):
+    """r_given: per layer a contiguous f32 [batch, Hkv] device tensor (mix "given_r"), or None."""
     n = len(Ks)
     arr = (MixkvLayerIn * n)()
     for i, (K, V, Q) in enumerate(zip(Ks, Vs, Qs)):
         assert K.dim() == 4 and K.stride(3) == 1 and V.shape == K.shape and V.stride() == K.stride()
         assert Q is None or Q.is_contiguous()
+        rg = None if r_given is None else r_given[i]
+        assert rg is None or (rg.is_contiguous() and rg.dtype == torch.float32 and rg.shape == K.shape[:2])
         arr[i] = MixkvLayerIn(K.data_ptr(), V.data_ptr(), K.stride(0), K.stride(1), K.stride(2),
-                              None if Q is None else Q.data_ptr())
+                              None if Q is None else Q.data_ptr(), None if rg is None else rg.data_ptr())
     return arr
 
 
@@ -177,9 +181,10 @@ def _ws(workspace: Optional[torch.Tensor]):
     return C.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()
 
 
-def mixkv_score(p: MixkvParams, Ks, Vs, Qs, outs: Sequence[LayerOut], workspace: torch.Tensor, stream=None):
+def mixkv_score(p: MixkvParams, Ks, Vs, Qs, outs: Sequence[LayerOut], workspace: torch.Tensor, stream=None,
+                r_given=None):
     wp, wb = _ws(workspace)
-    _check(lib().mixkv_score(C.byref(p), _in_array(Ks, Vs, Qs), _out_array(outs), len(outs), wp, wb, _stream(stream)),
+    _check(lib().mixkv_score(C.byref(p), _in_array(Ks, Vs, Qs, r_given), _out_array(outs), len(outs), wp, wb, _stream(stream)),
            "mixkv_score")
 
 
@@ -188,20 +193,21 @@ def mixkv_select(p: MixkvParams, outs: Sequence[LayerOut], workspace: Optional[t
     _check(lib().mixkv_select(C.byref(p), _out_array(outs), len(outs), wp, wb, _stream(stream)), "mixkv_select")
 
 
-def mixkv_compress(p: MixkvParams, Ks, Vs, Qs, outs: Sequence[LayerOut], workspace: torch.Tensor, stream=None):
+def mixkv_compress(p: MixkvParams, Ks, Vs, Qs, outs: Sequence[LayerOut], workspace: torch.Tensor, stream=None,
+                   r_given=None):
     wp, wb = _ws(workspace)
-    _check(lib().mixkv_compress(C.byref(p), _in_array(Ks, Vs, Qs), _out_array(outs), len(outs), wp, wb,
+    _check(lib().mixkv_compress(C.byref(p), _in_array(Ks, Vs, Qs, r_given), _out_array(outs), len(outs), wp, wb,
                                 _stream(stream)), "mixkv_compress")
 
 
 class PreparedCall:
     """The C argument arrays of one call, built once (so a timed loop measures the library, not ctypes)."""
 
-    def __init__(self, p: MixkvParams, Ks, Vs, Qs, outs: Sequence[LayerOut], workspace: torch.Tensor):
+    def __init__(self, p: MixkvParams, Ks, Vs, Qs, outs: Sequence[LayerOut], workspace: torch.Tensor, r_given=None):
         self.p, self.n = p, len(outs)
-        self.ins, self.outs = _in_array(Ks, Vs, Qs), _out_array(outs)
+        self.ins, self.outs = _in_array(Ks, Vs, Qs, r_given), _out_array(outs)
         self.wp, self.wb = _ws(workspace)
-        self._keep = (Ks, Vs, Qs, outs, workspace)
+        self._keep = (Ks, Vs, Qs, outs, workspace, r_given)
         self._L = lib()
 
     def compress(self, stream=None):

@@ -30,8 +30,10 @@ mixkv_status make_shape(const mixkv_params *p, Shape *s) {
   if (p->causal_window != 0 && p->causal_window != 1) return MIXKV_ERR_INVALID_ARG;
   if (!(p->softmax_scale > 0.f) || !std::isfinite(p->softmax_scale)) return MIXKV_ERR_INVALID_ARG;
   if (!(p->eps > 0.f) || !std::isfinite(p->eps)) return MIXKV_ERR_INVALID_ARG;
-  if (p->intrinsic != MIXKV_INTRINSIC_NONE && p->intrinsic != MIXKV_INTRINSIC_VNORM) return MIXKV_ERR_INVALID_ARG;
-  if (p->mix != MIXKV_MIX_HEAD_ADAPTIVE) return MIXKV_ERR_UNSUPPORTED;
+  if (p->intrinsic != MIXKV_INTRINSIC_NONE && p->intrinsic != MIXKV_INTRINSIC_VNORM &&
+      p->intrinsic != MIXKV_INTRINSIC_KNORM)
+    return MIXKV_ERR_INVALID_ARG;
+  if ((int)p->mix < MIXKV_MIX_HEAD_ADAPTIVE || (int)p->mix > MIXKV_MIX_GIVEN_R) return MIXKV_ERR_INVALID_ARG;
   if (p->budget_mode != MIXKV_BUDGET_FIXED && p->budget_mode != MIXKV_BUDGET_HEAD_ADAPTIVE) return MIXKV_ERR_INVALID_ARG;
   const int G = p->n_q_heads / p->n_kv_heads;
   if ((int64_t)G * p->window > MIXKV_MAX_GROUP_ROWS) return MIXKV_ERR_UNSUPPORTED;
@@ -53,7 +55,7 @@ mixkv_status make_shape(const mixkv_params *p, Shape *s) {
   s->units_per_layer = s->batch * s->hkv;
   s->nb_rows = (s->QT * 32 + 255) / 256 * 256;
   s->pool = p->pool; s->pool_k = p->pool == MIXKV_POOL_NONE ? 1 : p->pool_kernel;
-  s->causal = p->causal_window; s->intrinsic = p->intrinsic;
+  s->causal = p->causal_window; s->intrinsic = p->intrinsic; s->mix = p->mix;
   s->adaptive = p->budget_mode == MIXKV_BUDGET_HEAD_ADAPTIVE; s->floor_ = s->adaptive ? p->budget_floor : 0;
   s->scale_log2e = (float)((double)p->softmax_scale * 1.4426950408889634);
   s->eps = p->eps;
@@ -143,6 +145,7 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
       if (li.kv_stride_n < s.D || li.kv_stride_h < 0 || li.kv_stride_b < 0) return MIXKV_ERR_INVALID_ARG;
       if ((li.kv_stride_n * eb) % 16 || (li.kv_stride_h * eb) % 16 || (li.kv_stride_b * eb) % 16) return MIXKV_ERR_INVALID_ARG;
       if ((stages & kScore) && (!li.Qwin || !aligned16(li.Qwin))) return MIXKV_ERR_INVALID_ARG;
+      if ((stages & kScore) && s.mix == MIXKV_MIX_GIVEN_R && !li.r_given) return MIXKV_ERR_INVALID_ARG;
     }
     const mixkv_layer_out &lo = out[l];
     if (stages == kScore && !lo.scores) return MIXKV_ERR_INVALID_ARG;
@@ -187,7 +190,8 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
     for (int l = 0; l < nl; ++l) {
       if (in) {
         const mixkv_layer_in &li = in[l0 + l];
-        ti.l[l] = LayerIn{li.K, li.V, li.Qwin, li.kv_stride_b, li.kv_stride_h, li.kv_stride_n};
+        ti.l[l] = LayerIn{li.K, li.V, li.Qwin, li.kv_stride_b, li.kv_stride_h, li.kv_stride_n,
+                          s.mix == MIXKV_MIX_GIVEN_R ? li.r_given : nullptr};
       }
       const mixkv_layer_out &lo = out[l0 + l];
       float *scores = lo.scores;
@@ -204,7 +208,7 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
           ok(timed(2, [&] {
             return fused ? launch_mixsel(s, fused_select || cand_m > 0, to, ws, w, unit0, nunits, ti,
                                          fused_gather ? eb : 0, cand_m, stream)
-                         : launch_mix(s, to, ws, w, unit0, nunits, stream);
+                         : launch_mix(s, ti, to, ws, w, unit0, nunits, stream);
           }));
     }
     if (result == MIXKV_OK && (stages & kSelect) && !fused_select)

@@ -18,6 +18,7 @@ constexpr int kMaxStreamGrid = 1024;    // upper bound on the workgroups of a st
 struct LayerIn {
   const void *K, *V, *Q;
   int64_t sb, sh, sn;                  // K/V strides in elements
+  const float *r_given;                // caller's head weights (mix mode GIVEN_R), else null
 };
 struct LayerInTable { LayerIn l[kLayersPerLaunch]; };
 
@@ -39,7 +40,7 @@ struct Shape {
   int32_t Npad;          // nchunks * chunk, row length of the per-unit float arrays
   int32_t units_per_layer;
   int32_t nb_rows;       // row length of the per-unit exponent offsets: QT*32 rounded up to 256
-  int32_t pool, pool_k, causal, intrinsic, adaptive, floor_;
+  int32_t pool, pool_k, causal, intrinsic, mix, adaptive, floor_;
   float scale_log2e;     // softmax_scale * log2(e)
   float eps;
 };
@@ -73,8 +74,21 @@ hipError_t launch_stats(const Shape &s, int dtype, const LayerInTable &in, char 
                         int nunits, int grid, int64_t slot0, hipStream_t st);
 hipError_t launch_attn(const Shape &s, int dtype, const LayerInTable &in, const LayerOutTable &out, char *ws,
                        const Workspace &w, int64_t unit0, int nunits, int grid, int64_t slot0, hipStream_t st);
-hipError_t launch_mix(const Shape &s, const LayerOutTable &out, char *ws, const Workspace &w, int64_t unit0,
-                      int nunits, hipStream_t st);
+hipError_t launch_mix(const Shape &s, const LayerInTable &in, const LayerOutTable &out, char *ws, const Workspace &w,
+                      int64_t unit0, int nunits, hipStream_t st);
+// Weights of s_imp and of the scaled diversity in s_comp (Sec. 3.3, Eq. 5; Table 4's variants);
+// r is the head's redundancy, rg the caller's weight.
+__device__ __forceinline__ void mix_weights(int mix, float r, float rg, float &wi, float &wd) {
+  switch (mix) {
+    case MIXKV_MIX_SUM: wi = 1.f; wd = 1.f; break;
+    case MIXKV_MIX_DIV_ONLY: wi = 0.f; wd = 1.f; break;
+    case MIXKV_MIX_IMP_ONLY: wi = 1.f; wd = 0.f; break;
+    case MIXKV_MIX_GIVEN_R: wi = 1.f - rg; wd = rg; break;
+    default: wi = 1.f - r; wd = r; break;
+  }
+}
+// |K_i| from its stored reciprocal (0 for a key that normalises to the zero vector).
+__device__ __forceinline__ float neg_key_norm(float inv_norm) { return inv_norm > 0.f ? -1.f / inv_norm : 0.f; }
 hipError_t launch_select(const Shape &s, const LayerOutTable &out, int nlayers, hipStream_t st);
 // Head-adaptive budget split from the per-head candidate lists (cand_m entries each) in the workspace.
 int adaptive_candidates(const Shape &s);   // cand_m, or 0 if the lists would be too long

@@ -8,7 +8,8 @@
 // the head differ at all, which keeps the first histogram from collapsing into one bin.
 //
 // Paper: Sec. 3.2 Eq. 2 (importance = attention + scaled value norm), Sec. 3.3 (min-max and mean
-// matching of the diversity, Eq. 5 mix), Sec. 3.1 / Algorithm 1 (TopB with B' = B - W).
+// matching of the diversity, Eq. 5 mix), Sec. 3.1 / Algorithm 1 (TopB with B' = B - W); Sec. 4.3 /
+// Table 4 for the variants (key-norm intrinsic score, un-weighted and one-sided mixes, given weights).
 #include "mixkv_internal.h"
 #include "mixkv_wave.h"
 
@@ -122,8 +123,11 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
   const float *invn = reinterpret_cast<const float *>(ws + w.invnorm) + unit * s.Npad;
   const float r = reinterpret_cast<const float *>(ws + w.rbar)[unit];
   const int Nc = s.Nc, N = s.N, base = tid * EPT;
-  const bool use_v = s.intrinsic == MIXKV_INTRINSIC_VNORM;
+  const bool use_v = s.intrinsic != MIXKV_INTRINSIC_NONE;      // an intrinsic score takes part (held in v[])
+  const bool knorm = s.intrinsic == MIXKV_INTRINSIC_KNORM;
   const float inv_n = 1.f / (float)Nc;
+  float wi, wd;
+  mix_weights(s.mix, r, s.mix == MIXKV_MIX_GIVEN_R ? in.l[layer].r_given[bh] : 0.f, wi, wd);
 
   // ---- load: EPT consecutive candidates per thread (the per-unit rows are padded past Nc)
   float a[EPT], v[EPT], d[EPT];
@@ -135,7 +139,8 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
       ar = *reinterpret_cast<const float4 *>(araw + i);
       kr = *reinterpret_cast<const float4 *>(kdot + i);
       nr = *reinterpret_cast<const float4 *>(invn + i);
-      if (use_v) vr = *reinterpret_cast<const float4 *>(vnorm + i);
+      if (knorm) vr = make_float4(neg_key_norm(nr.x), neg_key_norm(nr.y), neg_key_norm(nr.z), neg_key_norm(nr.w));
+      else if (use_v) vr = *reinterpret_cast<const float4 *>(vnorm + i);
     }
     a[e4] = ar.x; a[e4 + 1] = ar.y; a[e4 + 2] = ar.z; a[e4 + 3] = ar.w;
     v[e4] = vr.x; v[e4 + 1] = vr.y; v[e4 + 2] = vr.z; v[e4 + 3] = vr.w;
@@ -204,7 +209,7 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
       }
     }
   }
-  // One round of statistics over the candidates.  The means of the min-max normalised value norm
+  // One round of statistics over the candidates.  The means of the min-max normalised intrinsic score
   // and diversity follow from the plain sums: sum((x - min) * c) = (sum(x) - Nc * min) * c, and
   // mean(s_imp) = mean(s_ex) + f_in * mean(s_in_norm).
   float st[7] = {0.f, 0.f, 0.f, INFINITY, INFINITY, -INFINITY, -INFINITY};   // sums a, v, d | min v, d | max v, d
@@ -227,7 +232,7 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
 #pragma unroll
   for (int e = 0; e < EPT; ++e) {
     const float imp = use_v ? a[e] + (v[e] - vmin) * rvden * f_in : a[e];          // Eq. 2
-    a[e] = (1.f - r) * imp + r * ((d[e] - dmin) * rdden * f_div);                  // Eq. 5: s_comp
+    a[e] = wi * imp + wd * ((d[e] - dmin) * rdden * f_div);                        // Eq. 5: s_comp
   }
 
   if (O.scores) {

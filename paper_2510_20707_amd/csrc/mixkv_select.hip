@@ -255,7 +255,7 @@ __device__ __forceinline__ float pooled(const float *a, int i, int n, int mode, 
 }
 
 __global__ __launch_bounds__(kSelectThreads) void mix_kernel(Shape s, LayerOutTable out, char *ws, Workspace w,
-                                                            int64_t unit0) {
+                                                            int64_t unit0, LayerInTable in) {
   __shared__ float fscr[kSelectThreads / 64 + 1];
   const int ul = blockIdx.x, tid = threadIdx.x, NT = blockDim.x;
   const int64_t unit = unit0 + ul;
@@ -268,15 +268,19 @@ __global__ __launch_bounds__(kSelectThreads) void mix_kernel(Shape s, LayerOutTa
   auto sdiv_at = [&](int i) { return -kdot[i] * invn[i]; };   // s_div_i = -Khat_i . Kbar
   const float r = reinterpret_cast<const float *>(ws + w.rbar)[unit];
   const int Nc = s.Nc;
-  const bool use_v = s.intrinsic == MIXKV_INTRINSIC_VNORM;
+  const bool use_v = s.intrinsic != MIXKV_INTRINSIC_NONE;
+  const bool knorm = s.intrinsic == MIXKV_INTRINSIC_KNORM;
+  auto sin_at = [&](int i) { return knorm ? neg_key_norm(invn[i]) : vnorm[i]; };   // intrinsic score (Sec. 3.2)
   const float inv_n = 1.f / (float)Nc;
+  float wi, wd;
+  mix_weights(s.mix, r, s.mix == MIXKV_MIX_GIVEN_R ? in.l[layer].r_given[bh] : 0.f, wi, wd);
 
   float sum_ex = 0.f, vmin = INFINITY, vmax = -INFINITY, dmin = INFINITY, dmax = -INFINITY;
   for (int i = tid; i < Nc; i += NT) {
     float a = pooled(araw, i, Nc, s.pool, s.pool_k);
     scores[i] = a;                          // parked here; re-read by the same thread below
     sum_ex += a;
-    if (use_v) { float v = vnorm[i]; vmin = fminf(vmin, v); vmax = fmaxf(vmax, v); }
+    if (use_v) { float v = sin_at(i); vmin = fminf(vmin, v); vmax = fmaxf(vmax, v); }
     float d = sdiv_at(i);
     dmin = fminf(dmin, d);
     dmax = fmaxf(dmax, d);
@@ -293,7 +297,7 @@ __global__ __launch_bounds__(kSelectThreads) void mix_kernel(Shape s, LayerOutTa
   }
   float sum_in = 0.f, sum_dn = 0.f;
   for (int i = tid; i < Nc; i += NT) {
-    if (use_v) sum_in += (vnorm[i] - vmin) / vden;
+    if (use_v) sum_in += (sin_at(i) - vmin) / vden;
     sum_dn += (sdiv_at(i) - dmin) / dden;
   }
   const float mean_dn = block_reduce<OpSum>(sum_dn, fscr) * inv_n;
@@ -304,7 +308,7 @@ __global__ __launch_bounds__(kSelectThreads) void mix_kernel(Shape s, LayerOutTa
   float sum_imp = 0.f;
   for (int i = tid; i < Nc; i += NT) {
     float imp = scores[i];
-    if (use_v) imp += ((vnorm[i] - vmin) / vden) * f_in;
+    if (use_v) imp += ((sin_at(i) - vmin) / vden) * f_in;
     scores[i] = imp;
     sum_imp += imp;
   }
@@ -312,7 +316,7 @@ __global__ __launch_bounds__(kSelectThreads) void mix_kernel(Shape s, LayerOutTa
   const float f_div = mean_imp / (mean_dn + s.eps);
   for (int i = tid; i < Nc; i += NT) {
     float dn = (sdiv_at(i) - dmin) / dden;
-    scores[i] = (1.f - r) * scores[i] + r * (dn * f_div);
+    scores[i] = wi * scores[i] + wd * (dn * f_div);
   }
   for (int i = Nc + tid; i < s.N; i += NT) scores[i] = INFINITY;
 }
@@ -532,9 +536,9 @@ __global__ __launch_bounds__(256) void gather_kernel(Shape s, int eb, LayerInTab
 // ------------------------------------------------------------------------------------------------
 // launchers
 // ------------------------------------------------------------------------------------------------
-hipError_t launch_mix(const Shape &s, const LayerOutTable &out, char *ws, const Workspace &w, int64_t unit0, int nunits,
-                      hipStream_t st) {
-  hipLaunchKernelGGL(mix_kernel, dim3(nunits), dim3(kSelectThreads), 0, st, s, out, ws, w, unit0);
+hipError_t launch_mix(const Shape &s, const LayerInTable &in, const LayerOutTable &out, char *ws, const Workspace &w,
+                      int64_t unit0, int nunits, hipStream_t st) {
+  hipLaunchKernelGGL(mix_kernel, dim3(nunits), dim3(kSelectThreads), 0, st, s, out, ws, w, unit0, in);
   return hipGetLastError();
 }
 

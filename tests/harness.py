@@ -62,15 +62,24 @@ def host_bits(wl: synth.Workload, arr: np.ndarray) -> np.ndarray:
     return np.ascontiguousarray(arr, dtype=np.float32).view(np.uint32)
 
 
-def run_compress(wl: synth.Workload, layers, device="cuda:0", want_scores=True, **over):
-    """mixkv_compress on a list of synth.Layer.  Returns (params, list of LayerOut on device)."""
+def given_weights(wl: synth.Workload, layer_id: int) -> np.ndarray:
+    """Seeded head weights in [0, 1) for mix "given_r", float32-exact, [batch, Hkv]."""
+    rng = np.random.default_rng([977, wl.cfg_id, layer_id])
+    return rng.uniform(0.0, 1.0, (wl.batch, wl.n_kv_heads)).astype(np.float32)
+
+
+def run_compress(wl: synth.Workload, layers, device="cuda:0", want_scores=True, r_given=None, **over):
+    """mixkv_compress on a list of synth.Layer.  `r_given`: per layer a float32 [batch, Hkv] array
+    (mix "given_r").  Returns (params, list of LayerOut on device)."""
     p = gpu_params(wl, **over)
     Ks = [to_device(wl, l.K, device) for l in layers]
     Vs = [to_device(wl, l.V, device) for l in layers]
     Qs = [to_device(wl, l.Q, device) for l in layers]
     outs = [B.alloc_layer_out(p, device, scores=want_scores) for _ in layers]
     ws = B.alloc_workspace(p, len(layers), device)
-    B.mixkv_compress(p, Ks, Vs, Qs, outs, ws)
+    rg = None if r_given is None else [torch.from_numpy(np.ascontiguousarray(r, dtype=np.float32)).to(device)
+                                        for r in r_given]
+    B.mixkv_compress(p, Ks, Vs, Qs, outs, ws, r_given=rg)
     torch.cuda.synchronize()
     return p, outs
 
@@ -105,9 +114,11 @@ def check_topk_set(dtype, kept: np.ndarray, s_ora: np.ndarray, k: int, what=""):
     return int(((s_ora >= tau - band) & (s_ora <= tau + band)).sum())   # band population (k-th itself included)
 
 
-def check_layer(wl: synth.Workload, lay: synth.Layer, p: B.MixkvParams, out: B.LayerOut, units=None, **over):
+def check_layer(wl: synth.Workload, lay: synth.Layer, p: B.MixkvParams, out: B.LayerOut, units=None, r_given=None,
+                **over):
     """Compare one layer of GPU output with the oracle.  `units`: iterable of (b, h) to check with
-    the oracle (default all); invariants are checked on every unit."""
+    the oracle (default all); invariants are checked on every unit.  `r_given`: this layer's
+    [batch, Hkv] weights for mix "given_r"."""
     op = oracle_params(wl, **over)
     Bt, Hkv, N, D, W = wl.batch, wl.n_kv_heads, wl.seq_len, wl.head_dim, wl.window
     Bud = op.budget
@@ -144,7 +155,8 @@ def check_layer(wl: synth.Workload, lay: synth.Layer, p: B.MixkvParams, out: B.L
                 assert np.all(np.isposinf(sc_g[b, h, Nc:]))
             if (b, h) not in todo:
                 continue
-            u = O.score_unit(lay.K[b, h], lay.V[b, h], lay.Q[b, h * G:(h + 1) * G], op)
+            u = O.score_unit(lay.K[b, h], lay.V[b, h], lay.Q[b, h * G:(h + 1) * G], op,
+                             None if r_given is None else float(r_given[b, h]))
             s_ora_heads[h] = u["s_comp"]
             what = f"{wl.name} b{b} h{h}"
             if sc_g is not None:

@@ -26,14 +26,14 @@ def test_library_exports_every_declared_symbol():
     L = B.lib()
     for n in set(names):
         assert hasattr(L, n), n
-    assert L.mixkv_version() == 1
+    assert L.mixkv_version() == 2
     assert B.status_string(0) == "ok" and "workspace" in B.status_string(3)
 
 
 def test_params_struct_matches_header_layout():
     # 17 four-byte members in the header, no padding
     assert C.sizeof(B.MixkvParams) == 17 * 4
-    assert C.sizeof(B.MixkvLayerIn) == 6 * 8 and C.sizeof(B.MixkvLayerOut) == 7 * 8
+    assert C.sizeof(B.MixkvLayerIn) == 7 * 8 and C.sizeof(B.MixkvLayerOut) == 7 * 8
 
 
 def test_workspace_size_scales_with_layers_and_is_aligned():
@@ -63,6 +63,20 @@ def test_bad_params_are_rejected(kw, status):
     with pytest.raises(B.MixkvError) as e:
         B.mixkv_workspace_size(_good(**kw), 1)
     assert e.value.status == status
+
+
+@pytest.mark.parametrize("field,value", [("mix", 5), ("mix", -1), ("intrinsic", 3), ("intrinsic", -1)])
+def test_unknown_variant_enums_are_rejected(field, value):
+    p = _good()
+    setattr(p, field, value)
+    with pytest.raises(B.MixkvError) as e:
+        B.mixkv_workspace_size(p, 1)
+    assert e.value.status == B.MIXKV_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("kw", [dict(mix=m) for m in B.MIX] + [dict(intrinsic=i) for i in B.INTRINSIC])
+def test_every_variant_is_accepted(kw):
+    assert B.mixkv_workspace_size(_good(**kw), 1) > 0
 
 
 def test_bad_call_arguments_are_rejected_before_any_launch():

@@ -21,10 +21,11 @@ def _run_and_check(wl, n_layers=None, units=None, layer_ids=None, **over):
     layers = [synth.make_layer(wl, l) for l in layer_ids]
     _say(f"[case] {wl.name} dtype={wl.dtype} L={len(layers)} Bt={wl.batch} Hq={wl.n_q_heads} Hkv={wl.n_kv_heads} "
          f"D={wl.head_dim} N={wl.seq_len} W={wl.window} B={over.get('budget', wl.budget)} over={over}")
-    p, outs = H.run_compress(wl, layers, **over)
+    rg = [H.given_weights(wl, l) for l in layer_ids] if over.get("mix") == "given_r" else None
+    p, outs = H.run_compress(wl, layers, r_given=rg, **over)
     tot = dict(max_err=0.0, band=0, exact=0, checked=0)
-    for lay, out in zip(layers, outs):
-        st = H.check_layer(wl, lay, p, out, units=units, **over)
+    for i, (lay, out) in enumerate(zip(layers, outs)):
+        st = H.check_layer(wl, lay, p, out, units=units, r_given=None if rg is None else rg[i], **over)
         tot["max_err"] = max(tot["max_err"], st["max_err"])
         for k in ("band", "exact", "checked"):
             tot[k] += st[k]
@@ -181,3 +182,46 @@ def test_score_entry_point_matches_compress_scores():
     B.mixkv_select(p, [sel])
     torch.cuda.synchronize()
     assert torch.equal(sel.indices, ref[0].indices) and torch.equal(sel.counts, ref[0].counts)
+
+
+# ------------------------------------------------------------------ ablation variants (Sec. 4.3, Table 4)
+
+VARIANTS = [dict(intrinsic="knorm"), dict(mix="sum"), dict(mix="div_only"), dict(mix="imp_only"), dict(mix="given_r"),
+            dict(mix="imp_only", intrinsic="none"), dict(mix="sum", intrinsic="knorm"),
+            dict(mix="given_r", intrinsic="knorm", pool="avg")]
+
+
+@pytest.mark.parametrize("over", VARIANTS)
+def test_c1_scoring_variants(over):
+    _run_and_check(WL["c1"], **over)
+
+
+@pytest.mark.parametrize("over", VARIANTS[:5])
+def test_c2_scoring_variants(over):
+    _run_and_check(WL["c2"], **over)
+
+
+def test_scoring_variants_adaptive_budgets_and_long_fallback():
+    wl = WL["c2"].with_(name="adaptive-variants", seq_len=1024, text_suffix_start=960, batch=2, budget=96,
+                        budget_mode="adaptive", budget_floor=16, sigma=(0.1, 0.8))
+    _run_and_check(wl, layer_ids=[1], mix="given_r", intrinsic="knorm")
+    # sequences too long for the fused mix kernel take the plain one
+    wl = WL["c2"].with_(name="long", seq_len=33000, batch=1, n_q_heads=2, n_kv_heads=1, text_suffix_start=32900)
+    _run_and_check(wl, n_layers=1, budget=400, mix="sum", intrinsic="knorm")
+
+
+def test_given_r_needs_the_weights():
+    wl = WL["c1"]
+    with pytest.raises(B.MixkvError) as e:
+        H.run_compress(wl, [synth.make_layer(wl, 0)], mix="given_r")      # rejected on the host, nothing launched
+    assert e.value.status == B.MIXKV_ERR_INVALID_ARG
+
+
+def test_given_r_equal_to_own_redundancy_reproduces_the_head_adaptive_mix():
+    wl = WL["c2"]
+    lay = synth.make_layer(wl, 0)
+    p, outs = H.run_compress(wl, [lay])
+    red = outs[0].redundancy.cpu().numpy()
+    p2, outs2 = H.run_compress(wl, [lay], r_given=[red], mix="given_r")
+    assert torch.equal(outs[0].scores, outs2[0].scores) and torch.equal(outs[0].indices, outs2[0].indices)
+    assert torch.equal(outs[0].redundancy, outs2[0].redundancy)
