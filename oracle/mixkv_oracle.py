@@ -36,7 +36,12 @@ constant):
     as VNorm; the un-weighted row "s_imp + s_div" adds the scaled diversity
     (the one Eq. 5 mixes), "s_div only" ranks by that scaled diversity alone,
     "importance only" by s_imp alone; the offline head weights of Table 4 are a
-    caller-given r per unit that replaces Eq. 4's value in Eq. 5.
+    caller-given r per unit that replaces Eq. 4's value in Eq. 5;
+  * the budget B of Sec. 3.1 / Algorithm 1 may be given per (layer, KV head),
+    as the layer-wise and head-wise allocation schemes the method is combined
+    with do (Sec. 4.1 and the appendix's baseline details; Table 1): head h
+    then keeps its own
+    b_h - W best candidates and the window, exactly as in the fixed case.
 
 Every function is pinned by tests/test_oracle_*.py against brute force, closed
 forms and library routines; the whole path against the authors' own code is
@@ -65,7 +70,7 @@ class Params:
     eps: float = 1e-6
     intrinsic: str = "vnorm"       # "none" | "vnorm" | "knorm"
     mix: str = "head_adaptive"     # "head_adaptive" | "sum" | "div_only" | "imp_only" | "given_r"
-    budget_mode: str = "fixed"     # "fixed" | "adaptive"
+    budget_mode: str = "fixed"     # "fixed" | "adaptive" | "per_head" (budgets passed to compress_layer)
     budget_floor: int = 0
 
     @property
@@ -245,10 +250,12 @@ def select_unit(s_comp: np.ndarray, b_prime: int, N: int, W: int) -> np.ndarray:
 # --------------------------------------------------------------------------- whole layer
 
 def compress_layer(K: np.ndarray, V: np.ndarray, Q: np.ndarray, p: Params,
-                   r_given: np.ndarray | None = None) -> Dict[str, object]:
+                   r_given: np.ndarray | None = None, head_budgets: np.ndarray | None = None) -> Dict[str, object]:
     """Algorithm 1 for every (batch item, KV head) of one layer.
 
-    K, V [Bt, Hkv, N, D]; Q [Bt, Hq, W, D]; r_given [Bt, Hkv] for mix "given_r".  Returns
+    K, V [Bt, Hkv, N, D]; Q [Bt, Hq, W, D]; r_given [Bt, Hkv] for mix "given_r";
+    head_budgets [Hkv] (rows kept by each head of this layer, window included)
+    for budget mode "per_head".  Returns
       scores [Bt, Hkv, N] (s_comp at candidates, +inf at window slots),
       redundancy [Bt, Hkv], counts [Bt, Hkv], offsets [Bt, Hkv+1],
       indices: list over batch of list over heads of int64 arrays,
@@ -276,6 +283,10 @@ def compress_layer(K: np.ndarray, V: np.ndarray, Q: np.ndarray, p: Params,
             bp = np.full(Hkv, p.budget - W, dtype=np.int64)
         elif p.budget_mode == "adaptive":
             bp = adaptive_budgets(scores[b, :, :Nc], p.budget, W, p.budget_floor)
+        elif p.budget_mode == "per_head":
+            hb = np.asarray(head_budgets, dtype=np.int64)
+            assert hb.shape == (Hkv,) and np.all(hb >= W) and np.all(hb <= N)
+            bp = hb - W                                   # Algorithm 1's budget line, per head
         else:
             raise ValueError(p.budget_mode)
         idx_b, k_b, v_b = [], [], []

@@ -436,3 +436,42 @@ def test_compress_layer_passes_given_r_per_unit():
             np.testing.assert_allclose(out["scores"][b, h, :N - W], want, rtol=1e-10, atol=1e-16)
             assert abs(out["redundancy"][b, h] - r) < 1e-13
             np.testing.assert_array_equal(out["indices"][b][h][:B - W], brute.topk_sorted(want, B - W))
+
+
+# ------------------------------------------------------------------ budgets given per layer and head
+
+def test_per_head_budgets_are_independent_fixed_selections():
+    rng = np.random.default_rng(41)
+    Bt, Hq, Hkv, N, D, W = 2, 6, 3, 40, 8, 4
+    K = rng.standard_normal((Bt, Hkv, N, D)) + 0.4
+    V = rng.standard_normal((Bt, Hkv, N, D))
+    Q = rng.standard_normal((Bt, Hq, W, D))
+    hb = np.array([4, 17, 40])                            # window only / some / everything
+    p = O.Params(Hq, Hkv, W, 20, pool="max", pool_kernel=3, budget_mode="per_head")
+    out = O.compress_layer(K, V, Q, p, head_budgets=hb)
+    np.testing.assert_array_equal(out["counts"], np.tile(hb, (Bt, 1)))
+    for b in range(Bt):
+        np.testing.assert_array_equal(out["offsets"][b], [0, 4, 21, 61])
+        for h in range(Hkv):
+            want, _ = brute.mixkv_scores(K[b, h].tolist(), V[b, h].tolist(), Q[b, 2 * h:2 * h + 2].tolist(), 1.0, True,
+                                         "max", 3, p.eps)
+            idx = out["indices"][b][h]
+            np.testing.assert_array_equal(idx[:hb[h] - W], brute.topk_sorted(want, int(hb[h]) - W))
+            np.testing.assert_array_equal(idx[hb[h] - W:], np.arange(N - W, N))
+            np.testing.assert_array_equal(out["K_out"][b][h], K[b, h][idx])
+            np.testing.assert_array_equal(out["V_out"][b][h], V[b, h][idx])
+            # a head's result is the fixed-budget result at its own budget
+            fixed = O.compress_layer(K, V, Q, O.Params(Hq, Hkv, W, int(hb[h]), pool="max", pool_kernel=3))
+            np.testing.assert_array_equal(idx, fixed["indices"][b][h])
+
+
+def test_per_head_budgets_nest():
+    # the candidates kept at budget b are among those kept at budget b + 1
+    K, V, Q = _rand_unit(42, N=30, D=8, G=2, W=3)
+    p = O.Params(2, 1, 3, 10, budget_mode="per_head")
+    prev = set()
+    for b in range(3, 31):
+        out = O.compress_layer(K[None, None], V[None, None], Q[None], p, head_budgets=np.array([b]))
+        cur = set(out["indices"][0][0].tolist())
+        assert len(cur) == b and prev <= cur
+        prev = cur
