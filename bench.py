@@ -40,23 +40,26 @@ _WL = None
 _BUDGET = None
 _VARIANT = ("vnorm", "head_adaptive")
 _RGIVEN = None
+_HEAD_BUDGETS = None
 
 
 def _oracle_layer(l):
     from oracle import mixkv_oracle as O
     wl = _WL
+    hb = _HEAD_BUDGETS
     p = O.Params(wl.n_q_heads, wl.n_kv_heads, wl.window, _BUDGET, pool=wl.pool, pool_kernel=wl.pool_kernel,
-                 softmax_scale=wl.softmax_scale, eps=wl.eps, budget_mode=wl.budget_mode, budget_floor=wl.budget_floor,
-                 intrinsic=_VARIANT[0], mix=_VARIANT[1])
-    out = O.compress_layer(_LAYERS[l].K, _LAYERS[l].V, _LAYERS[l].Q, p, None if _RGIVEN is None else _RGIVEN[l])
+                 softmax_scale=wl.softmax_scale, eps=wl.eps, budget_mode=wl.budget_mode if hb is None else "per_head",
+                 budget_floor=wl.budget_floor, intrinsic=_VARIANT[0], mix=_VARIANT[1])
+    out = O.compress_layer(_LAYERS[l].K, _LAYERS[l].V, _LAYERS[l].Q, p, None if _RGIVEN is None else _RGIVEN[l],
+                           None if hb is None else hb[l])
     return l, [[i.astype(np.int32) for i in row] for row in out["indices"]], out["scores"].astype(np.float32)
 
 
-def cpu_baseline(wl, layers, budget, max_layers, variant, r_given):
+def cpu_baseline(wl, layers, budget, max_layers, variant, r_given, head_budgets):
     """Time the oracle as it stands on a bounded sample (the first `max_layers` layers)."""
     import multiprocessing as mp
-    global _LAYERS, _WL, _BUDGET, _VARIANT, _RGIVEN
-    _LAYERS, _WL, _BUDGET, _VARIANT, _RGIVEN = layers, wl, budget, variant, r_given
+    global _LAYERS, _WL, _BUDGET, _VARIANT, _RGIVEN, _HEAD_BUDGETS
+    _LAYERS, _WL, _BUDGET, _VARIANT, _RGIVEN, _HEAD_BUDGETS = layers, wl, budget, variant, r_given, head_budgets
     n = min(max_layers, len(layers))
     workers = max(1, min(n, len(os.sched_getaffinity(0)), int(os.environ.get("MIXKV_BENCH_WORKERS", "16"))))
     ctx = mp.get_context("fork")                   # children inherit the generated layers; no GPU state exists yet
@@ -102,6 +105,9 @@ def main():
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="also launch an elementwise copy kernel that reads and writes this many MiB: a kernel of "
                          "known traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
+    ap.add_argument("--budgets", default="config", choices=["config", "pyramid"],
+                    help="pyramid: budgets given per layer, falling linearly from 2B-W in the first layer to W in the "
+                         "last (mean B); a per-head-table variant of a fixed-budget workload, not the headline")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path has no cross-GPU step); use --gpus 1",
@@ -120,17 +126,27 @@ def main():
     if args.mix == "given_r":       # seeded stand-in for head weights measured offline
         r_given = [np.random.default_rng([977, wl.cfg_id, l]).uniform(0, 1, (wl.batch, wl.n_kv_heads)).astype(np.float32)
                    for l in range(wl.n_layers)]
+    head_budgets = None
+    if args.budgets == "pyramid":
+        if wl.budget_mode != "fixed":
+            sys.exit("bench.py: --budgets pyramid needs a fixed-budget workload")
+        per_layer = np.round(np.linspace(2 * budget - wl.window, wl.window, wl.n_layers)).astype(np.int32)
+        head_budgets = np.repeat(per_layer[:, None], wl.n_kv_heads, axis=1)
+    budget_mode = wl.budget_mode if head_budgets is None else "per_head"
+    capacity = budget if head_budgets is None else int(head_budgets.max())      # rows per head in the output buffers
     cpu, oracle_res = (None, {})
     if args.cpu_layers > 0:
-        cpu, oracle_res = cpu_baseline(wl, layers, budget, args.cpu_layers, (args.intrinsic, args.mix), r_given)
+        cpu, oracle_res = cpu_baseline(wl, layers, budget, args.cpu_layers, (args.intrinsic, args.mix), r_given,
+                                       head_budgets)
 
     import torch
     from paper_2510_20707_amd import binding as B
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    p = B.make_params(wl.dtype, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.seq_len, wl.window, budget,
+    p = B.make_params(wl.dtype, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.seq_len, wl.window, capacity,
                       pool=wl.pool, pool_kernel=wl.pool_kernel, softmax_scale=wl.softmax_scale, eps=wl.eps,
-                      budget_mode=wl.budget_mode, budget_floor=wl.budget_floor, intrinsic=args.intrinsic, mix=args.mix)
+                      budget_mode=budget_mode, budget_floor=wl.budget_floor, intrinsic=args.intrinsic, mix=args.mix,
+                      head_budgets=head_budgets)
 
     def up(a):
         if wl.dtype == "bf16":
@@ -182,7 +198,7 @@ def main():
                 off = 0
                 for h in range(wl.n_kv_heads):
                     n = idx_o[b][h].shape[0]
-                    g = idx_g[b, h] if wl.budget_mode == "fixed" else idx_g.reshape(wl.batch, -1)[b, off:off + n]
+                    g = idx_g[b, h] if budget_mode == "fixed" else idx_g.reshape(wl.batch, -1)[b, off:off + n]
                     same += int(np.array_equal(g, idx_o[b][h]))
                     total += 1
                     off += n
@@ -207,7 +223,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.n_layers} layers x {wl.n_q_heads}Q/{wl.n_kv_heads}KV heads, D={wl.head_dim}, "
-                               f"N={wl.seq_len}, W={wl.window}, B={budget}, batch={wl.batch}, {wl.budget_mode} budgets, "
+                               f"N={wl.seq_len}, W={wl.window}, B={budget}, batch={wl.batch}, "
+                               f"{wl.budget_mode if head_budgets is None else 'per-layer pyramid (mean B)'} budgets, "
                                f"pool=max{wl.pool_kernel}, intrinsic={args.intrinsic}, mix={args.mix}",
                    "units": units, "input_copies_round_robin": len(copies)},
         "hbm_frac_end_to_end": bytes_step / (dt / args.steps) / HBM_PEAK,

@@ -39,7 +39,7 @@
 extern "C" {
 #endif
 
-#define MIXKV_VERSION 2
+#define MIXKV_VERSION 3
 #define MIXKV_MAX_LAYERS 128      /* layers per call */
 #define MIXKV_MAX_WINDOW 64
 #define MIXKV_MAX_GROUP_ROWS 512  /* G * W */
@@ -54,7 +54,12 @@ typedef enum {
 
 typedef enum { MIXKV_F32 = 0, MIXKV_BF16 = 1 } mixkv_dtype;
 typedef enum { MIXKV_POOL_NONE = 0, MIXKV_POOL_AVG = 1, MIXKV_POOL_MAX = 2 } mixkv_pool;
-typedef enum { MIXKV_BUDGET_FIXED = 0, MIXKV_BUDGET_HEAD_ADAPTIVE = 1 } mixkv_budget_mode;
+/* How many rows a head keeps (Sec. 3.1: the budget B; Algorithm 1, budget line).
+ *   FIXED          every head of every layer keeps params->budget rows
+ *   HEAD_ADAPTIVE  the heads of one (layer, batch item) share a pool of n_kv_heads * budget rows, split by score
+ *   PER_HEAD       the caller gives the rows kept by every (layer, KV head) in params->head_budgets: layer-wise
+ *                  (pyramid) and static head-wise allocation schemes (Sec. 4.1, Table 1) compute such tables */
+typedef enum { MIXKV_BUDGET_FIXED = 0, MIXKV_BUDGET_HEAD_ADAPTIVE = 1, MIXKV_BUDGET_PER_HEAD = 2 } mixkv_budget_mode;
 /* Intrinsic importance (Sec. 3.2): none, the value norm |V_i| (the method's choice), or the negative
  * key norm -|K_i| (the KNorm alternative of the ablation, Sec. 4.3 / Table 4). */
 typedef enum { MIXKV_INTRINSIC_NONE = 0, MIXKV_INTRINSIC_VNORM = 1, MIXKV_INTRINSIC_KNORM = 2 } mixkv_intrinsic;
@@ -78,7 +83,8 @@ typedef struct {
   int32_t head_dim;          /* D: 64 or 128 */
   int32_t seq_len;           /* N >= 2, window included */
   int32_t window;            /* 1 <= W <= MIXKV_MAX_WINDOW and W < N; the queries are the last W positions */
-  int32_t budget;            /* W <= B <= N rows kept per head (fixed mode) / on average (adaptive mode) */
+  int32_t budget;            /* W <= B <= N rows kept per head (fixed mode) / on average (adaptive mode) / on average
+                                at most (per-head mode: n_kv_heads * B rows is the capacity of one batch item's outputs) */
   mixkv_pool pool;           /* 1-D pooling of the window attention over candidates */
   int32_t pool_kernel;       /* odd, 1..63; ignored for MIXKV_POOL_NONE */
   int32_t causal_window;     /* 1: window query w (position Nc+w) attends to keys 0..Nc+w; 0: to all N keys */
@@ -88,6 +94,9 @@ typedef struct {
   mixkv_mix mix;             /* HEAD_ADAPTIVE: (1 - r) * importance + r * diversity (Sec. 3.3, Eq. 5); see the enum */
   mixkv_budget_mode budget_mode;
   int32_t budget_floor;      /* adaptive mode: minimum non-window rows per head, 0 <= floor <= B - W */
+  const int32_t *head_budgets; /* HOST, per-head mode only (else ignored, may be NULL): [n_layers, n_kv_heads], rows
+                                kept by KV head h of layer l (the l-th layer struct of the call), window included,
+                                the same for every batch item; W <= b <= N and sum_h b[l][h] <= n_kv_heads * B */
 } mixkv_params;
 
 /* One layer of the cache to compress. */
@@ -105,17 +114,23 @@ typedef struct {
   float *scores;             /* [batch, n_kv_heads, N]: the mixed score s_comp at candidates, +inf at the W window slots */
   float *redundancy;         /* [batch, n_kv_heads]: the head's redundancy r (Eq. 4) */
   int32_t *indices;          /* kept positions, ascending per head, the W window positions last.
-                                fixed: [batch, n_kv_heads, B]; adaptive: [batch, n_kv_heads * B], heads packed back to back */
+                                fixed: [batch, n_kv_heads, B]; adaptive and per-head: [batch, n_kv_heads * B], heads packed
+                                back to back (per-head mode may leave the tail of a batch item's slots untouched) */
   int32_t *counts;           /* [batch, n_kv_heads] rows kept per head (B in fixed mode) */
-  int32_t *offsets;          /* adaptive: [batch, n_kv_heads + 1] exclusive prefix sums of counts; may be NULL in fixed mode */
+  int32_t *offsets;          /* adaptive and per-head: [batch, n_kv_heads + 1] exclusive prefix sums of counts; may be
+                                NULL in fixed mode */
   void *K_out, *V_out;       /* rows of K / V at `indices`, copied bit for bit, D contiguous.
-                                fixed: [batch, n_kv_heads, B, D]; adaptive: [batch, n_kv_heads * B, D] packed like indices */
+                                fixed: [batch, n_kv_heads, B, D]; adaptive and per-head: [batch, n_kv_heads * B, D] packed
+                                like indices */
 } mixkv_layer_out;
 
 /*
  * Bytes of device workspace mixkv_score / mixkv_compress need for `n_layers`
- * layers of this shape (mixkv_select needs none and accepts NULL).  Host only;
- * touches no GPU.  The workspace needs no initialisation and 256-byte alignment.
+ * layers of this shape.  mixkv_select needs none and accepts NULL, except in
+ * per-head budget mode, where it stages the budget table there and needs
+ * n_layers * n_kv_heads * 4 bytes (this function's figure is always enough).
+ * Host only; touches no GPU (head_budgets is not read).  The workspace needs no
+ * initialisation and 256-byte alignment.
  */
 mixkv_status mixkv_workspace_size(const mixkv_params *params, int32_t n_layers, size_t *bytes);
 
@@ -146,7 +161,8 @@ mixkv_status mixkv_score(const mixkv_params *params, const mixkv_layer_in *in, m
  * Fixed mode: each head keeps its B' best candidates.  Head-adaptive mode, per (layer, batch
  * item): every head keeps its budget_floor best candidates, then the remaining
  * n_kv_heads * (B' - budget_floor) slots go to the best remaining candidates of all heads
- * together (ties: smaller head, then smaller position).
+ * together (ties: smaller head, then smaller position).  Per-head mode: head h of layer l keeps its
+ * head_budgets[l][h] - W best candidates.
  */
 mixkv_status mixkv_select(const mixkv_params *params, mixkv_layer_out *out, int32_t n_layers,
                           void *workspace, size_t workspace_bytes, void *hip_stream);

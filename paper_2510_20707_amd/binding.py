@@ -12,6 +12,7 @@ import os
 from dataclasses import dataclass
 from typing import List, Optional, Sequence
 
+import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -20,7 +21,7 @@ LIB_PATH = os.path.join(_HERE, "libmixkv.so")
 MIXKV_OK, MIXKV_ERR_INVALID_ARG, MIXKV_ERR_UNSUPPORTED, MIXKV_ERR_WORKSPACE_TOO_SMALL, MIXKV_ERR_HIP = range(5)
 DTYPE = {"f32": 0, "bf16": 1}
 POOL = {"none": 0, "avg": 1, "max": 2}
-BUDGET_MODE = {"fixed": 0, "adaptive": 1}
+BUDGET_MODE = {"fixed": 0, "adaptive": 1, "per_head": 2}
 INTRINSIC = {"none": 0, "vnorm": 1, "knorm": 2}
 MIX = {"head_adaptive": 0, "sum": 1, "div_only": 2, "imp_only": 3, "given_r": 4}
 TORCH_DTYPE = {0: torch.float32, 1: torch.bfloat16}
@@ -33,7 +34,7 @@ class MixkvParams(C.Structure):
         ("head_dim", C.c_int32), ("seq_len", C.c_int32), ("window", C.c_int32), ("budget", C.c_int32),
         ("pool", C.c_int), ("pool_kernel", C.c_int32), ("causal_window", C.c_int32),
         ("softmax_scale", C.c_float), ("eps", C.c_float), ("intrinsic", C.c_int), ("mix", C.c_int),
-        ("budget_mode", C.c_int), ("budget_floor", C.c_int32),
+        ("budget_mode", C.c_int), ("budget_floor", C.c_int32), ("head_budgets", C.c_void_p),
     ]
 
 
@@ -92,10 +93,18 @@ def status_string(status: int) -> str:
 def make_params(dtype: str, batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, seq_len: int, window: int,
                 budget: int, pool: str = "max", pool_kernel: int = 7, causal_window: bool = True,
                 softmax_scale: float = 1.0, eps: float = 1e-6, intrinsic: str = "vnorm",
-                budget_mode: str = "fixed", budget_floor: int = 0, mix: str = "head_adaptive") -> MixkvParams:
-    return MixkvParams(DTYPE[dtype], batch, n_q_heads, n_kv_heads, head_dim, seq_len, window, budget, POOL[pool],
-                       pool_kernel, int(causal_window), softmax_scale, eps, INTRINSIC[intrinsic], MIX[mix],
-                       BUDGET_MODE[budget_mode], budget_floor)
+                budget_mode: str = "fixed", budget_floor: int = 0, mix: str = "head_adaptive",
+                head_budgets=None) -> MixkvParams:
+    """`head_budgets`: host int32 array [n_layers, n_kv_heads] for budget mode "per_head"."""
+    p = MixkvParams(DTYPE[dtype], batch, n_q_heads, n_kv_heads, head_dim, seq_len, window, budget, POOL[pool],
+                    pool_kernel, int(causal_window), softmax_scale, eps, INTRINSIC[intrinsic], MIX[mix],
+                    BUDGET_MODE[budget_mode], budget_floor, None)
+    if head_budgets is not None:
+        hb = np.ascontiguousarray(head_budgets, dtype=np.int32)
+        assert hb.ndim == 2 and hb.shape[1] == n_kv_heads
+        p._head_budgets_keep = hb                   # the struct only holds the address
+        p.head_budgets = hb.ctypes.data
+    return p
 
 
 @dataclass

@@ -10,7 +10,8 @@ int stream_chunk_keys(int dtype, int D);
 int max_adaptive_heads();
 bool mixsel_supported(const Shape &s);
 hipError_t launch_mixsel(const Shape &s, bool select, const LayerOutTable &out, char *ws, const Workspace &w,
-                         int64_t unit0, int nunits, const LayerInTable &in, int gather_eb, int cand_m, hipStream_t st);
+                         int64_t unit0, int nunits, const LayerInTable &in, int gather_eb, int cand_m,
+                         const int32_t *budgets, hipStream_t st);
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -34,7 +35,9 @@ mixkv_status make_shape(const mixkv_params *p, Shape *s) {
       p->intrinsic != MIXKV_INTRINSIC_KNORM)
     return MIXKV_ERR_INVALID_ARG;
   if ((int)p->mix < MIXKV_MIX_HEAD_ADAPTIVE || (int)p->mix > MIXKV_MIX_GIVEN_R) return MIXKV_ERR_INVALID_ARG;
-  if (p->budget_mode != MIXKV_BUDGET_FIXED && p->budget_mode != MIXKV_BUDGET_HEAD_ADAPTIVE) return MIXKV_ERR_INVALID_ARG;
+  if (p->budget_mode != MIXKV_BUDGET_FIXED && p->budget_mode != MIXKV_BUDGET_HEAD_ADAPTIVE &&
+      p->budget_mode != MIXKV_BUDGET_PER_HEAD)
+    return MIXKV_ERR_INVALID_ARG;
   const int G = p->n_q_heads / p->n_kv_heads;
   if ((int64_t)G * p->window > MIXKV_MAX_GROUP_ROWS) return MIXKV_ERR_UNSUPPORTED;
   if (p->budget_mode == MIXKV_BUDGET_HEAD_ADAPTIVE) {
@@ -57,6 +60,7 @@ mixkv_status make_shape(const mixkv_params *p, Shape *s) {
   s->pool = p->pool; s->pool_k = p->pool == MIXKV_POOL_NONE ? 1 : p->pool_kernel;
   s->causal = p->causal_window; s->intrinsic = p->intrinsic; s->mix = p->mix;
   s->adaptive = p->budget_mode == MIXKV_BUDGET_HEAD_ADAPTIVE; s->floor_ = s->adaptive ? p->budget_floor : 0;
+  s->per_head = p->budget_mode == MIXKV_BUDGET_PER_HEAD;
   s->scale_log2e = (float)((double)p->softmax_scale * 1.4426950408889634);
   s->eps = p->eps;
   return MIXKV_OK;
@@ -69,6 +73,7 @@ void carve_workspace(const Shape &s, int64_t units, Workspace *w) {
   // one slot per run of the streaming kernels: each launch group owns kMaxStreamGrid + its units
   const size_t per_group = (size_t)kMaxStreamGrid + (size_t)kLayersPerLaunch * s.units_per_layer;
   const size_t groups = ((size_t)(units / s.units_per_layer) + kLayersPerLaunch - 1) / kLayersPerLaunch;
+  w->budgets = take(s.per_head ? (size_t)(units / s.units_per_layer) * s.hkv * 4 : 0);
   w->part_ml = take(groups * per_group * QTR * 8);
   w->part_ksum = take(groups * per_group * s.D * 4);
   w->rbar = take((size_t)units * 4);
@@ -133,9 +138,23 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
   const int64_t units = (int64_t)n_layers * s.units_per_layer;
   Workspace w;
   carve_workspace(s, units, &w);
-  if (stages & kScore) {   // selection on caller-provided scores needs no workspace
+  // selection on caller-provided scores needs no workspace, except for the per-head budget table
+  const bool stage_budgets = s.per_head && (stages & kSelect);
+  if ((stages & kScore) || stage_budgets) {
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return MIXKV_ERR_INVALID_ARG;
-    if (workspace_bytes < w.total) return MIXKV_ERR_WORKSPACE_TOO_SMALL;
+    if (workspace_bytes < ((stages & kScore) ? w.total : w.part_ml)) return MIXKV_ERR_WORKSPACE_TOO_SMALL;
+  }
+  if (stage_budgets) {
+    if (!params->head_budgets) return MIXKV_ERR_INVALID_ARG;
+    for (int l = 0; l < n_layers; ++l) {
+      int64_t sum = 0;
+      for (int h = 0; h < s.hkv; ++h) {
+        const int32_t b = params->head_budgets[(size_t)l * s.hkv + h];
+        if (b < s.W || b > s.N) return MIXKV_ERR_INVALID_ARG;
+        sum += b;
+      }
+      if (sum > (int64_t)s.hkv * s.B) return MIXKV_ERR_INVALID_ARG;
+    }
   }
 
   for (int l = 0; l < n_layers; ++l) {
@@ -152,7 +171,7 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
     if (stages == kSelect && !lo.scores) return MIXKV_ERR_INVALID_ARG;
     if (stages & kSelect) {
       if (!lo.indices || !lo.counts) return MIXKV_ERR_INVALID_ARG;
-      if (s.adaptive && !lo.offsets) return MIXKV_ERR_INVALID_ARG;
+      if ((s.adaptive || s.per_head) && !lo.offsets) return MIXKV_ERR_INVALID_ARG;
     }
     if (stages & kGather) {
       if (!lo.K_out || !lo.V_out || !aligned16(lo.K_out) || !aligned16(lo.V_out)) return MIXKV_ERR_INVALID_ARG;
@@ -167,6 +186,12 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&num_cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || num_cus < 1)
       return MIXKV_ERR_HIP;
+  }
+  const int32_t *budgets_dev = nullptr;
+  if (stage_budgets) {
+    int32_t *dst = reinterpret_cast<int32_t *>(ws + w.budgets);
+    if (upload_ints(params->head_budgets, n_layers * s.hkv, dst, stream) != hipSuccess) return MIXKV_ERR_HIP;
+    budgets_dev = dst;
   }
   StageTimer timed;
   timed.stream = stream;
@@ -200,6 +225,7 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
       to.l[l] = LayerOut{scores, lo.redundancy, lo.indices, lo.counts, lo.offsets, lo.K_out, lo.V_out};
     }
     const int nunits = nl * s.units_per_layer;
+    const int32_t *budgets_l0 = budgets_dev ? budgets_dev + (size_t)l0 * s.hkv : nullptr;
     if (result == MIXKV_OK && (stages & kScore)) {
       const int grid = stream_grid(s, nunits, num_cus);
       const int64_t slot0 = (int64_t)(l0 / kLayersPerLaunch) * (kMaxStreamGrid + kLayersPerLaunch * s.units_per_layer);
@@ -207,13 +233,13 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
           ok(timed(1, [&] { return launch_attn(s, params->dtype, ti, to, ws, w, unit0, nunits, grid, slot0, stream); })) &&
           ok(timed(2, [&] {
             return fused ? launch_mixsel(s, fused_select || cand_m > 0, to, ws, w, unit0, nunits, ti,
-                                         fused_gather ? eb : 0, cand_m, stream)
+                                         fused_gather ? eb : 0, cand_m, budgets_l0, stream)
                          : launch_mix(s, ti, to, ws, w, unit0, nunits, stream);
           }));
     }
     if (result == MIXKV_OK && (stages & kSelect) && !fused_select)
       ok(timed(3, [&] {
-        return cand_m > 0 ? launch_select_candidates(s, to, ws, w, unit0, nl, cand_m, stream) : launch_select(s, to, nl, stream);
+        return cand_m > 0 ? launch_select_candidates(s, to, ws, w, unit0, nl, cand_m, stream) : launch_select(s, to, nl, budgets_l0, stream);
       }));
     if (result == MIXKV_OK && (stages & kGather) && !fused_gather)
       ok(timed(4, [&] { return launch_gather(s, params->dtype, ti, to, nl, stream); }));

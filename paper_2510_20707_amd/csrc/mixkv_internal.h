@@ -40,13 +40,15 @@ struct Shape {
   int32_t Npad;          // nchunks * chunk, row length of the per-unit float arrays
   int32_t units_per_layer;
   int32_t nb_rows;       // row length of the per-unit exponent offsets: QT*32 rounded up to 256
-  int32_t pool, pool_k, causal, intrinsic, mix, adaptive, floor_;
+  int32_t pool, pool_k, causal, intrinsic, mix, adaptive, per_head, floor_;
   float scale_log2e;     // softmax_scale * log2(e)
   float eps;
 };
 
 // Workspace carve-up (byte offsets from a 256-byte aligned base).  Sizes are per call (all units).
 struct Workspace {
+  size_t budgets;        // int32  [layers][hkv]             per-head budget mode: the caller's table (first, so
+                         //                                  that selection alone can run on a workspace this small)
   size_t part_ml;        // float2 [slots][QT*32]            per-run (max, sum) of each softmax row, log2 domain
   size_t part_ksum;      // float  [slots][D]                per-run partial sums of normalised keys
   size_t rbar;           // float  [units]
@@ -89,7 +91,11 @@ __device__ __forceinline__ void mix_weights(int mix, float r, float rg, float &w
 }
 // |K_i| from its stored reciprocal (0 for a key that normalises to the zero vector).
 __device__ __forceinline__ float neg_key_norm(float inv_norm) { return inv_norm > 0.f ? -1.f / inv_norm : 0.f; }
-hipError_t launch_select(const Shape &s, const LayerOutTable &out, int nlayers, hipStream_t st);
+// `budgets` (per-head budget mode, else null): device table [layers of this launch][hkv].
+hipError_t launch_select(const Shape &s, const LayerOutTable &out, int nlayers, const int32_t *budgets, hipStream_t st);
+// Copies `n` ints from host memory to device memory through kernel arguments (no memcpy, so the
+// call neither synchronises nor depends on how the host memory was allocated).
+hipError_t upload_ints(const int32_t *host, int n, int32_t *dev, hipStream_t st);
 // Head-adaptive budget split from the per-head candidate lists (cand_m entries each) in the workspace.
 int adaptive_candidates(const Shape &s);   // cand_m, or 0 if the lists would be too long
 hipError_t launch_select_candidates(const Shape &s, const LayerOutTable &out, char *ws, const Workspace &w, int64_t unit0,

@@ -109,7 +109,8 @@ __device__ __forceinline__ void hist_add(int *hist, int bin, bool on) {
 
 template <int THREADS, int EPT, bool SELECT>
 __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable out, char *ws, Workspace w,
-                                                           int64_t unit0, LayerInTable in, int gather_eb, int cand_m) {
+                                                           int64_t unit0, LayerInTable in, int gather_eb, int cand_m,
+                                                           const int32_t *budgets) {
   constexpr int NW = THREADS / 64;
   extern __shared__ float a_s[];                        // [Nc] raw window attention of this head
   __shared__ MsScratch sc;
@@ -245,14 +246,23 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
   if constexpr (!SELECT) return;
 
   // ---- TopB': the B' candidates with the largest s_comp, ties to the smaller index.  In fixed
-  // budget mode B' = B - W and the indices are the head's final ones.  With cand_m > 0 (head-adaptive
+  // budget mode B' = B - W and the indices are the head's final ones; with a budget table (per-head
+  // mode) B is the head's own entry and the heads of a batch item are packed back to back.  With cand_m > 0 (head-adaptive
   // mode) the head's best cand_m candidates go to the workspace with their keys instead: no head
   // can end up keeping more than that, so the budget split only has to look at those.
   const bool cand = cand_m > 0;
-  int32_t *idx = cand ? reinterpret_cast<int32_t *>(ws + w.cand_idx) + unit * kMaxCandPerHead
-                      : O.indices + (int64_t)bh * s.B;
+  const int h = bh % s.hkv, b = bh / s.hkv;
+  int Bh = s.B, row0 = h * s.B;                        // rows this head keeps, and its first row in the batch item
+  if (budgets) {
+    const int32_t *bl = budgets + layer * s.hkv;
+    row0 = 0;
+    for (int j = 0; j < h; ++j) row0 += bl[j];
+    Bh = bl[h];
+  }
+  const int64_t out_row0 = (int64_t)b * s.hkv * s.B + row0;
+  int32_t *idx = cand ? reinterpret_cast<int32_t *>(ws + w.cand_idx) + unit * kMaxCandPerHead : O.indices + out_row0;
   uint32_t *ckey = reinterpret_cast<uint32_t *>(ws + w.cand_key) + unit * kMaxCandPerHead;
-  const int Bp = cand ? cand_m : s.Bp;
+  const int Bp = cand ? cand_m : Bh - s.W;
   if (Bp > 0) {
     uint32_t key[EPT];
     uint32_t kmin = 0xffffffffu, kmax = 0;
@@ -333,12 +343,11 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
   }
   if (cand) return;
   for (int wv = tid; wv < s.W; wv += THREADS) idx[Bp + wv] = Nc + wv;
-  const int h = bh % s.hkv, b = bh / s.hkv;
   if (tid == 0) {
-    O.counts[bh] = s.B;
+    O.counts[bh] = Bh;
     if (O.offsets) {
-      O.offsets[b * (s.hkv + 1) + h] = h * s.B;
-      if (h == s.hkv - 1) O.offsets[b * (s.hkv + 1) + s.hkv] = s.hkv * s.B;
+      O.offsets[b * (s.hkv + 1) + h] = row0;
+      if (h == s.hkv - 1) O.offsets[b * (s.hkv + 1) + s.hkv] = row0 + Bh;
     }
   }
   // ---- gather of the kept rows (Sec. 3.1, the compacted cache), if asked for: gather_eb is the
@@ -350,9 +359,9 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
     const int ppr = s.D * gather_eb / 16;
     const char *Kh = reinterpret_cast<const char *>(L.K) + ((int64_t)b * L.sb + (int64_t)h * L.sh) * gather_eb;
     const char *Vh = reinterpret_cast<const char *>(L.V) + ((int64_t)b * L.sb + (int64_t)h * L.sh) * gather_eb;
-    char *Ko = reinterpret_cast<char *>(O.K_out) + (int64_t)bh * s.B * s.D * gather_eb;
-    char *Vo = reinterpret_cast<char *>(O.V_out) + (int64_t)bh * s.B * s.D * gather_eb;
-    for (int p = tid; p < s.B * ppr; p += THREADS) {
+    char *Ko = reinterpret_cast<char *>(O.K_out) + out_row0 * s.D * gather_eb;
+    char *Vo = reinterpret_cast<char *>(O.V_out) + out_row0 * s.D * gather_eb;
+    for (int p = tid; p < Bh * ppr; p += THREADS) {
       const int row = p / ppr, piece = p - row * ppr;
       const int src = min(max(idx[row], 0), N - 1);    // indices come from the selection above; the clamp only guards the load
       const int64_t so = (int64_t)src * L.sn * gather_eb + piece * 16;
@@ -371,18 +380,18 @@ bool mixsel_supported(const Shape &s) { return s.Nc <= kMsMaxThreads * 32 && (si
 template <int THREADS, int EPT>
 static hipError_t launch_mixsel_e(const Shape &s, bool select, const LayerOutTable &out, char *ws, const Workspace &w,
                                   int64_t unit0, int nunits, const LayerInTable &in, int gather_eb, int cand_m,
-                                  hipStream_t st) {
+                                  const int32_t *budgets, hipStream_t st) {
   const size_t lds = (size_t)(s.Nc + s.Nc / 32 + 1) * 4;
   if (select) {
     auto kern = mixsel_kernel<THREADS, EPT, true>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(nunits), dim3(THREADS), lds, st, s, out, ws, w, unit0, in, gather_eb, cand_m);
+    hipLaunchKernelGGL(kern, dim3(nunits), dim3(THREADS), lds, st, s, out, ws, w, unit0, in, gather_eb, cand_m, budgets);
   } else {
     auto kern = mixsel_kernel<THREADS, EPT, false>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(nunits), dim3(THREADS), lds, st, s, out, ws, w, unit0, in, 0, 0);
+    hipLaunchKernelGGL(kern, dim3(nunits), dim3(THREADS), lds, st, s, out, ws, w, unit0, in, 0, 0, nullptr);
   }
   return hipGetLastError();
 }
@@ -392,13 +401,14 @@ static hipError_t launch_mixsel_e(const Shape &s, bool select, const LayerOutTab
 // kept rows, gather_eb being the element size) for `nunits` units starting at unit0.  Few waves per
 // workgroup keep the many block-wide steps cheap; long heads get more threads.
 hipError_t launch_mixsel(const Shape &s, bool select, const LayerOutTable &out, char *ws, const Workspace &w,
-                         int64_t unit0, int nunits, const LayerInTable &in, int gather_eb, int cand_m, hipStream_t st) {
+                         int64_t unit0, int nunits, const LayerInTable &in, int gather_eb, int cand_m,
+                         const int32_t *budgets, hipStream_t st) {
   const int nc = s.Nc;
-  if (nc <= 256 * 8) return launch_mixsel_e<256, 8>(s, select, out, ws, w, unit0, nunits, in, gather_eb, cand_m, st);
-  if (nc <= 512 * 8) return launch_mixsel_e<512, 8>(s, select, out, ws, w, unit0, nunits, in, gather_eb, cand_m, st);
-  if (nc <= 1024 * 8) return launch_mixsel_e<1024, 8>(s, select, out, ws, w, unit0, nunits, in, gather_eb, cand_m, st);
-  if (nc <= 1024 * 16) return launch_mixsel_e<1024, 16>(s, select, out, ws, w, unit0, nunits, in, gather_eb, cand_m, st);
-  return launch_mixsel_e<1024, 32>(s, select, out, ws, w, unit0, nunits, in, gather_eb, cand_m, st);
+  if (nc <= 256 * 8) return launch_mixsel_e<256, 8>(s, select, out, ws, w, unit0, nunits, in, gather_eb, cand_m, budgets, st);
+  if (nc <= 512 * 8) return launch_mixsel_e<512, 8>(s, select, out, ws, w, unit0, nunits, in, gather_eb, cand_m, budgets, st);
+  if (nc <= 1024 * 8) return launch_mixsel_e<1024, 8>(s, select, out, ws, w, unit0, nunits, in, gather_eb, cand_m, budgets, st);
+  if (nc <= 1024 * 16) return launch_mixsel_e<1024, 16>(s, select, out, ws, w, unit0, nunits, in, gather_eb, cand_m, budgets, st);
+  return launch_mixsel_e<1024, 32>(s, select, out, ws, w, unit0, nunits, in, gather_eb, cand_m, budgets, st);
 }
 
 }  // namespace mixkv

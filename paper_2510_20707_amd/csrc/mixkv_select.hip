@@ -324,30 +324,57 @@ __global__ __launch_bounds__(kSelectThreads) void mix_kernel(Shape s, LayerOutTa
 // ------------------------------------------------------------------------------------------------
 // select kernels (paper Sec. 3.1 TopB; Algorithm 1 TopB step: B' = B - W candidates, window kept)
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kSelectThreads) void select_fixed_kernel(Shape s, LayerOutTable out) {
+// One workgroup per unit; every head keeps B rows, or with a budget table (per-head mode,
+// [layers of this launch][hkv]) its own entry, the heads of a batch item packed back to back.
+__global__ __launch_bounds__(kSelectThreads) void select_fixed_kernel(Shape s, LayerOutTable out, const int32_t *budgets) {
   __shared__ SelectScratch sc;
   const int ul = blockIdx.x, layer = ul / s.units_per_layer, bh = ul - layer * s.units_per_layer;
+  const int h = bh % s.hkv, b = bh / s.hkv;
   const LayerOut O = out.l[layer];
   const float *scores = O.scores + (int64_t)bh * s.N;
-  int32_t *idx = O.indices + (int64_t)bh * s.B;
+  int Bh = s.B, row0 = h * s.B;
+  if (budgets) {
+    const int32_t *bl = budgets + layer * s.hkv;
+    row0 = 0;
+    for (int j = 0; j < h; ++j) row0 += bl[j];
+    Bh = bl[h];
+  }
+  const int Bp = Bh - s.W;
+  int32_t *idx = O.indices + (int64_t)b * s.hkv * s.B + row0;
   auto keyfn = [&](int i, uint32_t &key) { key = order_key(scores[i]); return true; };
-  if (s.Bp > 0) {
+  if (Bp > 0) {
     uint32_t tau;
     int need;
-    radix_select(1, s.Nc, s.Bp, [&](int, int i, uint32_t &key) { return keyfn(i, key); }, sc, &tau, &need);
+    radix_select(1, s.Nc, Bp, [&](int, int i, uint32_t &key) { return keyfn(i, key); }, sc, &tau, &need);
     const int cut = kth_equal_index(1, s.Nc, tau, need, [&](int, int i, uint32_t &key) { return keyfn(i, key); }, sc);
     compact_ascending(s.Nc, scores, [&](int i, float v) { uint32_t k = order_key(v); return k > tau || (k == tau && i <= cut); },
-                      idx, s.Bp, sc);
+                      idx, Bp, sc);
   }
-  for (int wv = threadIdx.x; wv < s.W; wv += blockDim.x) idx[s.Bp + wv] = s.Nc + wv;
+  for (int wv = threadIdx.x; wv < s.W; wv += blockDim.x) idx[Bp + wv] = s.Nc + wv;
   if (threadIdx.x == 0) {
-    const int h = bh % s.hkv, b = bh / s.hkv;
-    O.counts[bh] = s.B;
+    O.counts[bh] = Bh;
     if (O.offsets) {
-      O.offsets[b * (s.hkv + 1) + h] = h * s.B;
-      if (h == s.hkv - 1) O.offsets[b * (s.hkv + 1) + s.hkv] = s.hkv * s.B;
+      O.offsets[b * (s.hkv + 1) + h] = row0;
+      if (h == s.hkv - 1) O.offsets[b * (s.hkv + 1) + s.hkv] = row0 + Bh;
     }
   }
+}
+
+struct IntChunk { int32_t v[512]; };
+__global__ void upload_ints_kernel(IntChunk c, int n, int32_t *dst) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = c.v[i];
+}
+hipError_t upload_ints(const int32_t *host, int n, int32_t *dev, hipStream_t st) {
+  for (int at = 0; at < n; at += 512) {
+    IntChunk c;
+    const int m = n - at < 512 ? n - at : 512;
+    for (int i = 0; i < m; ++i) c.v[i] = host[at + i];
+    hipLaunchKernelGGL(upload_ints_kernel, dim3(2), dim3(256), 0, st, c, m, dev + at);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 // Head-adaptive budgets: one workgroup per (layer, batch item).
@@ -516,8 +543,9 @@ __global__ __launch_bounds__(256) void gather_kernel(Shape s, int eb, LayerInTab
   const int H = s.hkv, total = H * s.B;
   if (p >= total) return;
   int h;
-  if (s.adaptive) {
+  if (s.adaptive || s.per_head) {
     const int32_t *offs = O.offsets + b * (H + 1);
+    if (p >= offs[H]) return;                          // per-head budgets may leave the tail unused
     h = 0;
     while (h + 1 < H && p >= offs[h + 1]) ++h;
   } else {
@@ -542,11 +570,12 @@ hipError_t launch_mix(const Shape &s, const LayerInTable &in, const LayerOutTabl
   return hipGetLastError();
 }
 
-hipError_t launch_select(const Shape &s, const LayerOutTable &out, int nlayers, hipStream_t st) {
+hipError_t launch_select(const Shape &s, const LayerOutTable &out, int nlayers, const int32_t *budgets, hipStream_t st) {
   if (s.adaptive)
     hipLaunchKernelGGL(select_adaptive_kernel, dim3(nlayers * s.batch), dim3(kSelectThreads), 0, st, s, out);
   else
-    hipLaunchKernelGGL(select_fixed_kernel, dim3(nlayers * s.units_per_layer), dim3(kSelectThreads), 0, st, s, out);
+    hipLaunchKernelGGL(select_fixed_kernel, dim3(nlayers * s.units_per_layer), dim3(kSelectThreads), 0, st, s, out,
+                       budgets);
   return hipGetLastError();
 }
 

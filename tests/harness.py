@@ -68,10 +68,12 @@ def given_weights(wl: synth.Workload, layer_id: int) -> np.ndarray:
     return rng.uniform(0.0, 1.0, (wl.batch, wl.n_kv_heads)).astype(np.float32)
 
 
-def run_compress(wl: synth.Workload, layers, device="cuda:0", want_scores=True, r_given=None, **over):
+def run_compress(wl: synth.Workload, layers, device="cuda:0", want_scores=True, r_given=None, head_budgets=None,
+                 **over):
     """mixkv_compress on a list of synth.Layer.  `r_given`: per layer a float32 [batch, Hkv] array
-    (mix "given_r").  Returns (params, list of LayerOut on device)."""
-    p = gpu_params(wl, **over)
+    (mix "given_r"); `head_budgets`: int [len(layers), Hkv] (budget mode "per_head").
+    Returns (params, list of LayerOut on device)."""
+    p = gpu_params(wl, head_budgets=head_budgets, **over)
     Ks = [to_device(wl, l.K, device) for l in layers]
     Vs = [to_device(wl, l.V, device) for l in layers]
     Qs = [to_device(wl, l.Q, device) for l in layers]
@@ -115,7 +117,7 @@ def check_topk_set(dtype, kept: np.ndarray, s_ora: np.ndarray, k: int, what=""):
 
 
 def check_layer(wl: synth.Workload, lay: synth.Layer, p: B.MixkvParams, out: B.LayerOut, units=None, r_given=None,
-                **over):
+                head_budgets=None, **over):
     """Compare one layer of GPU output with the oracle.  `units`: iterable of (b, h) to check with
     the oracle (default all); invariants are checked on every unit.  `r_given`: this layer's
     [batch, Hkv] weights for mix "given_r"."""
@@ -124,6 +126,7 @@ def check_layer(wl: synth.Workload, lay: synth.Layer, p: B.MixkvParams, out: B.L
     Bud = op.budget
     Nc, G = N - W, wl.group
     adaptive = op.budget_mode == "adaptive"
+    per_head = op.budget_mode == "per_head"          # head_budgets: this layer's [Hkv] table
     idx_g = out.indices.cpu().numpy().reshape(Bt, Hkv * Bud)
     cnt_g = out.counts.cpu().numpy()
     off_g = out.offsets.cpu().numpy()
@@ -135,13 +138,16 @@ def check_layer(wl: synth.Workload, lay: synth.Layer, p: B.MixkvParams, out: B.L
     todo = set(units) if units is not None else {(b, h) for b in range(Bt) for h in range(Hkv)}
     stats = dict(max_err=0.0, band=0, exact=0, checked=0)
     for b in range(Bt):
-        assert cnt_g[b].sum() == Hkv * Bud
+        if per_head:
+            np.testing.assert_array_equal(cnt_g[b], head_budgets)
+        else:
+            assert cnt_g[b].sum() == Hkv * Bud
         np.testing.assert_array_equal(off_g[b], np.concatenate([[0], np.cumsum(cnt_g[b])]))
         s_ora_heads = {}
         for h in range(Hkv):
             lo, c = int(off_g[b, h]), int(cnt_g[b, h])
             idx = idx_g[b, lo:lo + c]
-            if not adaptive:
+            if not adaptive and not per_head:
                 assert c == Bud
             assert c >= W + (op.budget_floor if adaptive else 0)
             np.testing.assert_array_equal(idx[c - W:], np.arange(Nc, N))
@@ -167,7 +173,7 @@ def check_layer(wl: synth.Workload, lay: synth.Layer, p: B.MixkvParams, out: B.L
             stats["band"] += max(0, band - 1)
             stats["checked"] += 1
             if not adaptive:
-                ora_idx = O.select_unit(u["s_comp"], Bud - W, N, W)
+                ora_idx = O.select_unit(u["s_comp"], c - W, N, W)
                 stats["exact"] += int(np.array_equal(ora_idx, idx))
         if adaptive and len(s_ora_heads) == Hkv:
             # budgets may differ from the oracle's only through candidates inside the band of the pooled threshold

@@ -22,10 +22,12 @@ def _run_and_check(wl, n_layers=None, units=None, layer_ids=None, **over):
     _say(f"[case] {wl.name} dtype={wl.dtype} L={len(layers)} Bt={wl.batch} Hq={wl.n_q_heads} Hkv={wl.n_kv_heads} "
          f"D={wl.head_dim} N={wl.seq_len} W={wl.window} B={over.get('budget', wl.budget)} over={over}")
     rg = [H.given_weights(wl, l) for l in layer_ids] if over.get("mix") == "given_r" else None
-    p, outs = H.run_compress(wl, layers, r_given=rg, **over)
+    hb = over.pop("head_budgets", None)
+    p, outs = H.run_compress(wl, layers, r_given=rg, head_budgets=hb, **over)
     tot = dict(max_err=0.0, band=0, exact=0, checked=0)
     for i, (lay, out) in enumerate(zip(layers, outs)):
-        st = H.check_layer(wl, lay, p, out, units=units, r_given=None if rg is None else rg[i], **over)
+        st = H.check_layer(wl, lay, p, out, units=units, r_given=None if rg is None else rg[i],
+                           head_budgets=None if hb is None else hb[i], **over)
         tot["max_err"] = max(tot["max_err"], st["max_err"])
         for k in ("band", "exact", "checked"):
             tot[k] += st[k]
@@ -225,3 +227,48 @@ def test_given_r_equal_to_own_redundancy_reproduces_the_head_adaptive_mix():
     p2, outs2 = H.run_compress(wl, [lay], r_given=[red], mix="given_r")
     assert torch.equal(outs[0].scores, outs2[0].scores) and torch.equal(outs[0].indices, outs2[0].indices)
     assert torch.equal(outs[0].redundancy, outs2[0].redundancy)
+
+
+# ------------------------------------------------------------------ budgets given per layer and head
+
+def _pyramid(L, Hkv, top, bottom):
+    """A layer-wise schedule: `top` rows per head in layer 0 falling linearly to `bottom` in the last."""
+    per_layer = np.round(np.linspace(top, bottom, L)).astype(np.int32)
+    return np.repeat(per_layer[:, None], Hkv, axis=1)
+
+
+def test_per_head_budgets_c1_and_c2():
+    wl = WL["c1"]
+    _run_and_check(wl, budget_mode="per_head", head_budgets=np.array([[wl.window, 120]], dtype=np.int32))
+    wl = WL["c2"]
+    hb = np.array([[wl.window, 64, 500, wl.seq_len]], dtype=np.int32)        # window only ... keep everything
+    _run_and_check(wl, budget_mode="per_head", head_budgets=hb, budget=int(-(-hb.sum() // 4)))
+
+
+def test_per_layer_pyramid_over_two_launch_groups():
+    wl = WL["c1"].with_(n_layers=35)
+    hb = _pyramid(35, wl.n_kv_heads, 2 * wl.budget - wl.window, wl.window)   # mean = the fixed budget
+    rng = np.random.default_rng(5)
+    hb[::2] += rng.integers(-3, 4, size=hb[::2].shape).astype(np.int32)      # and some head-wise spread
+    hb = np.clip(hb, wl.window, None)
+    _run_and_check(wl, n_layers=35, budget_mode="per_head", head_budgets=hb, budget=int(hb.sum(axis=1).max() + 1) // 2 + 1)
+
+
+def test_per_head_budgets_ragged_f32_and_long_fallback():
+    wl = WL["c2"].with_(name="ragged-ph", dtype="f32", head_dim=64, seq_len=777, window=9, n_q_heads=4, n_kv_heads=4,
+                        budget=100, batch=2, text_prefix=16, text_suffix_start=700)
+    hb = np.array([[9, 10, 333, 40], [48, 100, 100, 152]], dtype=np.int32)
+    _run_and_check(wl, n_layers=2, budget_mode="per_head", head_budgets=hb)
+    wl = WL["c2"].with_(name="long-ph", seq_len=33000, batch=1, n_q_heads=4, n_kv_heads=2, text_suffix_start=32900)
+    _run_and_check(wl, n_layers=1, budget_mode="per_head", head_budgets=np.array([[300, 64]], dtype=np.int32), budget=200)
+
+
+def test_equal_per_head_budgets_reproduce_fixed_mode_bit_for_bit():
+    wl = WL["c2"]
+    lay = synth.make_layer(wl, 0)
+    p, outs = H.run_compress(wl, [lay])
+    hb = np.full((1, wl.n_kv_heads), wl.budget, dtype=np.int32)
+    p2, outs2 = H.run_compress(wl, [lay], budget_mode="per_head", head_budgets=hb)
+    for name in ("indices", "counts", "offsets", "K_out", "V_out", "scores"):
+        a, b = getattr(outs[0], name), getattr(outs2[0], name)
+        assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), name

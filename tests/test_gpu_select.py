@@ -74,3 +74,67 @@ def test_adaptive_budget_selection_is_bit_exact(kind, N, W, Bud, Hkv, floor):
         for h in range(Hkv):
             want = O.select_unit(s[b, h, :N - W].astype(np.float64), int(bp[h]), N, W)
             np.testing.assert_array_equal(idx[b, off[b, h]:off[b, h + 1]], want)
+
+
+@pytest.mark.parametrize("kind", ["normal", "ties"])
+@pytest.mark.parametrize("N,W,Bud,Hkv,L", [(512, 8, 64, 4, 3), (4099, 32, 300, 2, 34), (33000, 32, 128, 2, 1)])
+def test_per_head_budget_selection_is_bit_exact(kind, N, W, Bud, Hkv, L):
+    print(f"[case] select per-head kind={kind} N={N} W={W} B={Bud} Hkv={Hkv} L={L}", flush=True)
+    rng = np.random.default_rng([3, N, Bud])
+    Bt = 2
+    # budgets between W and 2B - W per head, then trimmed so that every layer fits its Hkv * B rows
+    hb = rng.integers(W, 2 * Bud - W + 1, size=(L, Hkv)).astype(np.int32)
+    hb[0, 0] = W                                               # a head that keeps the window only
+    for l in range(L):
+        while hb[l].sum() > Hkv * Bud:
+            hb[l, np.argmax(hb[l])] -= 1
+    p = B.make_params("bf16", Bt, Hkv, Hkv, 128, N, W, Bud, budget_mode="per_head", head_budgets=hb)
+    ss, outs = [], []
+    for l in range(L):
+        s = _scores(kind, rng, Bt, Hkv, N, W)
+        out = B.alloc_layer_out(p, "cuda:0", redundancy=False, gather=False)
+        out.scores = torch.from_numpy(s).to("cuda:0")
+        out.indices.fill_(-1)
+        ss.append(s)
+        outs.append(out)
+    ws = torch.empty((L * Hkv * 4 + 255) // 256 * 256, dtype=torch.uint8, device="cuda:0")   # the table only
+    B.mixkv_select(p, outs, ws)
+    torch.cuda.synchronize()
+    for l in range(L):
+        idx = outs[l].indices.cpu().numpy().reshape(Bt, Hkv * Bud)
+        off = np.concatenate([[0], np.cumsum(hb[l])])
+        np.testing.assert_array_equal(outs[l].counts.cpu().numpy(), np.tile(hb[l], (Bt, 1)))
+        np.testing.assert_array_equal(outs[l].offsets.cpu().numpy(), np.tile(off, (Bt, 1)))
+        for b in range(Bt):
+            for h in range(Hkv):
+                want = O.select_unit(ss[l][b, h, :N - W].astype(np.float64), int(hb[l, h]) - W, N, W)
+                np.testing.assert_array_equal(idx[b, off[h]:off[h + 1]], want)
+            assert np.all(idx[b, off[Hkv]:] == -1)             # unused capacity is left alone
+
+
+def test_per_head_budget_tables_are_validated_on_the_host():
+    N, W, Bud, Hkv = 512, 8, 64, 2
+    good = np.array([[8, 120]], dtype=np.int32)
+    s = _scores("normal", np.random.default_rng(4), 1, Hkv, N, W)
+    ws = torch.empty(256, dtype=torch.uint8, device="cuda:0")
+
+    def call(hb, workspace=ws):
+        p = B.make_params("bf16", 1, Hkv, Hkv, 128, N, W, Bud, budget_mode="per_head", head_budgets=hb)
+        out = B.alloc_layer_out(p, "cuda:0", redundancy=False, gather=False)
+        out.scores = torch.from_numpy(s).to("cuda:0")
+        out.indices.fill_(-7)
+        try:
+            B.mixkv_select(p, [out], workspace)
+            status = B.MIXKV_OK
+        except B.MixkvError as e:
+            status = e.status
+        torch.cuda.synchronize()
+        return status, out
+
+    assert call(good)[0] == B.MIXKV_OK
+    for bad in ([[7, 64]], [[8, 513]], [[64, 65]]):            # below W, above N, more than Hkv * B in all
+        status, out = call(np.array(bad, dtype=np.int32))
+        assert status == B.MIXKV_ERR_INVALID_ARG
+        assert torch.all(out.indices == -7)                    # nothing was launched
+    assert call(None)[0] == B.MIXKV_ERR_INVALID_ARG            # no table
+    assert call(good, None)[0] == B.MIXKV_ERR_INVALID_ARG      # no workspace to stage it in
