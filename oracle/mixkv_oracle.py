@@ -207,6 +207,31 @@ def score_unit(K: np.ndarray, V: np.ndarray, Qg: np.ndarray, p: Params,
                 s_div_scaled=s_div_scaled, r=np.float64(r), s_comp=s_comp)
 
 
+# --------------------------------------------------------------------------- redundancy analysis
+
+def similarity_analysis(X: np.ndarray, block: int) -> Dict[str, np.ndarray]:
+    """Pairwise cosine similarity of the rows of X [N, D] (keys or values of one head), as the
+    paper's redundancy figures show it (Sec. 1, the figures on key/value similarity inside a head
+    and across heads; Sec. 3.3, Eq. 3 for the matrix itself).
+
+    Written as the definition: the full N x N matrix R of cosine similarities, then
+      redundancy  the mean of its off-diagonal entries (Eq. 4 applied to X),
+      block_map   [nb, nb], nb = ceil(N / block): the mean of R over rows of block a and columns
+                  of block b (the last block may be short; diagonal entries are part of diagonal
+                  blocks), i.e. the heat-map at a resolution of `block` tokens.
+    """
+    Xh = normalised_keys(X)
+    N = Xh.shape[0]
+    R = Xh @ Xh.T
+    red = (R.sum() - np.trace(R)) / (N * (N - 1))
+    nb = (N + block - 1) // block
+    bm = np.empty((nb, nb))
+    for a in range(nb):
+        for b in range(nb):
+            bm[a, b] = R[a * block:(a + 1) * block, b * block:(b + 1) * block].mean()
+    return dict(redundancy=np.float64(red), block_map=bm)
+
+
 # --------------------------------------------------------------------------- selection
 
 def top_indices(s: np.ndarray, b: int) -> np.ndarray:

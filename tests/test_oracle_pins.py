@@ -475,3 +475,40 @@ def test_per_head_budgets_nest():
         cur = set(out["indices"][0][0].tolist())
         assert len(cur) == b and prev <= cur
         prev = cur
+
+
+# ------------------------------------------------------------------ redundancy analysis (similarity heat-maps)
+
+@pytest.mark.parametrize("N,block", [(13, 4), (16, 4), (9, 16)])
+def test_similarity_analysis_matches_brute_force_matrix(N, block):
+    rng = np.random.default_rng(51)
+    X = rng.standard_normal((N, 5)) + 0.7
+    R = brute.cosine_matrix(X.tolist())
+    out = O.similarity_analysis(X, block)
+    assert abs(float(out["redundancy"]) - brute.offdiag_mean(R)) < 1e-13
+    nb = -(-N // block)
+    assert out["block_map"].shape == (nb, nb)
+    for a in range(nb):
+        for b in range(nb):
+            cells = [R[i][j] for i in range(a * block, min(N, (a + 1) * block))
+                     for j in range(b * block, min(N, (b + 1) * block))]
+            assert abs(out["block_map"][a, b] - sum(cells) / len(cells)) < 1e-13
+    np.testing.assert_allclose(out["block_map"], out["block_map"].T, rtol=0, atol=1e-15)
+
+
+def test_similarity_analysis_closed_forms():
+    # identical rows: every similarity is 1; orthonormal rows: R is the identity, so a diagonal
+    # block of b rows averages 1/b; the same value as Eq. 4 through the keys' own routine
+    X = np.tile(np.array([0.3, -1.0, 2.0]), (12, 1))
+    out = O.similarity_analysis(X, 4)
+    np.testing.assert_allclose(out["block_map"], 1.0, rtol=1e-14)
+    assert abs(float(out["redundancy"]) - 1.0) < 1e-14
+    out = O.similarity_analysis(np.eye(12) * 3.0, 4)
+    np.testing.assert_allclose(out["block_map"], np.eye(3) / 4.0, atol=1e-15)
+    assert abs(float(out["redundancy"])) < 1e-15
+    K, _, _ = _rand_unit(52, N=40, D=8, offset=0.5)
+    assert abs(float(O.similarity_analysis(K, 8)["redundancy"]) - O.redundancy(O.normalised_keys(K))) < 1e-13
+    # block size 1 is the cosine matrix itself; one block covering everything is its overall mean
+    R = np.array(brute.cosine_matrix(K.tolist()))
+    np.testing.assert_allclose(O.similarity_analysis(K, 1)["block_map"], R, atol=1e-13)
+    np.testing.assert_allclose(O.similarity_analysis(K, 64)["block_map"], [[R.mean()]], atol=1e-13)
