@@ -105,6 +105,9 @@ def main():
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="also launch an elementwise copy kernel that reads and writes this many MiB: a kernel of "
                          "known traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
+    ap.add_argument("--similarity-block", type=int, default=0,
+                    help="also time mixkv_similarity (redundancy analysis of the keys: r and the heat-map at this "
+                         "block size) on the same cache; reported in an extra 'similarity' object")
     ap.add_argument("--budgets", default="config", choices=["config", "pyramid"],
                     help="pyramid: budgets given per layer, falling linearly from 2B-W in the first layer to W in the "
                          "last (mean B); a per-head-table variant of a fixed-budget workload, not the headline")
@@ -207,6 +210,27 @@ def main():
 
     units = wl.n_units
     e = 2 if wl.dtype == "bf16" else 4
+    sim = None
+    if args.similarity_block > 0:
+        blk = args.similarity_block
+        nb = -(-wl.seq_len // blk)
+        red = [torch.empty((wl.batch, wl.n_kv_heads), dtype=torch.float32, device=dev) for _ in layers]
+        maps = [torch.empty((wl.batch, wl.n_kv_heads, nb, nb), dtype=torch.float32, device=dev) for _ in layers]
+        sws = torch.empty(B.mixkv_similarity_workspace_size(p, len(layers), blk), dtype=torch.uint8, device=dev)
+        scalls = [B.PreparedSimilarity(p, [x[0] for x in c], red, maps, blk, sws) for c in copies]
+        for i in range(args.warmup):
+            scalls[i % len(scalls)].run(stream)
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record(stream)
+        for i in range(args.steps):
+            scalls[i % len(scalls)].run(stream)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        sim_s = ev0.elapsed_time(ev1) * 1e-3 / args.steps
+        sim_bytes = units * (wl.seq_len * wl.head_dim * e + nb * nb * 4)          # X once, the map written once
+        sim = {"block": blk, "ms_per_call": sim_s * 1e3, "algorithmic_bytes": sim_bytes,
+               "achieved_GBps": sim_bytes / sim_s / 1e9, "hbm_frac": sim_bytes / sim_s / HBM_PEAK,
+               "kernels": "blocksum_kernel + blockgram_kernel, HIP events on the launch stream"}
     reads_v = args.intrinsic == "vnorm"
     bytes_step = algorithmic_bytes(wl, budget, scores_out=False, reads_v=reads_v) * units
     dom = max(("stats", "attn"), key=lambda k: stage_ms.get(k, 0.0))
@@ -237,6 +261,7 @@ def main():
                      "algorithmic_bytes": dom_bytes, "avg_launch_us": dom_s * 1e6,
                      "traffic": MEASURED_TRAFFIC.get((wl.name, wl.n_layers, dom)) if reads_v else None},
         "cpu_baseline": cpu,
+        "similarity": sim,
         "parity_vs_oracle": parity,
         "host_gen_s": round(t_gen, 2),
     }

@@ -39,7 +39,7 @@
 extern "C" {
 #endif
 
-#define MIXKV_VERSION 3
+#define MIXKV_VERSION 4
 #define MIXKV_MAX_LAYERS 128      /* layers per call */
 #define MIXKV_MAX_WINDOW 64
 #define MIXKV_MAX_GROUP_ROWS 512  /* G * W */
@@ -188,6 +188,34 @@ mixkv_status mixkv_compress_profiled(const mixkv_params *params, const mixkv_lay
                                      int32_t n_layers, void *workspace, size_t workspace_bytes, void *hip_stream,
                                      float *stage_ms);
 const char *mixkv_stage_name(int32_t stage);
+
+/*
+ * Redundancy analysis of cached keys or values (Sec. 1, the figures that show the cosine similarity
+ * of keys inside one head, and the average similarity of keys and of values per layer and head;
+ * Sec. 3.3, Eq. 3-4 for the similarity matrix and its off-diagonal mean).  For every (batch item,
+ * head) of every layer, with R the N x N matrix of cosine similarities between the rows of X
+ * (a row of norm below 1e-30 counts as the zero vector):
+ *   redundancy  the mean of the off-diagonal entries of R (for X = K this is the r of mixkv_score);
+ *   block_map   [nb, nb], nb = ceil(N / block): the mean of R over the rows of block a and the
+ *               columns of block b, blocks being `block` consecutive positions (the last one may be
+ *               shorter; diagonal entries belong to the diagonal blocks): the heat-map of R at a
+ *               resolution of `block` tokens.
+ * Only dtype, batch, n_kv_heads (the number of heads of X), head_dim and seq_len of `params` are
+ * used; the rest must merely be valid.  1 <= block <= N.  Either output may be NULL, not both.
+ * Workspace: mixkv_similarity_workspace_size bytes, 256-byte aligned, no initialisation.
+ */
+typedef struct {
+  const void *X;             /* DEVICE [batch, n_kv_heads, N, D], D contiguous: keys or values */
+  int64_t stride_b, stride_h, stride_n;   /* in elements; stride_n >= D; row starts 16-byte aligned */
+} mixkv_rows_in;
+typedef struct {
+  float *redundancy;         /* DEVICE [batch, n_kv_heads] */
+  float *block_map;          /* DEVICE [batch, n_kv_heads, nb, nb] */
+} mixkv_similarity_out;
+mixkv_status mixkv_similarity_workspace_size(const mixkv_params *params, int32_t n_layers, int32_t block, size_t *bytes);
+mixkv_status mixkv_similarity(const mixkv_params *params, const mixkv_rows_in *in, const mixkv_similarity_out *out,
+                              int32_t n_layers, int32_t block, void *workspace, size_t workspace_bytes,
+                              void *hip_stream);
 
 const char *mixkv_status_string(mixkv_status status);
 int32_t mixkv_version(void);

@@ -48,6 +48,14 @@ class MixkvLayerOut(C.Structure):
                 ("offsets", C.c_void_p), ("K_out", C.c_void_p), ("V_out", C.c_void_p)]
 
 
+class MixkvRowsIn(C.Structure):
+    _fields_ = [("X", C.c_void_p), ("stride_b", C.c_int64), ("stride_h", C.c_int64), ("stride_n", C.c_int64)]
+
+
+class MixkvSimilarityOut(C.Structure):
+    _fields_ = [("redundancy", C.c_void_p), ("block_map", C.c_void_p)]
+
+
 class MixkvError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -76,6 +84,11 @@ def lib() -> C.CDLL:
         L.mixkv_compress_profiled.argtypes = [pp, pin, pout, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p,
                                               C.POINTER(C.c_float)]
         L.mixkv_compress_profiled.restype = C.c_int
+        L.mixkv_similarity_workspace_size.argtypes = [pp, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
+        L.mixkv_similarity_workspace_size.restype = C.c_int
+        L.mixkv_similarity.argtypes = [pp, C.POINTER(MixkvRowsIn), C.POINTER(MixkvSimilarityOut), C.c_int32, C.c_int32,
+                                       C.c_void_p, C.c_size_t, C.c_void_p]
+        L.mixkv_similarity.restype = C.c_int
         L.mixkv_stage_name.argtypes = [C.c_int32]
         L.mixkv_stage_name.restype = C.c_char_p
         L.mixkv_status_string.argtypes = [C.c_int]
@@ -207,6 +220,47 @@ def mixkv_compress(p: MixkvParams, Ks, Vs, Qs, outs: Sequence[LayerOut], workspa
     wp, wb = _ws(workspace)
     _check(lib().mixkv_compress(C.byref(p), _in_array(Ks, Vs, Qs, r_given), _out_array(outs), len(outs), wp, wb,
                                 _stream(stream)), "mixkv_compress")
+
+
+def mixkv_similarity_workspace_size(p: MixkvParams, n_layers: int, block: int) -> int:
+    n = C.c_size_t(0)
+    _check(lib().mixkv_similarity_workspace_size(C.byref(p), n_layers, block, C.byref(n)),
+           "mixkv_similarity_workspace_size")
+    return n.value
+
+
+class PreparedSimilarity:
+    """The C argument arrays of one mixkv_similarity call, built once."""
+
+    def __init__(self, p: MixkvParams, Xs, redundancy, block_maps, block: int, workspace: torch.Tensor):
+        n = len(Xs)
+        self.p, self.n, self.block = p, n, block
+        self.ins, self.outs = (MixkvRowsIn * n)(), (MixkvSimilarityOut * n)()
+        for i, X in enumerate(Xs):
+            assert X.dim() == 4 and X.stride(3) == 1
+            self.ins[i] = MixkvRowsIn(X.data_ptr(), X.stride(0), X.stride(1), X.stride(2))
+            self.outs[i] = MixkvSimilarityOut(_ptr(None if redundancy is None else redundancy[i]),
+                                              _ptr(None if block_maps is None else block_maps[i]))
+        self.wp, self.wb = _ws(workspace)
+        self._keep = (Xs, redundancy, block_maps, workspace)
+        self._L = lib()
+
+    def run(self, stream=None):
+        _check(self._L.mixkv_similarity(C.byref(self.p), self.ins, self.outs, self.n, self.block, self.wp, self.wb,
+                                        _stream(stream)), "mixkv_similarity")
+
+
+def mixkv_similarity(p: MixkvParams, Xs, block: int, want_map: bool = True, workspace=None, stream=None):
+    """Redundancy and (optionally) the block-mean similarity heat-map of every head of the layers Xs
+    ([batch, Hkv, N, D] device tensors: keys or values).  Returns (redundancy list, block_map list)."""
+    dev = Xs[0].device
+    nb = (p.seq_len + block - 1) // block
+    red = [torch.empty((p.batch, p.n_kv_heads), dtype=torch.float32, device=dev) for _ in Xs]
+    maps = [torch.empty((p.batch, p.n_kv_heads, nb, nb), dtype=torch.float32, device=dev) for _ in Xs] if want_map else None
+    if workspace is None:
+        workspace = torch.empty(mixkv_similarity_workspace_size(p, len(Xs), block), dtype=torch.uint8, device=dev)
+    PreparedSimilarity(p, Xs, red, maps, block, workspace).run(stream)
+    return red, maps
 
 
 class PreparedCall:

@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
     L = B.lib()
     for n in set(names):
         assert hasattr(L, n), n
-    assert L.mixkv_version() == 3
+    assert L.mixkv_version() == 4
     assert B.status_string(0) == "ok" and "workspace" in B.status_string(3)
 
 
@@ -103,3 +103,23 @@ def test_bad_call_arguments_are_rejected_before_any_launch():
     # row stride shorter than D
     ins[0] = B.MixkvLayerIn(0x1000, 0x2000, 0, 0, 64, 0x3000)
     assert L.mixkv_score(C.byref(p), ins, outs, 1, fake, 1 << 40, None) == B.MIXKV_ERR_INVALID_ARG
+
+
+def test_similarity_workspace_and_block_limits():
+    p = _good()
+    n = B.mixkv_similarity_workspace_size(p, 2, 64)
+    nb, units = 8192 // 64, 2 * p.batch * p.n_kv_heads
+    assert n % 256 == 0 and n >= units * nb * (p.head_dim + 1) * 4
+    for block in (0, -3, 8193):
+        with pytest.raises(B.MixkvError) as e:
+            B.mixkv_similarity_workspace_size(p, 1, block)
+        assert e.value.status == B.MIXKV_ERR_INVALID_ARG
+    L = B.lib()
+    ins, outs = (B.MixkvRowsIn * 1)(), (B.MixkvSimilarityOut * 1)()
+    fake = C.c_void_p(0x1000)                    # never dereferenced: validation fails first
+    assert L.mixkv_similarity(C.byref(p), ins, outs, 1, 64, None, 0, None) == B.MIXKV_ERR_INVALID_ARG
+    assert L.mixkv_similarity(C.byref(p), ins, outs, 1, 64, fake, 16, None) == B.MIXKV_ERR_WORKSPACE_TOO_SMALL
+    assert L.mixkv_similarity(C.byref(p), ins, outs, 1, 64, fake, 1 << 40, None) == B.MIXKV_ERR_INVALID_ARG   # null X
+    ins[0] = B.MixkvRowsIn(0x2000, 0, 0, 128)
+    assert L.mixkv_similarity(C.byref(p), ins, outs, 1, 64, fake, 1 << 40, None) == B.MIXKV_ERR_INVALID_ARG   # no output
+    assert L.mixkv_similarity(C.byref(p), None, outs, 1, 64, fake, 1 << 40, None) == B.MIXKV_ERR_INVALID_ARG

@@ -1,0 +1,101 @@
+"""GPU parity of mixkv_similarity (redundancy analysis of keys or values) against the oracle's
+explicit cosine matrix, on the same seeded inputs.
+
+Tolerances: the inputs are exact in their dtype and all arithmetic is fp32 (sums of at most `block`
+unit-vector components, then one dot product per heat-map cell), so both dtypes get the same
+absolute bounds: 2e-6 on heat-map cells (values in [-1, 1]) and the redundancy bounds of the
+scoring path (1e-5 bf16, 1e-6 f32)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mixkv_oracle as O
+from paper_2510_20707_amd import binding as B
+from paper_2510_20707_amd import synth
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+WL = synth.WORKLOADS
+MAP_ATOL = 2e-6
+
+
+def _check(wl, layers, which, block, units=None, strided=False):
+    print(f"[case] similarity {wl.name} {which} dtype={wl.dtype} D={wl.head_dim} N={wl.seq_len} block={block} "
+          f"L={len(layers)} strided={strided}", flush=True)
+    p = H.gpu_params(wl)
+    Xs = []
+    for lay in layers:
+        x = H.to_device(wl, getattr(lay, which))
+        if strided:                                   # rows twice as far apart, heads in a larger slab
+            big = torch.zeros((wl.batch, wl.n_kv_heads + 1, wl.seq_len, 2 * wl.head_dim), dtype=x.dtype, device=x.device)
+            big[:, :wl.n_kv_heads, :, :wl.head_dim] = x
+            x = big[:, :wl.n_kv_heads, :, :wl.head_dim]
+        Xs.append(x)
+    red, maps = B.mixkv_similarity(p, Xs, block)
+    torch.cuda.synchronize()
+    todo = units or [(b, h) for b in range(wl.batch) for h in range(wl.n_kv_heads)]
+    worst = 0.0
+    for lay, r, m in zip(layers, red, maps):
+        r, m = r.cpu().numpy(), m.cpu().numpy()
+        assert np.all(np.isfinite(m)) and np.all(np.isfinite(r))
+        np.testing.assert_allclose(m, np.swapaxes(m, 2, 3), rtol=0, atol=2e-6)      # symmetric up to summation order
+        for b, h in todo:
+            ora = O.similarity_analysis(getattr(lay, which)[b, h], block)
+            err = np.abs(m[b, h] - ora["block_map"]).max()
+            worst = max(worst, err)
+            assert err <= MAP_ATOL, f"b{b} h{h}: heat-map error {err:.2e}"
+            assert abs(float(r[b, h]) - float(ora["redundancy"])) <= H.RTOL_R[wl.dtype], \
+                f"b{b} h{h}: redundancy {r[b, h]} vs {ora['redundancy']}"
+    print(f"       max heat-map error {worst:.2e}", flush=True)
+    return red
+
+
+@pytest.mark.parametrize("which", ["K", "V"])
+def test_c1_f32_keys_and_values(which):
+    wl = WL["c1"]
+    _check(wl, [synth.make_layer(wl, 0)], which, 32)
+    _check(wl, [synth.make_layer(wl, 0)], which, 1)          # the cosine matrix itself
+
+
+@pytest.mark.parametrize("block", [64, 100, 4096])
+def test_c2_bf16_keys(block):
+    wl = WL["c2"]
+    _check(wl, [synth.make_layer(wl, 0)], "K", block)
+
+
+def test_c2_values_and_strided_input():
+    wl = WL["c2"]
+    lay = synth.make_layer(wl, 0)
+    _check(wl, [lay], "V", 128, units=[(0, 0), (0, 3)])
+    _check(wl, [lay], "K", 128, units=[(0, 1)], strided=True)
+
+
+@pytest.mark.parametrize("dtype,D,N,block", [("bf16", 64, 1000, 37), ("f32", 128, 777, 64), ("f32", 64, 70, 7),
+                                             ("bf16", 128, 333, 333)])
+def test_ragged_shapes(dtype, D, N, block):
+    wl = WL["c2"].with_(name="ragged-sim", dtype=dtype, head_dim=D, seq_len=N, window=5, n_q_heads=4, n_kv_heads=2,
+                        budget=20, batch=2, text_prefix=min(16, N // 4), text_suffix_start=N - max(5, N // 8))
+    _check(wl, [synth.make_layer(wl, l) for l in range(2)], "K", block)
+
+
+def test_more_layers_than_one_launch_group_and_agreement_with_the_scoring_path():
+    wl = WL["c1"].with_(n_layers=35)
+    layers = [synth.make_layer(wl, l) for l in range(35)]
+    red = _check(wl, layers, "K", 64, units=[(0, 1)])
+    p, outs = H.run_compress(wl, layers)
+    for r, o in zip(red, outs):                          # the same quantity by two routes (Eq. 4)
+        np.testing.assert_allclose(r.cpu().numpy(), o.redundancy.cpu().numpy(), rtol=0, atol=2e-6)
+
+
+def test_zero_rows_count_as_zero_vectors():
+    wl = WL["c1"]
+    lay = synth.make_layer(wl, 0)
+    lay.K[0, 0, 5] = 0.0
+    lay.K[0, 1, 100:140] = 0.0
+    _check(wl, [lay], "K", 32)
+
+
+def test_c3_sampled_heads_at_the_bench_configuration():
+    wl = WL["c3"]
+    layers = [synth.make_layer(wl, l) for l in (0, 27)]
+    _check(wl, layers, "K", 256, units=[(0, 2)])
