@@ -41,7 +41,11 @@ constant):
     as the layer-wise and head-wise allocation schemes the method is combined
     with do (Sec. 4.1 and the appendix's baseline details; Table 1): head h
     then keeps its own
-    b_h - W best candidates and the window, exactly as in the fixed case.
+    b_h - W best candidates and the window, exactly as in the fixed case;
+  * the softmax normaliser of the window rows may be handed in as the
+    log-sum-exp the prefill attention already produced for those rows
+    (Sec. 3.2: the extrinsic score reuses the attention of the window queries):
+    the weight of key i in row r is then exp(logit_ri - lse_r), masked entries 0.
 
 Every function is pinned by tests/test_oracle_*.py against brute force, closed
 forms and library routines; the whole path against the authors' own code is
@@ -80,11 +84,14 @@ class Params:
 
 # --------------------------------------------------------------------------- scores
 
-def window_attention(K: np.ndarray, Qg: np.ndarray, scale: float, causal: bool) -> np.ndarray:
+def window_attention(K: np.ndarray, Qg: np.ndarray, scale: float, causal: bool,
+                     lse: np.ndarray | None = None) -> np.ndarray:
     """Softmax attention weights of the window queries over all N keys.
 
     K [N, D], Qg [G, W, D] -> P [G, W, N].  (Sec. 3.2, extrinsic importance:
-    Attention(Q_j, K_i) for j in the window.)
+    Attention(Q_j, K_i) for j in the window.)  With `lse` [G, W] (natural-log
+    sum of exp(logit) over the keys each row attends to, as produced elsewhere)
+    the rows are normalised by it instead of by their own sum.
     """
     K = np.asarray(K, dtype=np.float64)
     Qg = np.asarray(Qg, dtype=np.float64)
@@ -96,6 +103,8 @@ def window_attention(K: np.ndarray, Qg: np.ndarray, scale: float, causal: bool) 
         pos = np.arange(N)
         for w in range(W):
             logits[:, w, pos > Nc + w] = -np.inf
+    if lse is not None:
+        return np.exp(logits - np.asarray(lse, dtype=np.float64)[:, :, None])
     m = logits.max(axis=2, keepdims=True)
     e = np.exp(logits - m)
     return e / e.sum(axis=2, keepdims=True)
@@ -120,11 +129,11 @@ def pool1d(a: np.ndarray, mode: str, k: int) -> np.ndarray:
     return out
 
 
-def extrinsic_importance(K, Qg, p: Params) -> np.ndarray:
+def extrinsic_importance(K, Qg, p: Params, lse: np.ndarray | None = None) -> np.ndarray:
     """s_ex over the candidates: window/group mean of attention, then pooling."""
     G, W, _ = np.asarray(Qg).shape
     Nc = np.asarray(K).shape[0] - W
-    P = window_attention(K, Qg, p.softmax_scale, p.causal_window)
+    P = window_attention(K, Qg, p.softmax_scale, p.causal_window, lse)
     a = P[:, :, :Nc].sum(axis=(0, 1)) / (G * W)
     return pool1d(a, p.pool, p.pool_kernel)
 
@@ -160,10 +169,11 @@ def diversity(Khat: np.ndarray) -> np.ndarray:
 
 
 def score_unit(K: np.ndarray, V: np.ndarray, Qg: np.ndarray, p: Params,
-               r_given: float | None = None) -> Dict[str, np.ndarray]:
+               r_given: float | None = None, lse: np.ndarray | None = None) -> Dict[str, np.ndarray]:
     """All scores of one unit.  K, V [N, D]; Qg [G, W, D].  Arrays over the Nc candidates.
 
-    `r_given` is the caller's head weight for mix "given_r" (Table 4, offline W^head).
+    `r_given` is the caller's head weight for mix "given_r" (Table 4, offline W^head);
+    `lse` [G, W] the window rows' log-sum-exp if the caller has it (see window_attention).
     """
     K = np.asarray(K, dtype=np.float64)
     V = np.asarray(V, dtype=np.float64)
@@ -171,7 +181,7 @@ def score_unit(K: np.ndarray, V: np.ndarray, Qg: np.ndarray, p: Params,
     W = np.asarray(Qg).shape[1]
     Nc = N - W
     assert N >= 2 and Nc >= 1
-    s_ex = extrinsic_importance(K, Qg, p)
+    s_ex = extrinsic_importance(K, Qg, p, lse)
     if p.intrinsic in ("vnorm", "knorm"):
         if p.intrinsic == "vnorm":
             s_in = np.sqrt((V[:Nc] * V[:Nc]).sum(axis=1))     # VNorm: ||V_i||
@@ -275,12 +285,14 @@ def select_unit(s_comp: np.ndarray, b_prime: int, N: int, W: int) -> np.ndarray:
 # --------------------------------------------------------------------------- whole layer
 
 def compress_layer(K: np.ndarray, V: np.ndarray, Q: np.ndarray, p: Params,
-                   r_given: np.ndarray | None = None, head_budgets: np.ndarray | None = None) -> Dict[str, object]:
+                   r_given: np.ndarray | None = None, head_budgets: np.ndarray | None = None,
+                   window_lse: np.ndarray | None = None) -> Dict[str, object]:
     """Algorithm 1 for every (batch item, KV head) of one layer.
 
     K, V [Bt, Hkv, N, D]; Q [Bt, Hq, W, D]; r_given [Bt, Hkv] for mix "given_r";
     head_budgets [Hkv] (rows kept by each head of this layer, window included)
-    for budget mode "per_head".  Returns
+    for budget mode "per_head"; window_lse [Bt, Hq, W] the window rows'
+    log-sum-exp when the caller has it.  Returns
       scores [Bt, Hkv, N] (s_comp at candidates, +inf at window slots),
       redundancy [Bt, Hkv], counts [Bt, Hkv], offsets [Bt, Hkv+1],
       indices: list over batch of list over heads of int64 arrays,
@@ -301,7 +313,8 @@ def compress_layer(K: np.ndarray, V: np.ndarray, Q: np.ndarray, p: Params,
     for b in range(Bt):
         for h in range(Hkv):
             u = score_unit(K[b, h], V[b, h], Q[b, h * G:(h + 1) * G], p,
-                           None if r_given is None else float(r_given[b, h]))
+                           None if r_given is None else float(r_given[b, h]),
+                           None if window_lse is None else window_lse[b, h * G:(h + 1) * G])
             scores[b, h, :Nc] = u["s_comp"]
             red[b, h] = u["r"]
         if p.budget_mode == "fixed":

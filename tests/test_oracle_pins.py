@@ -512,3 +512,47 @@ def test_similarity_analysis_closed_forms():
     R = np.array(brute.cosine_matrix(K.tolist()))
     np.testing.assert_allclose(O.similarity_analysis(K, 1)["block_map"], R, atol=1e-13)
     np.testing.assert_allclose(O.similarity_analysis(K, 64)["block_map"], [[R.mean()]], atol=1e-13)
+
+
+# ------------------------------------------------------------------ log-sum-exp handed in by the caller
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_given_lse_reproduces_the_softmax_and_is_actually_used(causal):
+    from scipy.special import logsumexp
+    K, V, Q = _rand_unit(61, N=26, D=8, G=2, W=3)
+    N, W = 26, 3
+    logits = 0.5 * np.einsum("gwd,nd->gwn", Q, K)
+    lse = np.empty((2, W))
+    for w in range(W):
+        hi = N - W + w + 1 if causal else N
+        lse[:, w] = logsumexp(logits[:, w, :hi], axis=1)       # library routine over the visible keys
+    P = O.window_attention(K, Q, 0.5, causal)
+    P2 = O.window_attention(K, Q, 0.5, causal, lse)
+    np.testing.assert_allclose(P2, P, rtol=1e-12, atol=1e-300)
+    p = _params(B=8, causal_window=causal, pool="max", pool_kernel=3)
+    a, b = O.score_unit(K, V, Q, p), O.score_unit(K, V, Q, p, lse=lse)
+    np.testing.assert_allclose(b["s_comp"], a["s_comp"], rtol=1e-11)
+    # a normaliser larger by ln 2 halves every weight: the given value is what normalises
+    np.testing.assert_allclose(O.window_attention(K, Q, 0.5, causal, lse + math.log(2.0)), 0.5 * P, rtol=1e-12)
+    want = brute.window_mean_attention(K.tolist(), Q.tolist(), 0.5, causal)
+    np.testing.assert_allclose(O.extrinsic_importance(K, Q, _params(causal_window=causal), lse), want[:N - W], rtol=1e-11)
+
+
+def test_compress_layer_maps_given_lse_to_the_heads_of_each_group():
+    from scipy.special import logsumexp
+    rng = np.random.default_rng(62)
+    Bt, Hq, Hkv, N, D, W, B = 2, 4, 2, 24, 8, 3, 8
+    K = rng.standard_normal((Bt, Hkv, N, D)) + 0.5
+    V = rng.standard_normal((Bt, Hkv, N, D))
+    Q = rng.standard_normal((Bt, Hq, W, D))
+    lse = np.empty((Bt, Hq, W))
+    for b in range(Bt):
+        for g in range(Hq):
+            for w in range(W):
+                lse[b, g, w] = logsumexp(Q[b, g, w] @ K[b, g // 2, :N - W + w + 1].T)
+    p = O.Params(Hq, Hkv, W, B, pool="max", pool_kernel=3)
+    a, c = O.compress_layer(K, V, Q, p), O.compress_layer(K, V, Q, p, window_lse=lse)
+    np.testing.assert_allclose(c["scores"][:, :, :N - W], a["scores"][:, :, :N - W], rtol=1e-11)
+    for b in range(Bt):
+        for h in range(Hkv):
+            np.testing.assert_array_equal(c["indices"][b][h], a["indices"][b][h])
