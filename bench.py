@@ -41,6 +41,7 @@ _BUDGET = None
 _VARIANT = ("vnorm", "head_adaptive")
 _RGIVEN = None
 _HEAD_BUDGETS = None
+_LSE = None
 
 
 def _oracle_layer(l):
@@ -51,15 +52,30 @@ def _oracle_layer(l):
                  softmax_scale=wl.softmax_scale, eps=wl.eps, budget_mode=wl.budget_mode if hb is None else "per_head",
                  budget_floor=wl.budget_floor, intrinsic=_VARIANT[0], mix=_VARIANT[1])
     out = O.compress_layer(_LAYERS[l].K, _LAYERS[l].V, _LAYERS[l].Q, p, None if _RGIVEN is None else _RGIVEN[l],
-                           None if hb is None else hb[l])
+                           None if hb is None else hb[l], None if _LSE is None else _LSE[l].astype(np.float64))
     return l, [[i.astype(np.int32) for i in row] for row in out["indices"]], out["scores"].astype(np.float32)
 
 
-def cpu_baseline(wl, layers, budget, max_layers, variant, r_given, head_budgets):
+def window_lse(wl, lay):
+    """Stand-in for what the prefill attention kernel hands over: log-sum-exp of the window rows'
+    logits over the keys each row attends to (causal), float32 [batch, Hq, W]."""
+    n, w, g = wl.seq_len, wl.window, wl.group
+    out = np.empty((wl.batch, wl.n_q_heads, w), dtype=np.float32)
+    vis = np.arange(n)[None, :] <= (n - w + np.arange(w))[:, None]
+    for b in range(wl.batch):
+        for h in range(wl.n_q_heads):
+            s = wl.softmax_scale * (lay.Q[b, h].astype(np.float64) @ lay.K[b, h // g].astype(np.float64).T)
+            s = np.where(vis, s, -np.inf)
+            m = s.max(axis=1)
+            out[b, h] = m + np.log(np.exp(s - m[:, None]).sum(axis=1))
+    return out
+
+
+def cpu_baseline(wl, layers, budget, max_layers, variant, r_given, head_budgets, lse):
     """Time the oracle as it stands on a bounded sample (the first `max_layers` layers)."""
     import multiprocessing as mp
-    global _LAYERS, _WL, _BUDGET, _VARIANT, _RGIVEN, _HEAD_BUDGETS
-    _LAYERS, _WL, _BUDGET, _VARIANT, _RGIVEN, _HEAD_BUDGETS = layers, wl, budget, variant, r_given, head_budgets
+    global _LAYERS, _WL, _BUDGET, _VARIANT, _RGIVEN, _HEAD_BUDGETS, _LSE
+    _LAYERS, _WL, _BUDGET, _VARIANT, _RGIVEN, _HEAD_BUDGETS, _LSE = layers, wl, budget, variant, r_given, head_budgets, lse
     n = min(max_layers, len(layers))
     workers = max(1, min(n, len(os.sched_getaffinity(0)), int(os.environ.get("MIXKV_BENCH_WORKERS", "16"))))
     ctx = mp.get_context("fork")                   # children inherit the generated layers; no GPU state exists yet
@@ -105,6 +121,9 @@ def main():
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="also launch an elementwise copy kernel that reads and writes this many MiB: a kernel of "
                          "known traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled")
+    ap.add_argument("--given-lse", action="store_true",
+                    help="hand the window rows' log-sum-exp to the library, as a prefill attention kernel would "
+                         "(the first pass then computes no logits); a variant, not the headline")
     ap.add_argument("--similarity-block", type=int, default=0,
                     help="also time mixkv_similarity (redundancy analysis of the keys: r and the heat-map at this "
                          "block size) on the same cache; reported in an extra 'similarity' object")
@@ -137,10 +156,11 @@ def main():
         head_budgets = np.repeat(per_layer[:, None], wl.n_kv_heads, axis=1)
     budget_mode = wl.budget_mode if head_budgets is None else "per_head"
     capacity = budget if head_budgets is None else int(head_budgets.max())      # rows per head in the output buffers
+    lse = [window_lse(wl, lay) for lay in layers] if args.given_lse else None
     cpu, oracle_res = (None, {})
     if args.cpu_layers > 0:
         cpu, oracle_res = cpu_baseline(wl, layers, budget, args.cpu_layers, (args.intrinsic, args.mix), r_given,
-                                       head_budgets)
+                                       head_budgets, lse)
 
     import torch
     from paper_2510_20707_amd import binding as B
@@ -161,7 +181,8 @@ def main():
     outs = [B.alloc_layer_out(p, dev, scores=False, redundancy=True) for _ in layers]
     ws = B.alloc_workspace(p, len(layers), dev)
     rg_dev = None if r_given is None else [torch.from_numpy(r).to(dev) for r in r_given]
-    calls = [B.PreparedCall(p, [x[0] for x in c], [x[1] for x in c], [x[2] for x in c], outs, ws, rg_dev)
+    lse_dev = None if lse is None else [torch.from_numpy(x).to(dev) for x in lse]
+    calls = [B.PreparedCall(p, [x[0] for x in c], [x[1] for x in c], [x[2] for x in c], outs, ws, rg_dev, lse_dev)
              for c in copies]
     stream = torch.cuda.current_stream()
 
@@ -249,7 +270,8 @@ def main():
         "config": {"workload": f"{wl.name}: {wl.n_layers} layers x {wl.n_q_heads}Q/{wl.n_kv_heads}KV heads, D={wl.head_dim}, "
                                f"N={wl.seq_len}, W={wl.window}, B={budget}, batch={wl.batch}, "
                                f"{wl.budget_mode if head_budgets is None else 'per-layer pyramid (mean B)'} budgets, "
-                               f"pool=max{wl.pool_kernel}, intrinsic={args.intrinsic}, mix={args.mix}",
+                               f"pool=max{wl.pool_kernel}, intrinsic={args.intrinsic}, mix={args.mix}"
+                               + (", window log-sum-exp given" if args.given_lse else ""),
                    "units": units, "input_copies_round_robin": len(copies)},
         "hbm_frac_end_to_end": bytes_step / (dt / args.steps) / HBM_PEAK,
         "algorithmic_bytes_per_step": bytes_step,

@@ -39,7 +39,7 @@
 extern "C" {
 #endif
 
-#define MIXKV_VERSION 4
+#define MIXKV_VERSION 5
 #define MIXKV_MAX_LAYERS 128      /* layers per call */
 #define MIXKV_MAX_WINDOW 64
 #define MIXKV_MAX_GROUP_ROWS 512  /* G * W */
@@ -107,6 +107,11 @@ typedef struct {
   const void *Qwin;          /* [batch, n_q_heads, W, D] contiguous, post-RoPE observation-window queries */
   const float *r_given;      /* [batch, n_kv_heads] head weights for MIXKV_MIX_GIVEN_R, finite; ignored (may be
                                 NULL) in every other mix mode */
+  const float *window_lse;   /* optional [batch, n_q_heads, W]: for every window query row the natural logarithm of
+                                sum_i exp(softmax_scale * Q.K_i) over the keys the row attends to (all N, or 0..Nc+w
+                                with causal_window), as the prefill attention kernel already produced it for these
+                                rows.  When given (then for every layer of the call) the first pass computes no
+                                window logits and the softmax is normalised by these values; NULL: computed here */
 } mixkv_layer_in;
 
 /* Outputs for one layer.  Which members are required is stated per entry point. */
@@ -138,7 +143,8 @@ mixkv_status mixkv_workspace_size(const mixkv_params *params, int32_t n_layers, 
  * Score every cached key (Algorithm 1, step 1 and the mixing half of step 2).
  * Per (layer, batch item, KV head):
  *   s_ex   mean over the G*W window queries of softmax attention on key i (Sec. 3.2,
- *          extrinsic importance), pooled over candidates;
+ *          extrinsic importance), pooled over candidates; the rows' normalisers are computed
+ *          here or taken from in[l].window_lse;
  *   s_imp  s_ex + min-max normalised value norm scaled to mean(s_ex) (Sec. 3.2, Eq. 2);
  *   s_div  -Khat_i . mean_j Khat_j with Khat the L2-normalised keys, all N keys in the mean
  *          (Sec. 3.2, diversity metrics), min-max normalised and scaled to mean(s_imp) (Sec. 3.3);

@@ -40,7 +40,8 @@ class MixkvParams(C.Structure):
 
 class MixkvLayerIn(C.Structure):
     _fields_ = [("K", C.c_void_p), ("V", C.c_void_p), ("kv_stride_b", C.c_int64), ("kv_stride_h", C.c_int64),
-                ("kv_stride_n", C.c_int64), ("Qwin", C.c_void_p), ("r_given", C.c_void_p)]
+                ("kv_stride_n", C.c_int64), ("Qwin", C.c_void_p), ("r_given", C.c_void_p),
+                ("window_lse", C.c_void_p)]
 
 
 class MixkvLayerOut(C.Structure):
@@ -154,8 +155,9 @@ def _ptr(t: Optional[torch.Tensor]):
     return None if t is None else C.c_void_p(t.data_ptr())
 
 
-def _in_array(Ks, Vs, Qs, r_given=None):
-    """r_given: per layer a contiguous f32 [batch, Hkv] device tensor (mix "given_r"), or None."""
+def _in_array(Ks, Vs, Qs, r_given=None, window_lse=None):
+    """r_given: per layer a contiguous f32 [batch, Hkv] device tensor (mix "given_r"), or None;
+    window_lse: per layer a contiguous f32 [batch, Hq, W] device tensor, or None."""
     n = len(Ks)
     arr = (MixkvLayerIn * n)()
     for i, (K, V, Q) in enumerate(zip(Ks, Vs, Qs)):
@@ -163,8 +165,11 @@ def _in_array(Ks, Vs, Qs, r_given=None):
         assert Q is None or Q.is_contiguous()
         rg = None if r_given is None else r_given[i]
         assert rg is None or (rg.is_contiguous() and rg.dtype == torch.float32 and rg.shape == K.shape[:2])
+        lse = None if window_lse is None else window_lse[i]
+        assert lse is None or (lse.is_contiguous() and lse.dtype == torch.float32 and lse.shape == Q.shape[:3])
         arr[i] = MixkvLayerIn(K.data_ptr(), V.data_ptr(), K.stride(0), K.stride(1), K.stride(2),
-                              None if Q is None else Q.data_ptr(), None if rg is None else rg.data_ptr())
+                              None if Q is None else Q.data_ptr(), None if rg is None else rg.data_ptr(),
+                              None if lse is None else lse.data_ptr())
     return arr
 
 
@@ -204,9 +209,9 @@ def _ws(workspace: Optional[torch.Tensor]):
 
 
 def mixkv_score(p: MixkvParams, Ks, Vs, Qs, outs: Sequence[LayerOut], workspace: torch.Tensor, stream=None,
-                r_given=None):
+                r_given=None, window_lse=None):
     wp, wb = _ws(workspace)
-    _check(lib().mixkv_score(C.byref(p), _in_array(Ks, Vs, Qs, r_given), _out_array(outs), len(outs), wp, wb, _stream(stream)),
+    _check(lib().mixkv_score(C.byref(p), _in_array(Ks, Vs, Qs, r_given, window_lse), _out_array(outs), len(outs), wp, wb, _stream(stream)),
            "mixkv_score")
 
 
@@ -216,9 +221,9 @@ def mixkv_select(p: MixkvParams, outs: Sequence[LayerOut], workspace: Optional[t
 
 
 def mixkv_compress(p: MixkvParams, Ks, Vs, Qs, outs: Sequence[LayerOut], workspace: torch.Tensor, stream=None,
-                   r_given=None):
+                   r_given=None, window_lse=None):
     wp, wb = _ws(workspace)
-    _check(lib().mixkv_compress(C.byref(p), _in_array(Ks, Vs, Qs, r_given), _out_array(outs), len(outs), wp, wb,
+    _check(lib().mixkv_compress(C.byref(p), _in_array(Ks, Vs, Qs, r_given, window_lse), _out_array(outs), len(outs), wp, wb,
                                 _stream(stream)), "mixkv_compress")
 
 
@@ -266,11 +271,12 @@ def mixkv_similarity(p: MixkvParams, Xs, block: int, want_map: bool = True, work
 class PreparedCall:
     """The C argument arrays of one call, built once (so a timed loop measures the library, not ctypes)."""
 
-    def __init__(self, p: MixkvParams, Ks, Vs, Qs, outs: Sequence[LayerOut], workspace: torch.Tensor, r_given=None):
+    def __init__(self, p: MixkvParams, Ks, Vs, Qs, outs: Sequence[LayerOut], workspace: torch.Tensor, r_given=None,
+                 window_lse=None):
         self.p, self.n = p, len(outs)
-        self.ins, self.outs = _in_array(Ks, Vs, Qs, r_given), _out_array(outs)
+        self.ins, self.outs = _in_array(Ks, Vs, Qs, r_given, window_lse), _out_array(outs)
         self.wp, self.wb = _ws(workspace)
-        self._keep = (Ks, Vs, Qs, outs, workspace, r_given)
+        self._keep = (Ks, Vs, Qs, outs, workspace, r_given, window_lse)
         self._L = lib()
 
     def compress(self, stream=None):

@@ -165,6 +165,7 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
       if ((li.kv_stride_n * eb) % 16 || (li.kv_stride_h * eb) % 16 || (li.kv_stride_b * eb) % 16) return MIXKV_ERR_INVALID_ARG;
       if ((stages & kScore) && (!li.Qwin || !aligned16(li.Qwin))) return MIXKV_ERR_INVALID_ARG;
       if ((stages & kScore) && s.mix == MIXKV_MIX_GIVEN_R && !li.r_given) return MIXKV_ERR_INVALID_ARG;
+      if ((stages & kScore) && ((li.window_lse != nullptr) != (in[0].window_lse != nullptr))) return MIXKV_ERR_INVALID_ARG;
     }
     const mixkv_layer_out &lo = out[l];
     if (stages == kScore && !lo.scores) return MIXKV_ERR_INVALID_ARG;
@@ -202,8 +203,10 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
     const int nl = (n_layers - l0 < kLayersPerLaunch) ? n_layers - l0 : kLayersPerLaunch;
     LayerInTable ti;
     LayerOutTable to;
+    LseTable tl;
     std::memset(&ti, 0, sizeof(ti));
     std::memset(&to, 0, sizeof(to));
+    std::memset(&tl, 0, sizeof(tl));
     const int64_t unit0 = (int64_t)l0 * s.units_per_layer;
     // One fused kernel mixes the scores and, in fixed-budget mode, selects; scores reach memory
     // only if somebody reads them (the caller, or the separate selection kernels).
@@ -217,6 +220,7 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
         const mixkv_layer_in &li = in[l0 + l];
         ti.l[l] = LayerIn{li.K, li.V, li.Qwin, li.kv_stride_b, li.kv_stride_h, li.kv_stride_n,
                           s.mix == MIXKV_MIX_GIVEN_R ? li.r_given : nullptr};
+        tl.l[l] = li.window_lse;
       }
       const mixkv_layer_out &lo = out[l0 + l];
       float *scores = lo.scores;
@@ -229,8 +233,9 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
     if (result == MIXKV_OK && (stages & kScore)) {
       const int grid = stream_grid(s, nunits, num_cus);
       const int64_t slot0 = (int64_t)(l0 / kLayersPerLaunch) * (kMaxStreamGrid + kLayersPerLaunch * s.units_per_layer);
-      ok(timed(0, [&] { return launch_stats(s, params->dtype, ti, ws, w, unit0, nunits, grid, slot0, stream); })) &&
-          ok(timed(1, [&] { return launch_attn(s, params->dtype, ti, to, ws, w, unit0, nunits, grid, slot0, stream); })) &&
+      const bool given_lse = in[0].window_lse != nullptr;
+      ok(timed(0, [&] { return launch_stats(s, params->dtype, ti, ws, w, unit0, nunits, grid, slot0, given_lse, stream); })) &&
+          ok(timed(1, [&] { return launch_attn(s, params->dtype, ti, to, tl, ws, w, unit0, nunits, grid, slot0, stream); })) &&
           ok(timed(2, [&] {
             return fused ? launch_mixsel(s, fused_select || cand_m > 0, to, ws, w, unit0, nunits, ti,
                                          fused_gather ? eb : 0, cand_m, budgets_l0, stream)

@@ -22,6 +22,9 @@ struct LayerIn {
 };
 struct LayerInTable { LayerIn l[kLayersPerLaunch]; };
 
+// The window rows' log-sum-exp per layer, when the caller has it (else all null).
+struct LseTable { const float *l[kLayersPerLaunch]; };
+
 struct LayerOut {
   float *scores;                       // may point into the workspace
   float *redundancy;                   // may be null
@@ -72,10 +75,12 @@ void carve_workspace(const Shape &s, int64_t units, Workspace *w);
 // `grid` (from stream_grid) is the number of workgroups of the two streaming kernels; `slot0` is the
 // first partial slot of this launch group (each group owns kMaxStreamGrid + its units).
 int stream_grid(const Shape &s, int nunits, int num_cus);
+// `given_lse`: the caller supplies the softmax normalisers, so the first pass takes key and value
+// statistics only; `lse` then holds them per layer (all null otherwise).
 hipError_t launch_stats(const Shape &s, int dtype, const LayerInTable &in, char *ws, const Workspace &w, int64_t unit0,
-                        int nunits, int grid, int64_t slot0, hipStream_t st);
-hipError_t launch_attn(const Shape &s, int dtype, const LayerInTable &in, const LayerOutTable &out, char *ws,
-                       const Workspace &w, int64_t unit0, int nunits, int grid, int64_t slot0, hipStream_t st);
+                        int nunits, int grid, int64_t slot0, bool given_lse, hipStream_t st);
+hipError_t launch_attn(const Shape &s, int dtype, const LayerInTable &in, const LayerOutTable &out, const LseTable &lse,
+                       char *ws, const Workspace &w, int64_t unit0, int nunits, int grid, int64_t slot0, hipStream_t st);
 hipError_t launch_mix(const Shape &s, const LayerInTable &in, const LayerOutTable &out, char *ws, const Workspace &w,
                       int64_t unit0, int nunits, hipStream_t st);
 // Weights of s_imp and of the scaled diversity in s_comp (Sec. 3.3, Eq. 5; Table 4's variants);

@@ -247,6 +247,9 @@ __device__ __forceinline__ void wait_tile(int t, int nt) {
 //     Sec. 3.3 Eq. 3-4: only the sum of normalised keys is needed, never the T x T matrix);
 //   * |V_i| (Sec. 3.2, VNorm intrinsic importance).
 // Per-run partials go to the workspace; fold_kernel folds them per unit.
+// With GIVEN_LSE the caller already has the softmax normalisers of the window rows (the prefill
+// attention produced them), so the kernel takes no queries and only the key and value statistics
+// remain: a plain streaming pass.
 // ------------------------------------------------------------------------------------------------
 // Waves per SIMD the register allocation of stats_kernel aims at: two workgroups per compute unit
 // where their two rings fit in LDS together (tiles of up to 8 KB), one otherwise.
@@ -256,7 +259,7 @@ __host__ __device__ constexpr int stats_waves_per_simd(int dtype, int D, int wav
   return waves / 4 * wgs;
 }
 
-template <int DT, int D, int WAVES, int TQ>
+template <int DT, int D, int WAVES, int TQ, bool GIVEN_LSE = false>
 __global__ __launch_bounds__(WAVES * 64, stats_waves_per_simd(DT, D, WAVES, TQ)) void stats_kernel(
     Shape s, LayerInTable in, char *ws, Workspace w, int64_t unit0, int nunits, int64_t slot0) {
   constexpr int EB = Tr<DT>::EB, EPC = Tr<DT>::EPC, NCHK = D / (2 * EPC), PPR = D * EB / 16;
@@ -311,7 +314,7 @@ __global__ __launch_bounds__(WAVES * 64, stats_waves_per_simd(DT, D, WAVES, TQ))
     int lim[TQ];
     float m[TQ], l[TQ];
 #pragma unroll
-    for (int q = 0; q < TQ; ++q) {
+    for (int q = 0; q < (GIVEN_LSE ? 0 : TQ); ++q) {
       const int row = (wave * TQ + q) * 32 + l32;
       const bool live = row < s.GW;
       const char *qrow = Qb + ((int64_t)(live ? row : 0) * D) * EB + half * 16;
@@ -346,20 +349,22 @@ __global__ __launch_bounds__(WAVES * 64, stats_waves_per_simd(DT, D, WAVES, TQ))
       const int tb = key0 + t * 32;
       const uint4 *img = kring + (t & (kRing - 1)) * TILE;
       const uint4 *vimg = vring + (t & (kRing - 1)) * TILE;
-      Frag kf[NCHK];
-#pragma unroll
-      for (int c = 0; c < NCHK; ++c) kf[c].q = read_key_frag<DT, D>(img, 0, c, l32, half);
 
       // ---- softmax statistics of all TQ tiles; the MFMA chains are independent
       f32x16 acc[TQ];
+      if constexpr (!GIVEN_LSE) {
+        Frag kf[NCHK];
 #pragma unroll
-      for (int q = 0; q < TQ; ++q)
+        for (int c = 0; c < NCHK; ++c) kf[c].q = read_key_frag<DT, D>(img, 0, c, l32, half);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[q][i] = 0.f;
+        for (int q = 0; q < TQ; ++q)
 #pragma unroll
-      for (int c = 0; c < NCHK; ++c)
+          for (int i = 0; i < 16; ++i) acc[q][i] = 0.f;
 #pragma unroll
-        for (int q = 0; q < TQ; ++q) acc[q] = mma<DT>(kf[c], qf[q][c], acc[q]);
+        for (int c = 0; c < NCHK; ++c)
+#pragma unroll
+          for (int q = 0; q < TQ; ++q) acc[q] = mma<DT>(kf[c], qf[q][c], acc[q]);
+      }
 
       // ---- key norms and the sum of normalised keys (independent of the MFMA results, so it can
       // fill the vector ALU while the matrix core runs).  The tile image is walked 64 pieces at a
@@ -395,7 +400,7 @@ __global__ __launch_bounds__(WAVES * 64, stats_waves_per_simd(DT, D, WAVES, TQ))
         }
       }
 
-      if (tb + 31 > free_limit) {                  // tile reaches into the window or past N: mask
+      if (!GIVEN_LSE && tb + 31 > free_limit) {    // tile reaches into the window or past N: mask
 #pragma unroll
         for (int q = 0; q < TQ; ++q)
 #pragma unroll
@@ -405,7 +410,7 @@ __global__ __launch_bounds__(WAVES * 64, stats_waves_per_simd(DT, D, WAVES, TQ))
           }
       }
 #pragma unroll
-      for (int q = 0; q < TQ; ++q) {
+      for (int q = 0; q < (GIVEN_LSE ? 0 : TQ); ++q) {
         float tmax = fmaxf(acc[q][0], acc[q][1]);
 #pragma unroll
         for (int i = 2; i < 16; i += 2) tmax = fmaxf(fmaxf(tmax, acc[q][i]), acc[q][i + 1]);
@@ -430,7 +435,7 @@ __global__ __launch_bounds__(WAVES * 64, stats_waves_per_simd(DT, D, WAVES, TQ))
     const int64_t slot = slot0 + blockIdx.x + ul;
     float2 *part_ml = reinterpret_cast<float2 *>(ws + w.part_ml) + slot * QTR;
 #pragma unroll
-    for (int q = 0; q < TQ; ++q) {
+    for (int q = 0; q < (GIVEN_LSE ? 0 : TQ); ++q) {
       ml_merge(m[q], l[q], __shfl_xor(m[q], 32), __shfl_xor(l[q], 32));
       if (q < nq && half == 0) part_ml[(wave * TQ + q) * 32 + l32] = make_float2(m[q], l[q]);
     }
@@ -457,6 +462,7 @@ __global__ __launch_bounds__(WAVES * 64, stats_waves_per_simd(DT, D, WAVES, TQ))
 // for the unit, in run order:
 //   * per window-query row the exponent offset -b_r, b_r = max_r + log2(sum_r * G*W), so that
 //     exp2(x - b_r) is the softmax weight already divided by the number of rows (-inf past G*W);
+//     with the caller's log-sum-exp of the row, b_r = lse_r * log2(e) + log2(G*W) instead;
 //   * the mean normalised key as two rows of 16-byte pieces: row 0 its bf16 head, row 1 the bf16
 //     remainder (zero for f32), piece (c, half) of row r at index (c * 2 + half) * 2 + r;
 //   * the redundancy r (paper Sec. 3.3, Eq. 3-4).
@@ -467,7 +473,7 @@ __global__ __launch_bounds__(WAVES * 64, stats_waves_per_simd(DT, D, WAVES, TQ))
 constexpr int kFoldThreads = 256;
 
 template <int DT, int D>
-__global__ __launch_bounds__(kFoldThreads) void fold_kernel(Shape s, LayerOutTable out, char *ws, Workspace w,
+__global__ __launch_bounds__(kFoldThreads) void fold_kernel(Shape s, LayerOutTable out, LseTable lse, char *ws, Workspace w,
                                                             int64_t unit0, int nunits, int G1, int64_t slot0) {
   constexpr int EPC = Tr<DT>::EPC, NCHK = D / (2 * EPC), NW = kFoldThreads / 64;
   __shared__ float kbar_f[D];
@@ -481,9 +487,13 @@ __global__ __launch_bounds__(kFoldThreads) void fold_kernel(Shape s, LayerOutTab
 
   const float2 *all_ml = reinterpret_cast<const float2 *>(ws + w.part_ml) + (slot0 + ul) * QTR;
   float *nb = reinterpret_cast<float *>(ws + w.nb) + unit * s.nb_rows;
+  // rows of this head's group are consecutive in [batch, n_q_heads, W]
+  const float *lse_u = lse.l[uc.layer] ? lse.l[uc.layer] + (int64_t)(uc.b * s.hq + uc.h * s.G) * s.W : nullptr;
   for (int r = tid; r < s.nb_rows; r += kFoldThreads) {
     float b = INFINITY;                                // rows past G*W: weight 0
-    if (r < s.GW) {
+    if (r < s.GW && lse_u) {
+      b = lse_u[r] * 1.4426950408889634f + log2f((float)s.GW);
+    } else if (r < s.GW) {
       float m = -INFINITY, l = 0.f;
       for (int g0 = g_lo; g0 <= g_hi; g0 += 8) {       // batches of eight independent loads
         float2 p[8];
@@ -763,19 +773,20 @@ int stream_grid(const Shape &s, int nunits, int num_cus) {
   return (int)(T < cap ? T : cap);
 }
 
-template <int DT, int D, int WAVES, int TQ>
+template <int DT, int D, int WAVES, int TQ, bool GIVEN_LSE = false>
 static hipError_t launch_stats_c(const Shape &s, const LayerInTable &in, char *ws, const Workspace &w, int64_t unit0,
                                  int nunits, int grid, int64_t slot0, hipStream_t st) {
-  auto kern = stats_kernel<DT, D, WAVES, TQ>;
+  auto kern = stats_kernel<DT, D, WAVES, TQ, GIVEN_LSE>;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES * 64), 0, st, s, in, ws, w, unit0, nunits, slot0);
   return hipGetLastError();
 }
 
 template <int DT, int D, int WAVES, int TQ>
-static hipError_t launch_attn_c(const Shape &s, const LayerInTable &in, const LayerOutTable &out, char *ws,
-                                const Workspace &w, int64_t unit0, int nunits, int grid, int64_t slot0, hipStream_t st) {
+static hipError_t launch_attn_c(const Shape &s, const LayerInTable &in, const LayerOutTable &out, const LseTable &lse,
+                                char *ws, const Workspace &w, int64_t unit0, int nunits, int grid, int64_t slot0,
+                                hipStream_t st) {
   auto fold = fold_kernel<DT, D>;
-  hipLaunchKernelGGL(fold, dim3(nunits), dim3(kFoldThreads), 0, st, s, out, ws, w, unit0, nunits, grid, slot0);
+  hipLaunchKernelGGL(fold, dim3(nunits), dim3(kFoldThreads), 0, st, s, out, lse, ws, w, unit0, nunits, grid, slot0);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   auto kern = attn_kernel<DT, D, WAVES, TQ>;
@@ -785,8 +796,10 @@ static hipError_t launch_attn_c(const Shape &s, const LayerInTable &in, const La
 
 template <int DT, int D>
 static hipError_t launch_stats_t(const Shape &s, const LayerInTable &in, char *ws, const Workspace &w, int64_t unit0,
-                                 int nunits, int grid, int64_t slot0, hipStream_t st) {
+                                 int nunits, int grid, int64_t slot0, bool given_lse, hipStream_t st) {
   int waves, tq;
+  // without the logits the pass is a plain stream: eight waves per workgroup keep more loads in flight
+  if (given_lse) return launch_stats_c<DT, D, 8, 1, true>(s, in, ws, w, unit0, nunits, grid, slot0, st);
   stats_config(s.QT, &waves, &tq);
   if (waves == 4 && tq == 1) return launch_stats_c<DT, D, 4, 1>(s, in, ws, w, unit0, nunits, grid, slot0, st);
   if (waves == 4) return launch_stats_c<DT, D, 4, 2>(s, in, ws, w, unit0, nunits, grid, slot0, st);
@@ -795,35 +808,36 @@ static hipError_t launch_stats_t(const Shape &s, const LayerInTable &in, char *w
 }
 
 template <int DT, int D>
-static hipError_t launch_attn_t(const Shape &s, const LayerInTable &in, const LayerOutTable &out, char *ws,
-                                const Workspace &w, int64_t unit0, int nunits, int grid, int64_t slot0, hipStream_t st) {
+static hipError_t launch_attn_t(const Shape &s, const LayerInTable &in, const LayerOutTable &out, const LseTable &lse,
+                                char *ws, const Workspace &w, int64_t unit0, int nunits, int grid, int64_t slot0,
+                                hipStream_t st) {
   int waves, tq;
   stream_config(s.QT, &waves, &tq);
-  if (waves == 4 && tq == 1) return launch_attn_c<DT, D, 4, 1>(s, in, out, ws, w, unit0, nunits, grid, slot0, st);
-  if (waves == 4) return launch_attn_c<DT, D, 4, 2>(s, in, out, ws, w, unit0, nunits, grid, slot0, st);
-  return launch_attn_c<DT, D, 8, 2>(s, in, out, ws, w, unit0, nunits, grid, slot0, st);
+  if (waves == 4 && tq == 1) return launch_attn_c<DT, D, 4, 1>(s, in, out, lse, ws, w, unit0, nunits, grid, slot0, st);
+  if (waves == 4) return launch_attn_c<DT, D, 4, 2>(s, in, out, lse, ws, w, unit0, nunits, grid, slot0, st);
+  return launch_attn_c<DT, D, 8, 2>(s, in, out, lse, ws, w, unit0, nunits, grid, slot0, st);
 }
 
 hipError_t launch_stats(const Shape &s, int dtype, const LayerInTable &in, char *ws, const Workspace &w, int64_t unit0,
-                        int nunits, int grid, int64_t slot0, hipStream_t st) {
+                        int nunits, int grid, int64_t slot0, bool given_lse, hipStream_t st) {
   if (dtype == MIXKV_BF16) {
-    if (s.D == 128) return launch_stats_t<MIXKV_BF16, 128>(s, in, ws, w, unit0, nunits, grid, slot0, st);
-    return launch_stats_t<MIXKV_BF16, 64>(s, in, ws, w, unit0, nunits, grid, slot0, st);
+    if (s.D == 128) return launch_stats_t<MIXKV_BF16, 128>(s, in, ws, w, unit0, nunits, grid, slot0, given_lse, st);
+    return launch_stats_t<MIXKV_BF16, 64>(s, in, ws, w, unit0, nunits, grid, slot0, given_lse, st);
   }
-  if (s.D == 128) return launch_stats_t<MIXKV_F32, 128>(s, in, ws, w, unit0, nunits, grid, slot0, st);
-  return launch_stats_t<MIXKV_F32, 64>(s, in, ws, w, unit0, nunits, grid, slot0, st);
+  if (s.D == 128) return launch_stats_t<MIXKV_F32, 128>(s, in, ws, w, unit0, nunits, grid, slot0, given_lse, st);
+  return launch_stats_t<MIXKV_F32, 64>(s, in, ws, w, unit0, nunits, grid, slot0, given_lse, st);
 }
 
 // `grid` must be the grid stats_kernel ran with: both kernels split the same items the same way,
 // and attn_kernel uses it to find the partials of its units.
-hipError_t launch_attn(const Shape &s, int dtype, const LayerInTable &in, const LayerOutTable &out, char *ws,
-                       const Workspace &w, int64_t unit0, int nunits, int grid, int64_t slot0, hipStream_t st) {
+hipError_t launch_attn(const Shape &s, int dtype, const LayerInTable &in, const LayerOutTable &out, const LseTable &lse,
+                       char *ws, const Workspace &w, int64_t unit0, int nunits, int grid, int64_t slot0, hipStream_t st) {
   if (dtype == MIXKV_BF16) {
-    if (s.D == 128) return launch_attn_t<MIXKV_BF16, 128>(s, in, out, ws, w, unit0, nunits, grid, slot0, st);
-    return launch_attn_t<MIXKV_BF16, 64>(s, in, out, ws, w, unit0, nunits, grid, slot0, st);
+    if (s.D == 128) return launch_attn_t<MIXKV_BF16, 128>(s, in, out, lse, ws, w, unit0, nunits, grid, slot0, st);
+    return launch_attn_t<MIXKV_BF16, 64>(s, in, out, lse, ws, w, unit0, nunits, grid, slot0, st);
   }
-  if (s.D == 128) return launch_attn_t<MIXKV_F32, 128>(s, in, out, ws, w, unit0, nunits, grid, slot0, st);
-  return launch_attn_t<MIXKV_F32, 64>(s, in, out, ws, w, unit0, nunits, grid, slot0, st);
+  if (s.D == 128) return launch_attn_t<MIXKV_F32, 128>(s, in, out, lse, ws, w, unit0, nunits, grid, slot0, st);
+  return launch_attn_t<MIXKV_F32, 64>(s, in, out, lse, ws, w, unit0, nunits, grid, slot0, st);
 }
 
 }  // namespace mixkv

@@ -68,8 +68,23 @@ def given_weights(wl: synth.Workload, layer_id: int) -> np.ndarray:
     return rng.uniform(0.0, 1.0, (wl.batch, wl.n_kv_heads)).astype(np.float32)
 
 
+def window_lse(wl: synth.Workload, lay: synth.Layer, causal=True) -> np.ndarray:
+    """What a prefill attention kernel would hand over for the window rows: log-sum-exp of
+    softmax_scale * Q.K over the keys each row attends to, float32, [batch, Hq, W] (computed here in
+    float64 with a library routine from the same inputs)."""
+    from scipy.special import logsumexp
+    N, W, G, Nc = wl.seq_len, wl.window, wl.group, wl.seq_len - wl.window
+    out = np.empty((wl.batch, wl.n_q_heads, W), dtype=np.float64)
+    for b in range(wl.batch):
+        for g in range(wl.n_q_heads):
+            logits = wl.softmax_scale * (lay.Q[b, g].astype(np.float64) @ lay.K[b, g // G].astype(np.float64).T)
+            for w in range(W):
+                out[b, g, w] = logsumexp(logits[w, :Nc + w + 1 if causal else N])
+    return out.astype(np.float32)
+
+
 def run_compress(wl: synth.Workload, layers, device="cuda:0", want_scores=True, r_given=None, head_budgets=None,
-                 **over):
+                 lse=None, **over):
     """mixkv_compress on a list of synth.Layer.  `r_given`: per layer a float32 [batch, Hkv] array
     (mix "given_r"); `head_budgets`: int [len(layers), Hkv] (budget mode "per_head").
     Returns (params, list of LayerOut on device)."""
@@ -81,7 +96,8 @@ def run_compress(wl: synth.Workload, layers, device="cuda:0", want_scores=True, 
     ws = B.alloc_workspace(p, len(layers), device)
     rg = None if r_given is None else [torch.from_numpy(np.ascontiguousarray(r, dtype=np.float32)).to(device)
                                         for r in r_given]
-    B.mixkv_compress(p, Ks, Vs, Qs, outs, ws, r_given=rg)
+    lse_dev = None if lse is None else [torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(device) for x in lse]
+    B.mixkv_compress(p, Ks, Vs, Qs, outs, ws, r_given=rg, window_lse=lse_dev)
     torch.cuda.synchronize()
     return p, outs
 
@@ -117,7 +133,7 @@ def check_topk_set(dtype, kept: np.ndarray, s_ora: np.ndarray, k: int, what=""):
 
 
 def check_layer(wl: synth.Workload, lay: synth.Layer, p: B.MixkvParams, out: B.LayerOut, units=None, r_given=None,
-                head_budgets=None, **over):
+                head_budgets=None, lse=None, **over):
     """Compare one layer of GPU output with the oracle.  `units`: iterable of (b, h) to check with
     the oracle (default all); invariants are checked on every unit.  `r_given`: this layer's
     [batch, Hkv] weights for mix "given_r"."""
@@ -162,7 +178,8 @@ def check_layer(wl: synth.Workload, lay: synth.Layer, p: B.MixkvParams, out: B.L
             if (b, h) not in todo:
                 continue
             u = O.score_unit(lay.K[b, h], lay.V[b, h], lay.Q[b, h * G:(h + 1) * G], op,
-                             None if r_given is None else float(r_given[b, h]))
+                             None if r_given is None else float(r_given[b, h]),
+                             None if lse is None else lse[b, h * G:(h + 1) * G].astype(np.float64))
             s_ora_heads[h] = u["s_comp"]
             what = f"{wl.name} b{b} h{h}"
             if sc_g is not None:

@@ -26,14 +26,14 @@ def test_library_exports_every_declared_symbol():
     L = B.lib()
     for n in set(names):
         assert hasattr(L, n), n
-    assert L.mixkv_version() == 4
+    assert L.mixkv_version() == 5
     assert B.status_string(0) == "ok" and "workspace" in B.status_string(3)
 
 
 def test_params_struct_matches_header_layout():
     # 17 four-byte members in the header, no padding
     assert C.sizeof(B.MixkvParams) == 17 * 4 + 4 + 8      # 17 four-byte fields, padding, one host pointer
-    assert C.sizeof(B.MixkvLayerIn) == 7 * 8 and C.sizeof(B.MixkvLayerOut) == 7 * 8
+    assert C.sizeof(B.MixkvLayerIn) == 8 * 8 and C.sizeof(B.MixkvLayerOut) == 7 * 8
 
 
 def test_workspace_size_scales_with_layers_and_is_aligned():

@@ -23,11 +23,12 @@ def _run_and_check(wl, n_layers=None, units=None, layer_ids=None, **over):
          f"D={wl.head_dim} N={wl.seq_len} W={wl.window} B={over.get('budget', wl.budget)} over={over}")
     rg = [H.given_weights(wl, l) for l in layer_ids] if over.get("mix") == "given_r" else None
     hb = over.pop("head_budgets", None)
-    p, outs = H.run_compress(wl, layers, r_given=rg, head_budgets=hb, **over)
+    lse = [H.window_lse(wl, lay, over.get("causal_window", True)) for lay in layers] if over.pop("given_lse", False) else None
+    p, outs = H.run_compress(wl, layers, r_given=rg, head_budgets=hb, lse=lse, **over)
     tot = dict(max_err=0.0, band=0, exact=0, checked=0)
     for i, (lay, out) in enumerate(zip(layers, outs)):
         st = H.check_layer(wl, lay, p, out, units=units, r_given=None if rg is None else rg[i],
-                           head_budgets=None if hb is None else hb[i], **over)
+                           head_budgets=None if hb is None else hb[i], lse=None if lse is None else lse[i], **over)
         tot["max_err"] = max(tot["max_err"], st["max_err"])
         for k in ("band", "exact", "checked"):
             tot[k] += st[k]
@@ -272,3 +273,41 @@ def test_equal_per_head_budgets_reproduce_fixed_mode_bit_for_bit():
     for name in ("indices", "counts", "offsets", "K_out", "V_out", "scores"):
         a, b = getattr(outs[0], name), getattr(outs2[0], name)
         assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), name
+
+
+# ------------------------------------------------------------------ softmax normalisers handed over by the caller
+
+def test_given_lse_c1_c2_and_variants():
+    _run_and_check(WL["c1"], given_lse=True)
+    _run_and_check(WL["c1"], given_lse=True, causal_window=False, pool="avg")
+    _run_and_check(WL["c2"], given_lse=True)
+    _run_and_check(WL["c2"], given_lse=True, intrinsic="knorm", mix="sum")
+
+
+@pytest.mark.parametrize("dtype,D,N,W,Hq,Hkv,B", [
+    ("bf16", 64, 1000, 5, 6, 2, 37), ("f32", 128, 777, 9, 4, 4, 100), ("bf16", 128, 333, 32, 16, 2, 40),
+])
+def test_given_lse_ragged_shapes(dtype, D, N, W, Hq, Hkv, B):
+    wl = WL["c2"].with_(name="ragged-lse", dtype=dtype, head_dim=D, seq_len=N, window=W, n_q_heads=Hq, n_kv_heads=Hkv,
+                        budget=B, batch=2, text_prefix=min(16, N // 4), text_suffix_start=N - max(W, N // 8))
+    _run_and_check(wl, n_layers=2, given_lse=True)
+
+
+def test_given_lse_c3_two_layers_and_adaptive_budgets():
+    _run_and_check(WL["c3"], layer_ids=[0, 17], units=[(0, 0), (0, 3)], given_lse=True)
+    wl = WL["c2"].with_(name="adaptive-lse", seq_len=1024, text_suffix_start=960, batch=2, budget=96,
+                        budget_mode="adaptive", budget_floor=16, sigma=(0.1, 0.8))
+    _run_and_check(wl, n_layers=2, given_lse=True)
+
+
+def test_given_lse_must_cover_every_layer_of_a_call():
+    wl = WL["c1"].with_(n_layers=2)
+    layers = [synth.make_layer(wl, l) for l in range(2)]
+    p = H.gpu_params(wl)
+    Ks, Vs, Qs = ([H.to_device(wl, getattr(l, n)) for l in layers] for n in ("K", "V", "Q"))
+    outs = [B.alloc_layer_out(p, "cuda:0") for _ in layers]
+    ws = B.alloc_workspace(p, 2, "cuda:0")
+    lse0 = torch.from_numpy(H.window_lse(wl, layers[0])).to("cuda:0")
+    with pytest.raises(B.MixkvError) as e:
+        B.mixkv_compress(p, Ks, Vs, Qs, outs, ws, window_lse=[lse0, None])
+    assert e.value.status == B.MIXKV_ERR_INVALID_ARG
