@@ -242,6 +242,29 @@ def similarity_analysis(X: np.ndarray, block: int) -> Dict[str, np.ndarray]:
     return dict(redundancy=np.float64(red), block_map=bm)
 
 
+# --------------------------------------------------------------------------- decoding on the compacted cache
+
+def decode_attention(q: np.ndarray, K_rows: List[np.ndarray], V_rows: List[np.ndarray], scale: float) -> np.ndarray:
+    """Attention of one new token over a compressed cache (Sec. 3.1: the compacted K, V serve the
+    attention of the decoding phase).
+
+    q [Hq, D]; K_rows / V_rows: per KV head the rows it holds, [n_h, D] (the kept rows followed by
+    whatever was appended since; n_h may differ between heads).  Query head g reads KV head
+    g // G.  Returns [Hq, D]: softmax_j(scale * q_g . k_j) weighted sum of the v_j.
+    """
+    q = np.asarray(q, dtype=np.float64)
+    Hq, Hkv = q.shape[0], len(K_rows)
+    G = Hq // Hkv
+    out = np.empty_like(q)
+    for g in range(Hq):
+        K = np.asarray(K_rows[g // G], dtype=np.float64)
+        V = np.asarray(V_rows[g // G], dtype=np.float64)
+        logit = scale * (K @ q[g])
+        e = np.exp(logit - logit.max())
+        out[g] = (e / e.sum()) @ V
+    return out
+
+
 # --------------------------------------------------------------------------- selection
 
 def top_indices(s: np.ndarray, b: int) -> np.ndarray:

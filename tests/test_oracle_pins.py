@@ -556,3 +556,41 @@ def test_compress_layer_maps_given_lse_to_the_heads_of_each_group():
     for b in range(Bt):
         for h in range(Hkv):
             np.testing.assert_array_equal(c["indices"][b][h], a["indices"][b][h])
+
+
+# ------------------------------------------------------------------ decoding on the compacted cache
+
+def test_decode_attention_matches_library_attention_on_ragged_heads():
+    rng = np.random.default_rng(71)
+    Hq, Hkv, D = 6, 3, 8
+    q = rng.standard_normal((Hq, D))
+    lens = [5, 1, 17]
+    Ks = [rng.standard_normal((n, D)) for n in lens]
+    Vs = [rng.standard_normal((n, D)) for n in lens]
+    out = O.decode_attention(q, Ks, Vs, 0.35)
+    for g in range(Hq):
+        h = g // 2
+        want = torch.nn.functional.scaled_dot_product_attention(
+            torch.from_numpy(q[g])[None, None], torch.from_numpy(Ks[h])[None], torch.from_numpy(Vs[h])[None], scale=0.35)
+        np.testing.assert_allclose(out[g], want[0, 0].numpy(), rtol=1e-12, atol=1e-14)
+        # and the definition with plain loops
+        lg = [0.35 * brute.dot(q[g].tolist(), k) for k in Ks[h].tolist()]
+        w = brute.softmax_row(lg)
+        ref = [sum(w[j] * Vs[h][j][d] for j in range(lens[h])) for d in range(D)]
+        np.testing.assert_allclose(out[g], ref, rtol=1e-12, atol=1e-14)
+
+
+def test_decode_attention_closed_forms():
+    rng = np.random.default_rng(72)
+    D = 6
+    q = rng.standard_normal((2, D))
+    V = rng.standard_normal((9, D))
+    same = np.tile(rng.standard_normal(D), (9, 1))
+    out = O.decode_attention(q, [same], [V], 1.0)             # equal logits: the plain mean of the values
+    np.testing.assert_allclose(out, np.tile(V.mean(axis=0), (2, 1)), rtol=1e-12)
+    K = rng.standard_normal((9, D))
+    K[4] = 50.0 * q[0] / np.linalg.norm(q[0])                 # one key far ahead for query 0: its value wins
+    out = O.decode_attention(q[:1], [K], [V], 1.0)
+    np.testing.assert_allclose(out[0], V[4], atol=1e-9)
+    out1 = O.decode_attention(q, [K[:1]], [V[:1]], 3.0)       # a single row: its value, whatever the logit
+    np.testing.assert_allclose(out1, np.tile(V[0], (2, 1)), rtol=1e-14)
