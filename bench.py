@@ -124,6 +124,9 @@ def main():
     ap.add_argument("--given-lse", action="store_true",
                     help="hand the window rows' log-sum-exp to the library, as a prefill attention kernel would "
                          "(the first pass then computes no logits); a variant, not the headline")
+    ap.add_argument("--decode-tail", type=int, default=-1,
+                    help="also time mixkv_decode_attention (one new token per layer over the cache just compacted "
+                         "plus this many appended rows); reported in an extra 'decode' object")
     ap.add_argument("--similarity-block", type=int, default=0,
                     help="also time mixkv_similarity (redundancy analysis of the keys: r and the heat-map at this "
                          "block size) on the same cache; reported in an extra 'similarity' object")
@@ -231,6 +234,31 @@ def main():
 
     units = wl.n_units
     e = 2 if wl.dtype == "bf16" else 4
+    dec = None
+    if args.decode_tail >= 0:
+        t = args.decode_tail
+        gen = torch.Generator(device=dev).manual_seed(7)
+        dt_ = B.TORCH_DTYPE[p.dtype]
+        qn = [(torch.randn((wl.batch, wl.n_q_heads, wl.head_dim), generator=gen, device=dev) * 0.3).to(dt_) for _ in layers]
+        tails = [(torch.randn((wl.batch, wl.n_kv_heads, max(t, 1), wl.head_dim), generator=gen, device=dev).to(dt_),
+                  torch.randn((wl.batch, wl.n_kv_heads, max(t, 1), wl.head_dim), generator=gen, device=dev).to(dt_))
+                 for _ in layers]
+        dout = [torch.empty_like(q) for q in qn]
+        dcall = B.PreparedDecode(p, outs, tails, qn, dout, t)
+        for _ in range(args.warmup):
+            dcall.run(stream)
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record(stream)
+        for _ in range(args.steps):
+            dcall.run(stream)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        dec_s = ev0.elapsed_time(ev1) * 1e-3 / args.steps
+        rows = units * (budget + t)                                              # rows read, K and V each
+        dec_bytes = rows * wl.head_dim * e * 2 + 2 * len(layers) * wl.batch * wl.n_q_heads * wl.head_dim * e
+        dec = {"tail_len": t, "us_per_call": dec_s * 1e6, "layers_per_call": len(layers), "algorithmic_bytes": dec_bytes,
+               "achieved_GBps": dec_bytes / dec_s / 1e9, "hbm_frac": dec_bytes / dec_s / HBM_PEAK,
+               "note": "same cache every call (it stays in the caches of the chip at this size)"}
     sim = None
     if args.similarity_block > 0:
         blk = args.similarity_block
@@ -284,6 +312,7 @@ def main():
                      "traffic": MEASURED_TRAFFIC.get((wl.name, wl.n_layers, dom)) if reads_v else None},
         "cpu_baseline": cpu,
         "similarity": sim,
+        "decode": dec,
         "parity_vs_oracle": parity,
         "host_gen_s": round(t_gen, 2),
     }

@@ -39,7 +39,7 @@
 extern "C" {
 #endif
 
-#define MIXKV_VERSION 5
+#define MIXKV_VERSION 6
 #define MIXKV_MAX_LAYERS 128      /* layers per call */
 #define MIXKV_MAX_WINDOW 64
 #define MIXKV_MAX_GROUP_ROWS 512  /* G * W */
@@ -222,6 +222,30 @@ mixkv_status mixkv_similarity_workspace_size(const mixkv_params *params, int32_t
 mixkv_status mixkv_similarity(const mixkv_params *params, const mixkv_rows_in *in, const mixkv_similarity_out *out,
                               int32_t n_layers, int32_t block, void *workspace, size_t workspace_bytes,
                               void *hip_stream);
+
+/*
+ * Attention of one new token over the compacted cache (Sec. 3.1: the compressed K, V are what the
+ * attention of the decoding phase reads).  Per layer, batch item and query head g (KV head
+ * h = g / G): out_g = sum_j softmax_j(softmax_scale * Q_g . k_j) v_j over the rows of head h: the
+ * counts[b][h] kept rows in K_cache / V_cache, laid out as mixkv_compress wrote them for
+ * params->budget_mode and params->budget (fixed: [batch, n_kv_heads, B, D]; otherwise packed
+ * [batch, n_kv_heads * B, D] with `offsets`), followed by the first tail_len rows of K_tail / V_tail
+ * ([batch, n_kv_heads, tail_capacity, D]: the rows appended since the compression, the new token's
+ * own row included; the caller's projection kernel writes them there).  fp32 accumulation; `out` has
+ * the dtype of the inputs (bf16: rounded to nearest even).  All pointers are DEVICE pointers, rows
+ * 16-byte aligned; K_tail / V_tail may be NULL when tail_len is 0, offsets when the layout is fixed.
+ * Needs no workspace.  counts / offsets are clamped to the capacity of the layout before use.
+ */
+typedef struct {
+  const void *K_cache, *V_cache;
+  const int32_t *counts;     /* [batch, n_kv_heads] */
+  const int32_t *offsets;    /* [batch, n_kv_heads + 1], packed layouts */
+  const void *K_tail, *V_tail;
+  const void *Q;             /* [batch, n_q_heads, D] the new token's queries */
+  void *out;                 /* [batch, n_q_heads, D] */
+} mixkv_decode_layer;
+mixkv_status mixkv_decode_attention(const mixkv_params *params, const mixkv_decode_layer *layers, int32_t n_layers,
+                                    int32_t tail_len, int32_t tail_capacity, void *hip_stream);
 
 const char *mixkv_status_string(mixkv_status status);
 int32_t mixkv_version(void);

@@ -57,6 +57,11 @@ class MixkvSimilarityOut(C.Structure):
     _fields_ = [("redundancy", C.c_void_p), ("block_map", C.c_void_p)]
 
 
+class MixkvDecodeLayer(C.Structure):
+    _fields_ = [("K_cache", C.c_void_p), ("V_cache", C.c_void_p), ("counts", C.c_void_p), ("offsets", C.c_void_p),
+                ("K_tail", C.c_void_p), ("V_tail", C.c_void_p), ("Q", C.c_void_p), ("out", C.c_void_p)]
+
+
 class MixkvError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -90,6 +95,8 @@ def lib() -> C.CDLL:
         L.mixkv_similarity.argtypes = [pp, C.POINTER(MixkvRowsIn), C.POINTER(MixkvSimilarityOut), C.c_int32, C.c_int32,
                                        C.c_void_p, C.c_size_t, C.c_void_p]
         L.mixkv_similarity.restype = C.c_int
+        L.mixkv_decode_attention.argtypes = [pp, C.POINTER(MixkvDecodeLayer), C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
+        L.mixkv_decode_attention.restype = C.c_int
         L.mixkv_stage_name.argtypes = [C.c_int32]
         L.mixkv_stage_name.restype = C.c_char_p
         L.mixkv_status_string.argtypes = [C.c_int]
@@ -266,6 +273,37 @@ def mixkv_similarity(p: MixkvParams, Xs, block: int, want_map: bool = True, work
         workspace = torch.empty(mixkv_similarity_workspace_size(p, len(Xs), block), dtype=torch.uint8, device=dev)
     PreparedSimilarity(p, Xs, red, maps, block, workspace).run(stream)
     return red, maps
+
+
+class PreparedDecode:
+    """The C argument array of one mixkv_decode_attention call, built once.
+
+    caches: per layer a LayerOut as filled by mixkv_compress; tails: per layer (K_tail, V_tail)
+    [batch, Hkv, tail_capacity, D] or None; Qs / outs: per layer [batch, Hq, D]."""
+
+    def __init__(self, p: MixkvParams, caches: Sequence[LayerOut], tails, Qs, outs, tail_len: int):
+        n = len(caches)
+        self.p, self.n, self.tail_len = p, n, tail_len
+        self.tail_cap = 0 if tails is None else tails[0][0].shape[2]
+        self.arr = (MixkvDecodeLayer * n)()
+        for i, c in enumerate(caches):
+            kt, vt = (None, None) if tails is None else tails[i]
+            assert Qs[i].is_contiguous() and outs[i].is_contiguous() and (kt is None or kt.is_contiguous())
+            self.arr[i] = MixkvDecodeLayer(_ptr(c.K_out), _ptr(c.V_out), _ptr(c.counts), _ptr(c.offsets), _ptr(kt), _ptr(vt),
+                                           _ptr(Qs[i]), _ptr(outs[i]))
+        self._keep = (caches, tails, Qs, outs)
+        self._L = lib()
+
+    def run(self, stream=None):
+        _check(self._L.mixkv_decode_attention(C.byref(self.p), self.arr, self.n, self.tail_len, self.tail_cap,
+                                              _stream(stream)), "mixkv_decode_attention")
+
+
+def mixkv_decode_attention(p: MixkvParams, caches, tails, Qs, tail_len: int, stream=None):
+    """Returns per layer the attention output [batch, Hq, D] of the new token (dtype of the inputs)."""
+    outs = [torch.empty_like(q) for q in Qs]
+    PreparedDecode(p, caches, tails, Qs, outs, tail_len).run(stream)
+    return outs
 
 
 class PreparedCall:

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmixkv.so")
-SOURCES = ["mixkv_api.hip", "mixkv_stream.hip", "mixkv_mixsel.hip", "mixkv_select.hip", "mixkv_analysis.hip"]
+SOURCES = ["mixkv_api.hip", "mixkv_stream.hip", "mixkv_mixsel.hip", "mixkv_select.hip", "mixkv_analysis.hip", "mixkv_decode.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

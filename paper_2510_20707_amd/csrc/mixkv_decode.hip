@@ -1,0 +1,233 @@
+// Attention of one new token over the compacted cache (paper Sec. 3.1: the compressed K, V are
+// what the attention of the decoding phase reads).  One workgroup per (layer, batch item, KV head,
+// group of up to eight query heads): the head's kept rows, then the rows appended since the
+// compression, are streamed once; every lane owns one 16-byte piece of a row slot and carries a
+// running softmax (maximum, sum, weighted value piece) per query head, so nothing crosses lanes
+// inside the loop except the dot-product reduction over the lanes of a row.
+#include "mixkv_internal.h"
+#include "mixkv_wave.h"
+
+namespace mixkv {
+
+struct DecodeLayer {
+  const void *Kc, *Vc;               // compacted rows as mixkv_compress wrote them
+  const int32_t *counts, *offsets;   // rows per head; first row of a head inside its batch item (packed layouts)
+  const void *Kt, *Vt;               // [batch, hkv, tail_cap, D] rows appended since
+  const void *Q;                     // [batch, hq, D]
+  void *out;                         // [batch, hq, D]
+};
+struct DecodeTable { DecodeLayer l[kLayersPerLaunch]; };
+
+struct DShape {
+  int32_t batch, hq, hkv, G, B, tail_len, tail_cap, packed, units_per_layer, gchunks;
+  float scale_log2e;
+};
+
+constexpr int kDecThreads = 512, kDecWaves = kDecThreads / 64, kDecHeads = 8;
+
+template <int DT>
+__device__ __forceinline__ void unpack16(const uint4 &q, float *x) {
+  if constexpr (DT == MIXKV_BF16) {
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      x[2 * j] = __uint_as_float(w[j] << 16);
+      x[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
+    }
+  } else {
+    x[0] = __uint_as_float(q.x); x[1] = __uint_as_float(q.y);
+    x[2] = __uint_as_float(q.z); x[3] = __uint_as_float(q.w);
+  }
+}
+
+__device__ __forceinline__ uint16_t bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+
+// GT: query heads carried per workgroup (1, 2, 4 or 8; heads past G are idle).
+template <int DT, int D, int GT>
+__global__ __launch_bounds__(kDecThreads) void decode_kernel(DShape s, DecodeTable tab) {
+  constexpr int EB = DT == MIXKV_BF16 ? 2 : 4, E = 16 / EB, PPR = D * EB / 16, RPL = 64 / PPR;
+  __shared__ float sm[kDecWaves][GT], sl[kDecWaves][GT], so[kDecWaves][GT][D];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lr = lane / PPR, piece = lane - lr * PPR;
+  const int ul = blockIdx.x / s.gchunks, gc = blockIdx.x - ul * s.gchunks;
+  const int layer = ul / s.units_per_layer, bh = ul - layer * s.units_per_layer;
+  const int b = bh / s.hkv, h = bh - b * s.hkv;
+  const DecodeLayer L = tab.l[layer];
+  const int g0 = gc * kDecHeads, ng = min(GT, s.G - g0);          // query heads of this workgroup
+
+  // rows of this head: `cnt` compacted ones, then `tail_len` appended ones
+  const int cap = s.packed ? s.hkv * s.B : s.B;                   // rows the head's slot can hold at most
+  int row0 = s.packed ? (L.offsets ? L.offsets[b * (s.hkv + 1) + h] : 0) : 0;
+  row0 = min(max(row0, 0), cap);
+  const int cnt = min(max(L.counts[bh], 0), cap - row0);          // the clamps only guard the loads
+  const int n = cnt + s.tail_len;
+  const int64_t slot_rows = s.packed ? (int64_t)b * s.hkv * s.B + row0 : (int64_t)bh * s.B;
+  const char *Kc = reinterpret_cast<const char *>(L.Kc) + slot_rows * D * EB;
+  const char *Vc = reinterpret_cast<const char *>(L.Vc) + slot_rows * D * EB;
+  const char *Kt = reinterpret_cast<const char *>(L.Kt) + (int64_t)bh * s.tail_cap * D * EB;
+  const char *Vt = reinterpret_cast<const char *>(L.Vt) + (int64_t)bh * s.tail_cap * D * EB;
+
+  // this lane's piece of every query row, already times softmax_scale * log2(e)
+  float q[GT][E];
+#pragma unroll
+  for (int g = 0; g < GT; ++g) {
+    const int gq = g < ng ? g0 + g : g0;
+    const uint4 v = *reinterpret_cast<const uint4 *>(reinterpret_cast<const char *>(L.Q) +
+                                                     ((int64_t)(b * s.hq + h * s.G + gq) * D) * EB + piece * 16);
+    unpack16<DT>(v, q[g]);
+#pragma unroll
+    for (int e = 0; e < E; ++e) q[g][e] *= s.scale_log2e;
+  }
+  float m[GT], l[GT], o[GT][E];
+#pragma unroll
+  for (int g = 0; g < GT; ++g) {
+    m[g] = -INFINITY; l[g] = 0.f;
+#pragma unroll
+    for (int e = 0; e < E; ++e) o[g][e] = 0.f;
+  }
+
+  auto row_ptrs = [&](int row, const char *&kp, const char *&vp) {
+    if (row < cnt) { kp = Kc + (int64_t)row * D * EB; vp = Vc + (int64_t)row * D * EB; }
+    else { kp = Kt + (int64_t)(row - cnt) * D * EB; vp = Vt + (int64_t)(row - cnt) * D * EB; }
+  };
+  constexpr int U = 4;                                             // row groups in flight per wave
+  for (int r = wave * RPL; r < n; r += kDecWaves * RPL * U) {
+    uint4 kq[U], vq[U];
+    bool ok[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int row = r + u * kDecWaves * RPL + lr;
+      ok[u] = row < n;
+      kq[u] = make_uint4(0u, 0u, 0u, 0u); vq[u] = kq[u];
+      if (ok[u]) {
+        const char *kp, *vp;
+        row_ptrs(row, kp, vp);
+        kq[u] = *reinterpret_cast<const uint4 *>(kp + piece * 16);
+        vq[u] = *reinterpret_cast<const uint4 *>(vp + piece * 16);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float x[E], v[E];
+      unpack16<DT>(kq[u], x);
+      unpack16<DT>(vq[u], v);
+#pragma unroll
+      for (int g = 0; g < GT; ++g) {
+        float part = 0.f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) part = fmaf(q[g][e], x[e], part);
+        const float dot = seg_sum<PPR>(part);                     // all lanes take part in the reduction
+        const float sc = ok[u] ? dot : -INFINITY;
+        const float mn = fmaxf(m[g], sc);
+        const float mu = mn == -INFINITY ? 0.f : mn;
+        const float f = __builtin_amdgcn_exp2f(m[g] - mu), p = __builtin_amdgcn_exp2f(sc - mu);
+        l[g] = fmaf(l[g], f, p);
+#pragma unroll
+        for (int e = 0; e < E; ++e) o[g][e] = fmaf(o[g][e], f, p * v[e]);
+        m[g] = mn;
+      }
+    }
+  }
+  // fold the row slots of the wave (lanes holding the same piece), then the waves through LDS
+#pragma unroll
+  for (int off = PPR; off < 64; off <<= 1) {
+#pragma unroll
+    for (int g = 0; g < GT; ++g) {
+      const float m2 = __shfl_xor(m[g], off), l2 = __shfl_xor(l[g], off);
+      const float mn = fmaxf(m[g], m2), mu = mn == -INFINITY ? 0.f : mn;
+      const float f1 = __builtin_amdgcn_exp2f(m[g] - mu), f2 = __builtin_amdgcn_exp2f(m2 - mu);
+      l[g] = l[g] * f1 + l2 * f2;
+#pragma unroll
+      for (int e = 0; e < E; ++e) o[g][e] = o[g][e] * f1 + __shfl_xor(o[g][e], off) * f2;
+      m[g] = mn;
+    }
+  }
+  if (lane < PPR) {
+#pragma unroll
+    for (int g = 0; g < GT; ++g) {
+      if (piece == 0) { sm[wave][g] = m[g]; sl[wave][g] = l[g]; }
+#pragma unroll
+      for (int e = 0; e < E; ++e) so[wave][g][piece * E + e] = o[g][e];
+    }
+  }
+  __syncthreads();
+  for (int idx = tid; idx < ng * D; idx += kDecThreads) {
+    const int g = idx / D, d = idx - g * D;
+    float mn = sm[0][g];
+#pragma unroll
+    for (int w = 1; w < kDecWaves; ++w) mn = fmaxf(mn, sm[w][g]);
+    const float mu = mn == -INFINITY ? 0.f : mn;
+    float acc = 0.f, tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < kDecWaves; ++w) {                          // waves in order
+      const float f = __builtin_amdgcn_exp2f(sm[w][g] - mu);
+      acc = fmaf(so[w][g][d], f, acc);
+      tot = fmaf(sl[w][g], f, tot);
+    }
+    const float res = tot > 0.f ? acc / tot : 0.f;
+    const int64_t at = (int64_t)(b * s.hq + h * s.G + g0 + g) * D + d;
+    if constexpr (DT == MIXKV_BF16) reinterpret_cast<uint16_t *>(L.out)[at] = bf16_rne(res);
+    else reinterpret_cast<float *>(L.out)[at] = res;
+  }
+}
+
+template <int DT, int D>
+static void launch_decode_g(const DShape &s, const DecodeTable &t, int nunits, int gt, hipStream_t st) {
+  const dim3 grid((unsigned)(nunits * s.gchunks)), block(kDecThreads);
+  switch (gt) {
+    case 1: hipLaunchKernelGGL((decode_kernel<DT, D, 1>), grid, block, 0, st, s, t); break;
+    case 2: hipLaunchKernelGGL((decode_kernel<DT, D, 2>), grid, block, 0, st, s, t); break;
+    case 4: hipLaunchKernelGGL((decode_kernel<DT, D, 4>), grid, block, 0, st, s, t); break;
+    default: hipLaunchKernelGGL((decode_kernel<DT, D, 8>), grid, block, 0, st, s, t); break;
+  }
+}
+
+}  // namespace mixkv
+
+extern "C" mixkv_status mixkv_decode_attention(const mixkv_params *params, const mixkv_decode_layer *layers,
+                                               int32_t n_layers, int32_t tail_len, int32_t tail_capacity,
+                                               void *hip_stream) {
+  using namespace mixkv;
+  Shape sh;
+  mixkv_status st = make_shape(params, &sh);
+  if (st != MIXKV_OK) return st;
+  if (!layers || n_layers < 1 || n_layers > MIXKV_MAX_LAYERS) return MIXKV_ERR_INVALID_ARG;
+  if (tail_len < 0 || tail_capacity < tail_len) return MIXKV_ERR_INVALID_ARG;
+  const bool packed = params->budget_mode != MIXKV_BUDGET_FIXED;
+  auto bad16 = [](const void *p) { return !p || (reinterpret_cast<uintptr_t>(p) & 15u); };
+  for (int l = 0; l < n_layers; ++l) {
+    const mixkv_decode_layer &d = layers[l];
+    if (bad16(d.K_cache) || bad16(d.V_cache) || bad16(d.Q) || bad16(d.out) || !d.counts) return MIXKV_ERR_INVALID_ARG;
+    if (packed && !d.offsets) return MIXKV_ERR_INVALID_ARG;
+    if (tail_len > 0 && (bad16(d.K_tail) || bad16(d.V_tail))) return MIXKV_ERR_INVALID_ARG;
+  }
+  DShape s;
+  s.batch = sh.batch; s.hq = sh.hq; s.hkv = sh.hkv; s.G = sh.G; s.B = sh.B;
+  s.tail_len = tail_len; s.tail_cap = tail_capacity; s.packed = packed; s.units_per_layer = sh.units_per_layer;
+  s.gchunks = (sh.G + kDecHeads - 1) / kDecHeads;
+  s.scale_log2e = sh.scale_log2e;
+  int gt = 1;
+  while (gt < sh.G && gt < kDecHeads) gt <<= 1;
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  for (int l0 = 0; l0 < n_layers; l0 += kLayersPerLaunch) {
+    const int nl = (n_layers - l0 < kLayersPerLaunch) ? n_layers - l0 : kLayersPerLaunch;
+    DecodeTable t;
+    for (int l = 0; l < kLayersPerLaunch; ++l) t.l[l] = DecodeLayer{};
+    for (int l = 0; l < nl; ++l) {
+      const mixkv_decode_layer &d = layers[l0 + l];
+      t.l[l] = DecodeLayer{d.K_cache, d.V_cache, d.counts, d.offsets, d.K_tail, d.V_tail, d.Q, d.out};
+    }
+    const int nunits = nl * sh.units_per_layer;
+    if (params->dtype == MIXKV_BF16) {
+      if (sh.D == 128) launch_decode_g<MIXKV_BF16, 128>(s, t, nunits, gt, stream);
+      else launch_decode_g<MIXKV_BF16, 64>(s, t, nunits, gt, stream);
+    } else {
+      if (sh.D == 128) launch_decode_g<MIXKV_F32, 128>(s, t, nunits, gt, stream);
+      else launch_decode_g<MIXKV_F32, 64>(s, t, nunits, gt, stream);
+    }
+    if (hipGetLastError() != hipSuccess) return MIXKV_ERR_HIP;
+  }
+  return MIXKV_OK;
+}

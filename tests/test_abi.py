@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
     L = B.lib()
     for n in set(names):
         assert hasattr(L, n), n
-    assert L.mixkv_version() == 5
+    assert L.mixkv_version() == 6
     assert B.status_string(0) == "ok" and "workspace" in B.status_string(3)
 
 

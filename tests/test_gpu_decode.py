@@ -1,0 +1,113 @@
+"""GPU parity of mixkv_decode_attention: the new token's attention over the cache that
+mixkv_compress just compacted (plus rows appended since), against the float64 oracle fed with the
+same rows.
+
+Tolerance, per output row (one query head): |gpu - ora| <= tol * max_d |ora_d| with tol = 1e-5 for
+fp32 inputs (fp32 accumulation over at most a few thousand rows) and 2^-8 + 1e-4 for bf16 inputs
+(the output is rounded to bf16, whose half ulp is up to 2^-8 of the element; 1e-4 covers the fp32
+sums in front of the rounding)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mixkv_oracle as O
+from paper_2510_20707_amd import binding as B
+from paper_2510_20707_amd import synth
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+WL = synth.WORKLOADS
+TOL = {"f32": 1e-5, "bf16": 2.0 ** -8 + 1e-4}
+
+
+def _quant(wl, a):
+    if wl.dtype == "bf16":
+        return (synth.round_to_bf16_bits(a.astype(np.float32)).astype(np.uint32) << 16).view(np.float32)
+    return a.astype(np.float32)
+
+
+def _decode_and_check(wl, layer_ids, tail_len, tail_cap=None, head_budgets=None, **over):
+    tail_cap = tail_len if tail_cap is None else tail_cap
+    print(f"[case] decode {wl.name} dtype={wl.dtype} D={wl.head_dim} Hq={wl.n_q_heads} Hkv={wl.n_kv_heads} "
+          f"B={over.get('budget', wl.budget)} mode={over.get('budget_mode', wl.budget_mode)} tail={tail_len}/{tail_cap} "
+          f"L={len(layer_ids)}", flush=True)
+    layers = [synth.make_layer(wl, l) for l in layer_ids]
+    p, caches = H.run_compress(wl, layers, head_budgets=head_budgets, **over)
+    Bt, Hq, Hkv, D, G = wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.group
+    rng = np.random.default_rng([81, wl.cfg_id, tail_len])
+    qs, kts, vts = [], [], []
+    for _ in layers:
+        qs.append(_quant(wl, rng.standard_normal((Bt, Hq, D)) / np.sqrt(D) * 4.0))
+        kts.append(_quant(wl, rng.standard_normal((Bt, Hkv, max(tail_cap, 1), D)) + 0.3))
+        vts.append(_quant(wl, rng.standard_normal((Bt, Hkv, max(tail_cap, 1), D))))
+    Qd = [H.to_device(wl, q) for q in qs]
+    tails = [(H.to_device(wl, k), H.to_device(wl, v)) for k, v in zip(kts, vts)] if tail_cap > 0 else None
+    outs = B.mixkv_decode_attention(p, caches, tails, Qd, tail_len)
+    torch.cuda.synchronize()
+    Bud = p.budget
+    worst = 0.0
+    for lay, c, q, kt, vt, o in zip(layers, caches, qs, kts, vts, outs):
+        got = o.float().cpu().numpy().astype(np.float64)
+        idx = c.indices.cpu().numpy().reshape(Bt, Hkv * Bud)
+        cnt, off = c.counts.cpu().numpy(), c.offsets.cpu().numpy()
+        for b in range(Bt):
+            Ks, Vs = [], []
+            for h in range(Hkv):
+                rows = idx[b, off[b, h]:off[b, h] + cnt[b, h]]
+                Ks.append(np.concatenate([_quant(wl, lay.K[b, h][rows]), kt[b, h, :tail_len]]))
+                Vs.append(np.concatenate([_quant(wl, lay.V[b, h][rows]), vt[b, h, :tail_len]]))
+            want = O.decode_attention(q[b], Ks, Vs, wl.softmax_scale)
+            for g in range(Hq):
+                err = np.abs(got[b, g] - want[g]).max() / np.abs(want[g]).max()
+                worst = max(worst, err)
+                assert err <= TOL[wl.dtype], f"b{b} g{g}: error {err:.2e}"
+    print(f"       max error {worst:.2e} of the row's largest element", flush=True)
+
+
+@pytest.mark.parametrize("tail_len", [0, 1, 5])
+def test_c1_f32(tail_len):
+    _decode_and_check(WL["c1"], [0], tail_len)
+
+
+@pytest.mark.parametrize("tail_len,tail_cap", [(0, 0), (1, 16), (13, 16)])
+def test_c2_bf16(tail_len, tail_cap):
+    _decode_and_check(WL["c2"], [0], tail_len, tail_cap)
+
+
+def test_packed_layouts_adaptive_and_per_head():
+    wl = WL["c2"].with_(name="adaptive-dec", seq_len=1024, text_suffix_start=960, batch=2, budget=96,
+                        budget_mode="adaptive", budget_floor=16, sigma=(0.1, 0.8))
+    _decode_and_check(wl, [0, 1], 3, 8)
+    wl = WL["c2"].with_(name="perhead-dec", seq_len=1024, text_suffix_start=960, batch=2)
+    hb = np.array([[32, 64, 500, 1024], [40, 41, 42, 43]], dtype=np.int32)
+    _decode_and_check(wl, [0, 1], 2, 4, head_budgets=hb, budget_mode="per_head", budget=405)
+
+
+@pytest.mark.parametrize("dtype,D,Hq,Hkv,B", [("f32", 64, 32, 2, 37), ("bf16", 64, 6, 2, 21), ("f32", 128, 3, 3, 100),
+                                              ("bf16", 128, 24, 2, 77)])
+def test_group_sizes_and_ragged_row_counts(dtype, D, Hq, Hkv, B):
+    # G = 16 and 12 take two workgroups per KV head; G = 3 pads to four query heads
+    wl = WL["c2"].with_(name="ragged-dec", dtype=dtype, head_dim=D, seq_len=300, window=5, n_q_heads=Hq, n_kv_heads=Hkv,
+                        budget=B, batch=2, text_prefix=16, text_suffix_start=260)
+    _decode_and_check(wl, [0], 7, 9)
+
+
+def test_c3_whole_cache_and_more_layers_than_one_launch_group():
+    _decode_and_check(WL["c3"], [0, 9, 27], 1, 4)
+    wl = WL["c1"].with_(n_layers=35)
+    _decode_and_check(wl, list(range(35)), 2, 2)
+
+
+def test_bad_arguments_are_rejected_before_any_launch():
+    wl = WL["c1"]
+    p, caches = H.run_compress(wl, [synth.make_layer(wl, 0)])
+    q = torch.zeros((wl.batch, wl.n_q_heads, wl.head_dim), device="cuda:0")
+    for tail_len, tails in ((1, None), (-1, None)):
+        with pytest.raises((B.MixkvError, AssertionError)) as e:
+            B.mixkv_decode_attention(p, caches, tails, [q], tail_len)
+        if isinstance(e.value, B.MixkvError):
+            assert e.value.status == B.MIXKV_ERR_INVALID_ARG
+    kt = torch.zeros((wl.batch, wl.n_kv_heads, 2, wl.head_dim), device="cuda:0")
+    with pytest.raises(B.MixkvError) as e:                       # more rows than the tail holds
+        B.mixkv_decode_attention(p, caches, [(kt, kt)], [q], 3)
+    assert e.value.status == B.MIXKV_ERR_INVALID_ARG
