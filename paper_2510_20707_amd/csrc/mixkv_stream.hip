@@ -274,8 +274,10 @@ __global__ __launch_bounds__(WAVES * 64, stats_waves_per_simd(DT, D, WAVES, TQ))
   const int N = s.N, Nc = s.Nc, QTR = s.QT * 32;
   const float c2 = s.scale_log2e;
   const int free_limit = s.causal ? Nc : N - 1;      // keys <= this are visible to every row
-  const int nq = max(0, min(TQ, s.QT - wave * TQ));  // query tiles this wave owns
+  const int nq = GIVEN_LSE ? 0 : max(0, min(TQ, s.QT - wave * TQ));  // query tiles this wave owns
   const bool use_v = s.intrinsic == MIXKV_INTRINSIC_VNORM;
+  // Waves without a query tile (the workgroup has more tile slots than the head has tiles, or the
+  // normalisers are given) run no matrix or softmax work.
   const uint32_t kring_a = lds_base_of(kring), vring_a = lds_base_of(vring);
   const int64_t T = (int64_t)nunits * s.nchunks;
   int64_t item = wg_first_item(blockIdx.x, gridDim.x, T);
@@ -352,7 +354,7 @@ __global__ __launch_bounds__(WAVES * 64, stats_waves_per_simd(DT, D, WAVES, TQ))
 
       // ---- softmax statistics of all TQ tiles; the MFMA chains are independent
       f32x16 acc[TQ];
-      if constexpr (!GIVEN_LSE) {
+      if (nq > 0) {
         Frag kf[NCHK];
 #pragma unroll
         for (int c = 0; c < NCHK; ++c) kf[c].q = read_key_frag<DT, D>(img, 0, c, l32, half);
@@ -400,7 +402,7 @@ __global__ __launch_bounds__(WAVES * 64, stats_waves_per_simd(DT, D, WAVES, TQ))
         }
       }
 
-      if (!GIVEN_LSE && tb + 31 > free_limit) {    // tile reaches into the window or past N: mask
+      if (nq > 0 && tb + 31 > free_limit) {        // tile reaches into the window or past N: mask
 #pragma unroll
         for (int q = 0; q < TQ; ++q)
 #pragma unroll
@@ -410,7 +412,8 @@ __global__ __launch_bounds__(WAVES * 64, stats_waves_per_simd(DT, D, WAVES, TQ))
           }
       }
 #pragma unroll
-      for (int q = 0; q < (GIVEN_LSE ? 0 : TQ); ++q) {
+      for (int q = 0; q < TQ; ++q) {
+        if (nq == 0) break;                               // wave-uniform: this wave has no query tile
         float tmax = fmaxf(acc[q][0], acc[q][1]);
 #pragma unroll
         for (int i = 2; i < 16; i += 2) tmax = fmaxf(fmaxf(tmax, acc[q][i]), acc[q][i + 1]);
