@@ -124,3 +124,19 @@ def test_similarity_workspace_and_block_limits():
     ins[0] = B.MixkvRowsIn(0x2000, 0, 0, 128)
     assert L.mixkv_similarity(C.byref(p), ins, outs, 1, 64, fake, 1 << 40, None) == B.MIXKV_ERR_INVALID_ARG   # no output
     assert L.mixkv_similarity(C.byref(p), None, outs, 1, 64, fake, 1 << 40, None) == B.MIXKV_ERR_INVALID_ARG
+
+
+def test_header_is_plain_c_and_the_library_links_from_c(tmp_path):
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = os.path.join(ROOT, "tests", "c", "abi_host_check.c")
+    exe = str(tmp_path / "abi_host_check")
+    libdir = os.path.dirname(B.LIB_PATH)
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), src,
+                    "-o", exe, "-L", libdir, "-l:libmixkv.so", f"-Wl,-rpath,{libdir}",
+                    "-Wl,-rpath,/opt/rocm/lib", "-Wl,--allow-shlib-undefined"], check=True)
+    r = subprocess.run([exe], capture_output=True, text=True)
+    assert r.returncode == 0 and r.stdout.startswith("ok ok"), (r.returncode, r.stdout, r.stderr)
