@@ -311,3 +311,11 @@ def test_given_lse_must_cover_every_layer_of_a_call():
     with pytest.raises(B.MixkvError) as e:
         B.mixkv_compress(p, Ks, Vs, Qs, outs, ws, window_lse=[lse0, None])
     assert e.value.status == B.MIXKV_ERR_INVALID_ARG
+
+
+def test_very_long_video_cache_128k_tokens():
+    # 256 frames of 510 tokens: beyond the fused mix kernel (plain mix, select and gather kernels),
+    # 1024 chunks per head in the streaming kernels; oracle on one head
+    wl = WL["c5"].with_(name="video-128k", batch=1, seq_len=64 + 256 * 510 + 64, text_suffix_start=64 + 256 * 510,
+                        n_frames=256, budget_mode="fixed", budget=256)
+    _run_and_check(wl, layer_ids=[0], units=[(0, 2)])
