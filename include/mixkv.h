@@ -39,7 +39,7 @@
 extern "C" {
 #endif
 
-#define MIXKV_VERSION 6
+#define MIXKV_VERSION 7
 #define MIXKV_MAX_LAYERS 128      /* layers per call */
 #define MIXKV_MAX_WINDOW 64
 #define MIXKV_MAX_GROUP_ROWS 512  /* G * W */
@@ -234,7 +234,11 @@ mixkv_status mixkv_similarity(const mixkv_params *params, const mixkv_rows_in *i
  * own row included; the caller's projection kernel writes them there).  fp32 accumulation; `out` has
  * the dtype of the inputs (bf16: rounded to nearest even).  All pointers are DEVICE pointers, rows
  * 16-byte aligned; K_tail / V_tail may be NULL when tail_len is 0, offsets when the layout is fixed.
- * Needs no workspace.  counts / offsets are clamped to the capacity of the layout before use.
+ * counts / offsets are clamped to the capacity of the layout before use.
+ * Workspace: long caches (more than 384 rows per head at params->budget + tail_len) are split over
+ * several workgroups per head whose partial results pass through `workspace`:
+ * mixkv_decode_workspace_size bytes (0 for short caches, then NULL is accepted), 256-byte aligned,
+ * no initialisation.
  */
 typedef struct {
   const void *K_cache, *V_cache;
@@ -244,8 +248,10 @@ typedef struct {
   const void *Q;             /* [batch, n_q_heads, D] the new token's queries */
   void *out;                 /* [batch, n_q_heads, D] */
 } mixkv_decode_layer;
+mixkv_status mixkv_decode_workspace_size(const mixkv_params *params, int32_t n_layers, int32_t tail_len, size_t *bytes);
 mixkv_status mixkv_decode_attention(const mixkv_params *params, const mixkv_decode_layer *layers, int32_t n_layers,
-                                    int32_t tail_len, int32_t tail_capacity, void *hip_stream);
+                                    int32_t tail_len, int32_t tail_capacity, void *workspace, size_t workspace_bytes,
+                                    void *hip_stream);
 
 const char *mixkv_status_string(mixkv_status status);
 int32_t mixkv_version(void);

@@ -95,8 +95,11 @@ def lib() -> C.CDLL:
         L.mixkv_similarity.argtypes = [pp, C.POINTER(MixkvRowsIn), C.POINTER(MixkvSimilarityOut), C.c_int32, C.c_int32,
                                        C.c_void_p, C.c_size_t, C.c_void_p]
         L.mixkv_similarity.restype = C.c_int
-        L.mixkv_decode_attention.argtypes = [pp, C.POINTER(MixkvDecodeLayer), C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
+        L.mixkv_decode_attention.argtypes = [pp, C.POINTER(MixkvDecodeLayer), C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                             C.c_size_t, C.c_void_p]
         L.mixkv_decode_attention.restype = C.c_int
+        L.mixkv_decode_workspace_size.argtypes = [pp, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
+        L.mixkv_decode_workspace_size.restype = C.c_int
         L.mixkv_stage_name.argtypes = [C.c_int32]
         L.mixkv_stage_name.restype = C.c_char_p
         L.mixkv_status_string.argtypes = [C.c_int]
@@ -281,8 +284,13 @@ class PreparedDecode:
     caches: per layer a LayerOut as filled by mixkv_compress; tails: per layer (K_tail, V_tail)
     [batch, Hkv, tail_capacity, D] or None; Qs / outs: per layer [batch, Hq, D]."""
 
-    def __init__(self, p: MixkvParams, caches: Sequence[LayerOut], tails, Qs, outs, tail_len: int):
+    def __init__(self, p: MixkvParams, caches: Sequence[LayerOut], tails, Qs, outs, tail_len: int, workspace="alloc"):
         n = len(caches)
+        if isinstance(workspace, str):                # allocate what the shape needs (possibly nothing)
+            need = mixkv_decode_workspace_size(p, n, tail_len)
+            workspace = torch.empty(need, dtype=torch.uint8, device=Qs[0].device) if need else None
+        self.wp, self.wb = _ws(workspace)
+        self._ws_keep = workspace
         self.p, self.n, self.tail_len = p, n, tail_len
         self.tail_cap = 0 if tails is None else tails[0][0].shape[2]
         self.arr = (MixkvDecodeLayer * n)()
@@ -296,13 +304,19 @@ class PreparedDecode:
 
     def run(self, stream=None):
         _check(self._L.mixkv_decode_attention(C.byref(self.p), self.arr, self.n, self.tail_len, self.tail_cap,
-                                              _stream(stream)), "mixkv_decode_attention")
+                                              self.wp, self.wb, _stream(stream)), "mixkv_decode_attention")
 
 
-def mixkv_decode_attention(p: MixkvParams, caches, tails, Qs, tail_len: int, stream=None):
+def mixkv_decode_workspace_size(p: MixkvParams, n_layers: int, tail_len: int) -> int:
+    n = C.c_size_t(0)
+    _check(lib().mixkv_decode_workspace_size(C.byref(p), n_layers, tail_len, C.byref(n)), "mixkv_decode_workspace_size")
+    return n.value
+
+
+def mixkv_decode_attention(p: MixkvParams, caches, tails, Qs, tail_len: int, stream=None, workspace="alloc"):
     """Returns per layer the attention output [batch, Hq, D] of the new token (dtype of the inputs)."""
     outs = [torch.empty_like(q) for q in Qs]
-    PreparedDecode(p, caches, tails, Qs, outs, tail_len).run(stream)
+    PreparedDecode(p, caches, tails, Qs, outs, tail_len, workspace).run(stream)
     return outs
 
 

@@ -3,7 +3,9 @@
 // group of up to eight query heads): the head's kept rows, then the rows appended since the
 // compression, are streamed once; every lane owns one 16-byte piece of a row slot and carries a
 // running softmax (maximum, sum, weighted value piece) per query head, so nothing crosses lanes
-// inside the loop except the dot-product reduction over the lanes of a row.
+// inside the loop except the dot-product reduction over the lanes of a row.  Long caches are
+// split over several workgroups per head (contiguous row ranges); each leaves its running softmax
+// in the workspace and decode_merge_kernel folds them in order.
 #include "mixkv_internal.h"
 #include "mixkv_wave.h"
 
@@ -19,7 +21,7 @@ struct DecodeLayer {
 struct DecodeTable { DecodeLayer l[kLayersPerLaunch]; };
 
 struct DShape {
-  int32_t batch, hq, hkv, G, B, tail_len, tail_cap, packed, units_per_layer, gchunks;
+  int32_t batch, hq, hkv, G, B, tail_len, tail_cap, packed, units_per_layer, gchunks, nsplit;
   float scale_log2e;
 };
 
@@ -47,11 +49,12 @@ __device__ __forceinline__ uint16_t bf16_rne(float f) {
 
 // GT: query heads carried per workgroup (1, 2, 4 or 8; heads past G are idle).
 template <int DT, int D, int GT>
-__global__ __launch_bounds__(kDecThreads) void decode_kernel(DShape s, DecodeTable tab) {
+__global__ __launch_bounds__(kDecThreads) void decode_kernel(DShape s, DecodeTable tab, float *part) {
   constexpr int EB = DT == MIXKV_BF16 ? 2 : 4, E = 16 / EB, PPR = D * EB / 16, RPL = 64 / PPR;
   __shared__ float sm[kDecWaves][GT], sl[kDecWaves][GT], so[kDecWaves][GT][D];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lr = lane / PPR, piece = lane - lr * PPR;
-  const int ul = blockIdx.x / s.gchunks, gc = blockIdx.x - ul * s.gchunks;
+  const int sp = blockIdx.x % s.nsplit, ugc = blockIdx.x / s.nsplit;   // row split, (unit, query-head group)
+  const int ul = ugc / s.gchunks, gc = ugc - ul * s.gchunks;
   const int layer = ul / s.units_per_layer, bh = ul - layer * s.units_per_layer;
   const int b = bh / s.hkv, h = bh - b * s.hkv;
   const DecodeLayer L = tab.l[layer];
@@ -62,7 +65,8 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DShape s, DecodeTab
   int row0 = s.packed ? (L.offsets ? L.offsets[b * (s.hkv + 1) + h] : 0) : 0;
   row0 = min(max(row0, 0), cap);
   const int cnt = min(max(L.counts[bh], 0), cap - row0);          // the clamps only guard the loads
-  const int n = cnt + s.tail_len;
+  const int n_all = cnt + s.tail_len;
+  const int r_begin = (int)((int64_t)n_all * sp / s.nsplit), n = (int)((int64_t)n_all * (sp + 1) / s.nsplit);   // rows [r_begin, n)
   const int64_t slot_rows = s.packed ? (int64_t)b * s.hkv * s.B + row0 : (int64_t)bh * s.B;
   const char *Kc = reinterpret_cast<const char *>(L.Kc) + slot_rows * D * EB;
   const char *Vc = reinterpret_cast<const char *>(L.Vc) + slot_rows * D * EB;
@@ -93,7 +97,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DShape s, DecodeTab
     else { kp = Kt + (int64_t)(row - cnt) * D * EB; vp = Vt + (int64_t)(row - cnt) * D * EB; }
   };
   constexpr int U = 4;                                             // row groups in flight per wave
-  for (int r = wave * RPL; r < n; r += kDecWaves * RPL * U) {
+  for (int r = r_begin + wave * RPL; r < n; r += kDecWaves * RPL * U) {
     uint4 kq[U], vq[U];
     bool ok[U];
 #pragma unroll
@@ -120,13 +124,20 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DShape s, DecodeTab
         for (int e = 0; e < E; ++e) part = fmaf(q[g][e], x[e], part);
         const float dot = seg_sum<PPR>(part);                     // all lanes take part in the reduction
         const float sc = ok[u] ? dot : -INFINITY;
-        const float mn = fmaxf(m[g], sc);
-        const float mu = mn == -INFINITY ? 0.f : mn;
-        const float f = __builtin_amdgcn_exp2f(m[g] - mu), p = __builtin_amdgcn_exp2f(sc - mu);
-        l[g] = fmaf(l[g], f, p);
+        // the running maximum moves (and the sums are rescaled) only in the steps where some row
+        // slot of the wave sees a new one
+        if (__builtin_amdgcn_ballot_w64(sc > m[g]) != 0) {
+          const float mn = fmaxf(m[g], sc);
+          const float f = __builtin_amdgcn_exp2f(m[g] - (mn == -INFINITY ? 0.f : mn));
+          l[g] *= f;
 #pragma unroll
-        for (int e = 0; e < E; ++e) o[g][e] = fmaf(o[g][e], f, p * v[e]);
-        m[g] = mn;
+          for (int e = 0; e < E; ++e) o[g][e] *= f;
+          m[g] = mn;
+        }
+        const float p = __builtin_amdgcn_exp2f(sc - (m[g] == -INFINITY ? 0.f : m[g]));
+        l[g] += p;
+#pragma unroll
+        for (int e = 0; e < E; ++e) o[g][e] = fmaf(p, v[e], o[g][e]);
       }
     }
   }
@@ -166,6 +177,12 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DShape s, DecodeTab
       acc = fmaf(so[w][g][d], f, acc);
       tot = fmaf(sl[w][g], f, tot);
     }
+    if (s.nsplit > 1) {                                            // partial: weighted values, then (max, sum)
+      float *dst = part + ((int64_t)blockIdx.x * GT + g) * (D + 2);
+      dst[d] = acc;
+      if (d == 0) { dst[D] = mn; dst[D + 1] = tot; }
+      continue;
+    }
     const float res = tot > 0.f ? acc / tot : 0.f;
     const int64_t at = (int64_t)(b * s.hq + h * s.G + g0 + g) * D + d;
     if constexpr (DT == MIXKV_BF16) reinterpret_cast<uint16_t *>(L.out)[at] = bf16_rne(res);
@@ -173,28 +190,97 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DShape s, DecodeTab
   }
 }
 
-template <int DT, int D>
-static void launch_decode_g(const DShape &s, const DecodeTable &t, int nunits, int gt, hipStream_t st) {
-  const dim3 grid((unsigned)(nunits * s.gchunks)), block(kDecThreads);
-  switch (gt) {
-    case 1: hipLaunchKernelGGL((decode_kernel<DT, D, 1>), grid, block, 0, st, s, t); break;
-    case 2: hipLaunchKernelGGL((decode_kernel<DT, D, 2>), grid, block, 0, st, s, t); break;
-    case 4: hipLaunchKernelGGL((decode_kernel<DT, D, 4>), grid, block, 0, st, s, t); break;
-    default: hipLaunchKernelGGL((decode_kernel<DT, D, 8>), grid, block, 0, st, s, t); break;
+// Folds the nsplit partial results of one (unit, query-head group) in split order and writes the output rows.
+template <int DT, int D, int GT>
+__global__ __launch_bounds__(256) void decode_merge_kernel(DShape s, DecodeTable tab, const float *part) {
+  const int ugc = blockIdx.x, ul = ugc / s.gchunks, gc = ugc - ul * s.gchunks;
+  const int layer = ul / s.units_per_layer, bh = ul - layer * s.units_per_layer;
+  const int b = bh / s.hkv, h = bh - b * s.hkv;
+  const int g0 = gc * kDecHeads, ng = min(GT, s.G - g0);
+  void *out = tab.l[layer].out;
+  for (int idx = threadIdx.x; idx < ng * D; idx += 256) {
+    const int g = idx / D, d = idx - g * D;
+    const float *src = part + ((int64_t)ugc * s.nsplit * GT + g) * (D + 2);
+    const int64_t step = (int64_t)GT * (D + 2);                    // from one split to the next
+    float mn = -INFINITY;
+    for (int sp = 0; sp < s.nsplit; ++sp) mn = fmaxf(mn, src[sp * step + D]);
+    const float mu = mn == -INFINITY ? 0.f : mn;
+    float acc = 0.f, tot = 0.f;
+    for (int sp = 0; sp < s.nsplit; ++sp) {
+      const float f = __builtin_amdgcn_exp2f(src[sp * step + D] - mu);
+      acc = fmaf(src[sp * step + d], f, acc);
+      tot = fmaf(src[sp * step + D + 1], f, tot);
+    }
+    const float res = tot > 0.f ? acc / tot : 0.f;
+    const int64_t at = (int64_t)(b * s.hq + h * s.G + g0 + g) * D + d;
+    if constexpr (DT == MIXKV_BF16) reinterpret_cast<uint16_t *>(out)[at] = bf16_rne(res);
+    else reinterpret_cast<float *>(out)[at] = res;
   }
+}
+
+template <int DT, int D, int GT>
+static void launch_decode_gt(const DShape &s, const DecodeTable &t, int nunits, float *part, hipStream_t st) {
+  const dim3 grid((unsigned)(nunits * s.gchunks * s.nsplit)), block(kDecThreads);
+  hipLaunchKernelGGL((decode_kernel<DT, D, GT>), grid, block, 0, st, s, t, part);
+  if (s.nsplit > 1)
+    hipLaunchKernelGGL((decode_merge_kernel<DT, D, GT>), dim3((unsigned)(nunits * s.gchunks)), dim3(256), 0, st, s, t, part);
+}
+
+template <int DT, int D>
+static void launch_decode_g(const DShape &s, const DecodeTable &t, int nunits, int gt, float *part, hipStream_t st) {
+  switch (gt) {
+    case 1: launch_decode_gt<DT, D, 1>(s, t, nunits, part, st); break;
+    case 2: launch_decode_gt<DT, D, 2>(s, t, nunits, part, st); break;
+    case 4: launch_decode_gt<DT, D, 4>(s, t, nunits, part, st); break;
+    default: launch_decode_gt<DT, D, 8>(s, t, nunits, part, st); break;
+  }
+}
+
+// Query heads carried per workgroup and row splits per head for a shape.
+static void decode_config(const Shape &sh, int tail_len, int *gt, int *gchunks, int *nsplit) {
+  *gt = 1;
+  while (*gt < sh.G && *gt < kDecHeads) *gt <<= 1;
+  *gchunks = (sh.G + kDecHeads - 1) / kDecHeads;
+  const int rows = sh.B + tail_len;                     // per head, on average in the packed layouts
+  int ns = (rows + 383) / 384;
+  *nsplit = ns < 1 ? 1 : (ns > 16 ? 16 : ns);
+}
+static size_t decode_part_bytes(const Shape &sh, int n_layers, int gt, int gchunks, int nsplit) {
+  if (nsplit == 1) return 0;
+  return (size_t)n_layers * sh.units_per_layer * gchunks * nsplit * gt * (sh.D + 2) * sizeof(float);
 }
 
 }  // namespace mixkv
 
+extern "C" mixkv_status mixkv_decode_workspace_size(const mixkv_params *params, int32_t n_layers, int32_t tail_len,
+                                                    size_t *bytes) {
+  using namespace mixkv;
+  Shape sh;
+  mixkv_status st = make_shape(params, &sh);
+  if (st != MIXKV_OK) return st;
+  if (!bytes || n_layers < 1 || n_layers > MIXKV_MAX_LAYERS || tail_len < 0) return MIXKV_ERR_INVALID_ARG;
+  int gt, gchunks, nsplit;
+  decode_config(sh, tail_len, &gt, &gchunks, &nsplit);
+  *bytes = (decode_part_bytes(sh, n_layers, gt, gchunks, nsplit) + 255) / 256 * 256;
+  return MIXKV_OK;
+}
+
 extern "C" mixkv_status mixkv_decode_attention(const mixkv_params *params, const mixkv_decode_layer *layers,
                                                int32_t n_layers, int32_t tail_len, int32_t tail_capacity,
-                                               void *hip_stream) {
+                                               void *workspace, size_t workspace_bytes, void *hip_stream) {
   using namespace mixkv;
   Shape sh;
   mixkv_status st = make_shape(params, &sh);
   if (st != MIXKV_OK) return st;
   if (!layers || n_layers < 1 || n_layers > MIXKV_MAX_LAYERS) return MIXKV_ERR_INVALID_ARG;
   if (tail_len < 0 || tail_capacity < tail_len) return MIXKV_ERR_INVALID_ARG;
+  int gt, gchunks, nsplit;
+  decode_config(sh, tail_len, &gt, &gchunks, &nsplit);
+  const size_t need = decode_part_bytes(sh, n_layers, gt, gchunks, nsplit);
+  if (need > 0) {
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return MIXKV_ERR_INVALID_ARG;
+    if (workspace_bytes < need) return MIXKV_ERR_WORKSPACE_TOO_SMALL;
+  }
   const bool packed = params->budget_mode != MIXKV_BUDGET_FIXED;
   auto bad16 = [](const void *p) { return !p || (reinterpret_cast<uintptr_t>(p) & 15u); };
   for (int l = 0; l < n_layers; ++l) {
@@ -206,10 +292,8 @@ extern "C" mixkv_status mixkv_decode_attention(const mixkv_params *params, const
   DShape s;
   s.batch = sh.batch; s.hq = sh.hq; s.hkv = sh.hkv; s.G = sh.G; s.B = sh.B;
   s.tail_len = tail_len; s.tail_cap = tail_capacity; s.packed = packed; s.units_per_layer = sh.units_per_layer;
-  s.gchunks = (sh.G + kDecHeads - 1) / kDecHeads;
+  s.gchunks = gchunks; s.nsplit = nsplit;
   s.scale_log2e = sh.scale_log2e;
-  int gt = 1;
-  while (gt < sh.G && gt < kDecHeads) gt <<= 1;
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
   for (int l0 = 0; l0 < n_layers; l0 += kLayersPerLaunch) {
     const int nl = (n_layers - l0 < kLayersPerLaunch) ? n_layers - l0 : kLayersPerLaunch;
@@ -220,12 +304,16 @@ extern "C" mixkv_status mixkv_decode_attention(const mixkv_params *params, const
       t.l[l] = DecodeLayer{d.K_cache, d.V_cache, d.counts, d.offsets, d.K_tail, d.V_tail, d.Q, d.out};
     }
     const int nunits = nl * sh.units_per_layer;
+    // this launch group's partials
+    float *part = need > 0 ? reinterpret_cast<float *>(workspace) +
+                                 (size_t)l0 * sh.units_per_layer * gchunks * nsplit * gt * (sh.D + 2)
+                           : nullptr;
     if (params->dtype == MIXKV_BF16) {
-      if (sh.D == 128) launch_decode_g<MIXKV_BF16, 128>(s, t, nunits, gt, stream);
-      else launch_decode_g<MIXKV_BF16, 64>(s, t, nunits, gt, stream);
+      if (sh.D == 128) launch_decode_g<MIXKV_BF16, 128>(s, t, nunits, gt, part, stream);
+      else launch_decode_g<MIXKV_BF16, 64>(s, t, nunits, gt, part, stream);
     } else {
-      if (sh.D == 128) launch_decode_g<MIXKV_F32, 128>(s, t, nunits, gt, stream);
-      else launch_decode_g<MIXKV_F32, 64>(s, t, nunits, gt, stream);
+      if (sh.D == 128) launch_decode_g<MIXKV_F32, 128>(s, t, nunits, gt, part, stream);
+      else launch_decode_g<MIXKV_F32, 64>(s, t, nunits, gt, part, stream);
     }
     if (hipGetLastError() != hipSuccess) return MIXKV_ERR_HIP;
   }

@@ -24,7 +24,11 @@ int main(void) {
   /* NULL arguments are rejected before anything touches a GPU */
   p.head_dim = 128;
   if (mixkv_compress(&p, NULL, NULL, 1, NULL, 0, NULL) != MIXKV_ERR_INVALID_ARG) return 7;
-  if (mixkv_decode_attention(&p, NULL, 1, 0, 0, NULL) != MIXKV_ERR_INVALID_ARG) return 8;
+  if (mixkv_decode_attention(&p, NULL, 1, 0, 0, NULL, 0, NULL) != MIXKV_ERR_INVALID_ARG) return 8;
+  if (mixkv_decode_workspace_size(&p, 1, 0, &sim) != MIXKV_OK || sim != 0) return 10;      /* 64 rows: no split */
+  p.budget = 2048;
+  if (mixkv_decode_workspace_size(&p, 1, 16, &sim) != MIXKV_OK || sim == 0) return 11;
+  p.budget = 64;
   if (mixkv_similarity(&p, NULL, NULL, 1, 64, NULL, 0, NULL) != MIXKV_ERR_INVALID_ARG) return 9;
   printf("ok %s %zu %zu\n", mixkv_status_string(MIXKV_OK), one, sim);
   return 0;

@@ -98,6 +98,30 @@ def test_c3_whole_cache_and_more_layers_than_one_launch_group():
     _decode_and_check(wl, list(range(35)), 2, 2)
 
 
+def test_long_caches_are_split_over_workgroups():
+    # 1024 + 7 rows per head: three row ranges per head, merged in order; a per-head table with one very long head
+    _decode_and_check(WL["c2"], [0], 7, 8, budget=1024)
+    wl = WL["c2"].with_(name="perhead-long", batch=2)
+    hb = np.array([[32, 40, 3000, 500]], dtype=np.int32)
+    _decode_and_check(wl, [0], 2, 4, head_budgets=hb, budget_mode="per_head", budget=900)
+    wl = WL["c1"].with_(n_layers=34)
+    _decode_and_check(wl, list(range(34)), 3, 4, budget=500)          # f32, two launch groups of partials
+
+
+def test_split_needs_its_workspace():
+    wl = WL["c2"]
+    p, caches = H.run_compress(wl, [synth.make_layer(wl, 0)], budget=1024)
+    q = torch.zeros((wl.batch, wl.n_q_heads, wl.head_dim), device="cuda:0", dtype=torch.bfloat16)
+    assert B.mixkv_decode_workspace_size(p, 1, 0) > 0
+    with pytest.raises(B.MixkvError) as e:
+        B.mixkv_decode_attention(p, caches, None, [q], 0, workspace=None)
+    assert e.value.status == B.MIXKV_ERR_INVALID_ARG
+    small = torch.empty(256, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(B.MixkvError) as e:
+        B.mixkv_decode_attention(p, caches, None, [q], 0, workspace=small)
+    assert e.value.status == B.MIXKV_ERR_WORKSPACE_TOO_SMALL
+
+
 def test_bad_arguments_are_rejected_before_any_launch():
     wl = WL["c1"]
     p, caches = H.run_compress(wl, [synth.make_layer(wl, 0)])
