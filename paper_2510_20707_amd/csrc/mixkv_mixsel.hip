@@ -303,7 +303,7 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
         for (int j = 0; j < BPT; ++j) {
           const int bi = kBins - 1 - (tid * BPT + j);
           const int c = bi >= 0 ? sc.hist[bi] : 0;
-          if (run < k && k <= run + c) { sc.bin = bi; sc.krem = k - run; }
+          if (run < k && k <= run + c) { sc.bin = bi; sc.krem = k - run; sc.cut = c; }
           run += c;
         }
       }
@@ -311,7 +311,11 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
       prefix |= (uint32_t)sc.bin << shift;
       k = sc.krem;
       undecided = shift;
+      const bool whole_bin = sc.cut == k && shift > 0 && prefix != 0;
       __syncthreads();
+      // Every key of the bin is needed: the kept set is "all keys at or above the bin", whatever
+      // the lower digits are, so the remaining rounds can be skipped.
+      if (whole_bin) { prefix -= 1; k = 0; break; }
     }
     const uint32_t tau = prefix;       // the B'-th largest key; k of the keys equal to it are still needed
     // one scan carries both counts: keys above tau (low half) and keys equal to tau (high half)
