@@ -21,7 +21,6 @@ constexpr int kDigit = 11, kBins = 1 << kDigit;     // radix-select digit
 struct MsScratch {
   float f[kMsMaxWaves][8];
   float fr[8];
-  uint32_t u[kMsMaxWaves][2];
   uint32_t ur[2];
   int i[kMsMaxWaves + 1];
   int hist[kBins];
@@ -54,18 +53,17 @@ __device__ __forceinline__ void block_reduce_mixed(float (&v)[NS + NMIN + NMAX],
   }
 }
 
-template <int NW>
+// Block-wide minimum and maximum of unsigned keys through two LDS atomics per wave (integer
+// min / max do not depend on the order).  sc.ur must hold {0xffffffff, 0} from before an earlier
+// barrier of the kernel.
 __device__ __forceinline__ void block_minmax_u32(uint32_t &lo, uint32_t &hi, MsScratch &sc) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
   lo = wave_reduce<WMin>(lo, 0xffffffffu);
   hi = wave_reduce<WMax>(hi, 0u);
+  if (lane == 0) { atomicMin(&sc.ur[0], lo); atomicMax(&sc.ur[1], hi); }
   __syncthreads();
-  if (lane == 0) { sc.u[wave][0] = lo; sc.u[wave][1] = hi; }
-  __syncthreads();
-  uint32_t a = (lane & 15) < NW ? sc.u[lane & 15][0] : 0xffffffffu;
-  uint32_t b = (lane & 15) < NW ? sc.u[lane & 15][1] : 0u;
-  lo = read_lane(row_scan_incl<WMin>(a, 0xffffffffu), 15);
-  hi = read_lane(row_scan_incl<WMax>(b, 0u), 15);
+  lo = sc.ur[0];
+  hi = sc.ur[1];
 }
 
 // Exclusive prefix sum of one int per thread (thread order); *total receives the block sum.
@@ -150,6 +148,7 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
   // The raw attention row goes to LDS with one pad word per 32 so that the strided accesses of
   // consecutive-range owners spread over the banks.
   auto slot = [](int i) { return i + (i >> 5); };
+  if (tid == 0) { sc.ur[0] = 0xffffffffu; sc.ur[1] = 0u; }   // for the key range, read after later barriers
 #pragma unroll
   for (int e = 0; e < EPT; ++e)
     if (base + e < Nc) a_s[slot(base + e)] = a[e];
@@ -271,7 +270,7 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
       key[e] = order_key_u(a[e]);
       if (base + e < Nc) { kmin = min(kmin, key[e]); kmax = max(kmax, key[e]); }
     }
-    block_minmax_u32<NW>(kmin, kmax, sc);
+    block_minmax_u32(kmin, kmax, sc);
     // bits at and above `undecided` are common to all keys; digits of up to kDigit bits from there down
     int undecided = kmin == kmax ? 0 : 32 - __clz((int)(kmin ^ kmax));
     uint32_t prefix = undecided >= 32 ? 0u : (kmax >> undecided) << undecided;
