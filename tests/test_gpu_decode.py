@@ -135,3 +135,11 @@ def test_bad_arguments_are_rejected_before_any_launch():
     with pytest.raises(B.MixkvError) as e:                       # more rows than the tail holds
         B.mixkv_decode_attention(p, caches, [(kt, kt)], [q], 3)
     assert e.value.status == B.MIXKV_ERR_INVALID_ARG
+
+
+def test_window_only_cache_and_single_row():
+    wl = WL["c1"]
+    _decode_and_check(wl, [0], 0, budget=wl.window)              # the cache holds the window rows only
+    _decode_and_check(wl, [0], 1, budget=wl.window)
+    tiny = WL["c1"].with_(name="tiny-dec", seq_len=2, window=1, budget=1, n_q_heads=1, n_kv_heads=1)
+    _decode_and_check(tiny, [0], 0)                              # one row: the output is that value row

@@ -99,3 +99,12 @@ def test_c3_sampled_heads_at_the_bench_configuration():
     wl = WL["c3"]
     layers = [synth.make_layer(wl, l) for l in (0, 27)]
     _check(wl, layers, "K", 256, units=[(0, 2)])
+
+
+def test_smallest_shapes():
+    wl = WL["c1"].with_(name="tiny-sim", seq_len=2, window=1, budget=1, n_q_heads=1, n_kv_heads=1, batch=1)
+    lay = synth.make_layer(wl, 0)
+    _check(wl, [lay], "K", 1)
+    _check(wl, [lay], "K", 2)
+    wl = WL["c1"].with_(name="tiny-sim3", seq_len=3, window=1, budget=2, n_q_heads=2, n_kv_heads=2, batch=3)
+    _check(wl, [synth.make_layer(wl, 0)], "V", 2)
