@@ -19,6 +19,7 @@
 // with b_r = max_r + log2(sum_r * G*W), so one fused multiply-add and one v_exp_f32 per element
 // give the weight already divided by the row sum and by the number of rows
 // (paper Sec. 3.2, extrinsic importance: mean over the window queries of the attention weights).
+#include <type_traits>
 #include "mixkv_internal.h"
 #include "mixkv_wave.h"
 
@@ -339,18 +340,26 @@ __global__ __launch_bounds__(WAVES * 64, stats_waves_per_simd(DT, D, WAVES, TQ))
 #pragma unroll
     for (int e = 0; e < EPC; ++e) ksacc[e] = 0.f;
 
-    for (int t = 0; t < nt; ++t) {
+    // One tile step.  The loop is unrolled over the ring, so the ring slot of a step (t mod kRing) is
+    // a constant and the LDS addresses of its reads are a loop-invariant lane offset plus an immediate.
+    auto tile_step = [&](auto slot_c, int t) {
+      constexpr int SLOT = decltype(slot_c)::value;
       __builtin_amdgcn_sched_barrier(0);
       if (use_v) wait_tile<2 * KL>(t, nt); else wait_tile<KL>(t, nt);
       lds_barrier();
 #ifndef MIXKV_NODMA   // developer switch: time the arithmetic alone (results are then meaningless)
-      if (t + kLead < nt) request(t + kLead);
+      if (t + kLead < nt) {                            // tile t + kLead goes into the image tile t - 1 has left
+        constexpr uint32_t off = (uint32_t)((SLOT + kLead) & (kRing - 1)) * (TILE * 16);
+        const int tbr = key0 + (t + kLead) * 32;
+        fetch_tile<DT, D, WAVES>(Kb, row_bytes, tbr, N, kring_a + off, wave, lane);
+        if (use_v) fetch_tile<DT, D, WAVES>(Vb, row_bytes, tbr, N, vring_a + off, wave, lane);
+      }
 #endif
       __builtin_amdgcn_sched_barrier(0);
 
       const int tb = key0 + t * 32;
-      const uint4 *img = kring + (t & (kRing - 1)) * TILE;
-      const uint4 *vimg = vring + (t & (kRing - 1)) * TILE;
+      const uint4 *img = kring + SLOT * TILE;
+      const uint4 *vimg = vring + SLOT * TILE;
 
       // ---- softmax statistics of all TQ tiles; the MFMA chains are independent
       f32x16 acc[TQ];
@@ -432,6 +441,13 @@ __global__ __launch_bounds__(WAVES * 64, stats_waves_per_simd(DT, D, WAVES, TQ))
         for (int i = 0; i < 16; ++i) sum[i & 3] += fast_exp2(fmaf(acc[q][i], c2, nmu));
         l[q] += (sum[0] + sum[1]) + (sum[2] + sum[3]);
       }
+    };
+    static_assert(kRing == 4, "unrolled four times below");
+    for (int t = 0; t < nt; t += kRing) {
+      tile_step(std::integral_constant<int, 0>{}, t);
+      if (t + 1 < nt) tile_step(std::integral_constant<int, 1>{}, t + 1);
+      if (t + 2 < nt) tile_step(std::integral_constant<int, 2>{}, t + 2);
+      if (t + 3 < nt) tile_step(std::integral_constant<int, 3>{}, t + 3);
     }
 
     // ---- run partials to global
@@ -620,6 +636,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
 #pragma unroll
     for (int j = 0; j <= kLead; ++j)
       if (j < nt) request(j);
+    static_assert(kLead + 1 == kRing && kRing % KT == 0, "the tile loop below is unrolled over the ring");
 
     // query tiles in fragment form (tiles past QT are zero, except for the two mean-key rows) and
     // the exponent offset of each of the lane's 16 rows per tile
@@ -664,20 +681,25 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
     // fragments of tile t are already in registers (kf), those of tile t + 1 are read into kfn
     // under this tile's arithmetic, and tile t + 1 + kLead is requested into the image of tile t,
     // which nobody reads any more.
-    auto step = [&](int t, Frag (&kf)[NCHK], Frag (&kfn)[NCHK]) {
+    // The loop is unrolled over the ring, so the ring slot of a step (t mod kRing) is a constant and
+    // the LDS addresses of its reads are a loop-invariant lane offset plus an immediate.
+    auto step = [&](auto slot_c, int t, Frag (&kf)[NCHK], Frag (&kfn)[NCHK]) {
+      constexpr int SLOT = decltype(slot_c)::value;
       __builtin_amdgcn_sched_barrier(0);
       wait_tile<KL>(t + 1, nt);
       lds_barrier();                                   // every wave holds the fragments of tile t: its image is free
 #ifndef MIXKV_NODMA   // developer switch: time the arithmetic alone (results are then meaningless)
-      if (t + 1 + kLead < nt) request(t + 1 + kLead);
+      if (t + 1 + kLead < nt)                          // tile t + kRing goes into the image of tile t
+        fetch_tile<DT, D, WAVES>(Kb, row_bytes, key0 + (t + 1 + kLead) * 32, N, kring_a + (uint32_t)SLOT * (TILE * 16), wave,
+                                 lane);
 #endif
       if (t + 1 < nt) {
-        const uint4 *imgn = kring + ((t + 1) & (kRing - 1)) * TILE;
+        const uint4 *imgn = kring + ((SLOT + 1) & (kRing - 1)) * TILE;
 #pragma unroll
         for (int c = 0; c < NCHK; ++c) kfn[c].q = read_key_frag<DT, D>(imgn, 0, c, l32, half);
       }
       __builtin_amdgcn_sched_barrier(0);
-      const int k = t % KT, g = t / KT;                // tile within its chunk, chunk within the run
+      const int k = SLOT % KT, g = t / KT;             // tile within its chunk, chunk within the run
       if (k == 0 && g > 0) flush_colsums(c0 + g - 1, (g - 1) & 1);
       float *cs = cs_s + ((g & 1) * WAVES + wave) * CH;
       const int tb = key0 + t * 32, key = tb + l32;
@@ -739,9 +761,11 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
     Frag kfa[NCHK], kfb[NCHK];
 #pragma unroll
     for (int c = 0; c < NCHK; ++c) kfa[c].q = read_key_frag<DT, D>(kring, 0, c, l32, half);   // tile 0
-    for (int t = 0; t < nt; t += 2) {
-      step(t, kfa, kfb);
-      if (t + 1 < nt) step(t + 1, kfb, kfa);
+    for (int t = 0; t < nt; t += kRing) {
+      step(std::integral_constant<int, 0>{}, t, kfa, kfb);
+      if (t + 1 < nt) step(std::integral_constant<int, 1>{}, t + 1, kfb, kfa);
+      if (t + 2 < nt) step(std::integral_constant<int, 2>{}, t + 2, kfa, kfb);
+      if (t + 3 < nt) step(std::integral_constant<int, 3>{}, t + 3, kfb, kfa);
     }
     lds_barrier();
     flush_colsums(c0 + (nt - 1) / KT, ((nt - 1) / KT) & 1);
