@@ -157,10 +157,11 @@ __device__ __forceinline__ int tile_swz(int r) {
 // the compiler does not make later reads of the ring wait for every load in flight - the waits are
 // placed by hand (wait_vm) where the data is needed.
 //
-// fetch_tile_clamped is the last tile of a sequence, kept out of line so that the common path stays
-// a scalar base plus a fixed lane offset.
+// `tile` points at row tb of the tensor (the callers keep it as a running scalar pointer, so the
+// common path is that pointer plus loop-invariant scalar and lane offsets and needs no vector
+// arithmetic).  fetch_tile_clamped is the last tile of a sequence, kept out of line.
 template <int DT, int D, int WAVES>
-__device__ __attribute__((noinline)) void fetch_tile_clamped(const char *Kb, int64_t row_bytes, int tb, int N, uint32_t img,
+__device__ __attribute__((noinline)) void fetch_tile_clamped(const char *tile, int64_t row_bytes, int tb, int N, uint32_t img,
                                                              int wave, int lane) {
   constexpr int PPR = D * Tr<DT>::EB / 16, LOADS = 32 * PPR / 64, RPL = 64 / PPR;
   const int lrow = lane / PPR, lq = lane % PPR;
@@ -168,14 +169,14 @@ __device__ __attribute__((noinline)) void fetch_tile_clamped(const char *Kb, int
   for (int jj = 0; jj < (LOADS + WAVES - 1) / WAVES; ++jj) {
     const int j = (jj * WAVES + wave) % LOADS;
     const int row = j * RPL + lrow;
-    const int krow = min(tb + row, N - 1);
-    const char *src = Kb + (int64_t)krow * row_bytes + (lq ^ tile_swz<DT, D>(row)) * 16;
+    const int krow = min(row, N - 1 - tb);                     // rows past the last one repeat it
+    const char *src = tile + (int64_t)krow * row_bytes + (lq ^ tile_swz<DT, D>(row)) * 16;
     __builtin_amdgcn_global_load_lds((glb_void_t *)src, (lds_void_t *)(uintptr_t)(img + j * 1024), 16, 0, 0);
   }
 }
 
 template <int DT, int D, int WAVES>
-__device__ __forceinline__ void fetch_tile(const char *Kb, int64_t row_bytes, int tb, int N, uint32_t img, int wave,
+__device__ __forceinline__ void fetch_tile(const char *tile, int64_t row_bytes, int tb, int N, uint32_t img, int wave,
                                            int lane) {
   constexpr int PPR = D * Tr<DT>::EB / 16, LOADS = 32 * PPR / 64;      // loads per tile
   constexpr int RPL = 64 / PPR;                                         // rows per load
@@ -186,12 +187,12 @@ __device__ __forceinline__ void fetch_tile(const char *Kb, int64_t row_bytes, in
 #pragma unroll
     for (int jj = 0; jj < (LOADS + WAVES - 1) / WAVES; ++jj) {
       const int j = (jj * WAVES + wave) % LOADS;
-      const char *base = Kb + (int64_t)(tb + j * RPL) * row_bytes;               // wave-uniform
+      const char *base = tile + (int64_t)(j * RPL) * row_bytes;                  // wave-uniform
       const uint32_t off = (uint32_t)lrow * rb + (uint32_t)((lq ^ tile_swz<DT, D>(j * RPL + lrow)) * 16);   // loop-invariant
       __builtin_amdgcn_global_load_lds((glb_void_t *)(base + off), (lds_void_t *)(uintptr_t)(img + j * 1024), 16, 0, 0);
     }
   } else {
-    fetch_tile_clamped<DT, D, WAVES>(Kb, row_bytes, tb, N, img, wave, lane);
+    fetch_tile_clamped<DT, D, WAVES>(tile, row_bytes, tb, N, img, wave, lane);
   }
 }
 
@@ -301,12 +302,15 @@ __global__ __launch_bounds__(WAVES * 64, stats_waves_per_simd(DT, D, WAVES, TQ))
     const int nt = min(nit * KT, (N - key0 + 31) / 32);              // tiles of the run that hold keys
 
     // Request tile tr of the run (keys, and values if they are needed) into its ring image.
+    const int64_t tile_bytes = 32 * row_bytes;
     auto request = [&](int tr) {
       const int tbr = key0 + tr * 32;
       const uint32_t off = (uint32_t)(tr & (kRing - 1)) * (TILE * 16);
-      fetch_tile<DT, D, WAVES>(Kb, row_bytes, tbr, N, kring_a + off, wave, lane);
-      if (use_v) fetch_tile<DT, D, WAVES>(Vb, row_bytes, tbr, N, vring_a + off, wave, lane);
+      fetch_tile<DT, D, WAVES>(Kb + tbr * row_bytes, row_bytes, tbr, N, kring_a + off, wave, lane);
+      if (use_v) fetch_tile<DT, D, WAVES>(Vb + tbr * row_bytes, row_bytes, tbr, N, vring_a + off, wave, lane);
     };
+    // first rows of the tile the next step of the loop requests (tile t + kLead at step t)
+    const char *Kreq = Kb + (key0 + kLead * 32) * row_bytes, *Vreq = Vb + (key0 + kLead * 32) * row_bytes;
     lds_barrier();                                     // the previous run is done with LDS
 #pragma unroll
     for (int j = 0; j < kLead; ++j)
@@ -351,10 +355,12 @@ __global__ __launch_bounds__(WAVES * 64, stats_waves_per_simd(DT, D, WAVES, TQ))
       if (t + kLead < nt) {                            // tile t + kLead goes into the image tile t - 1 has left
         constexpr uint32_t off = (uint32_t)((SLOT + kLead) & (kRing - 1)) * (TILE * 16);
         const int tbr = key0 + (t + kLead) * 32;
-        fetch_tile<DT, D, WAVES>(Kb, row_bytes, tbr, N, kring_a + off, wave, lane);
-        if (use_v) fetch_tile<DT, D, WAVES>(Vb, row_bytes, tbr, N, vring_a + off, wave, lane);
+        fetch_tile<DT, D, WAVES>(Kreq, row_bytes, tbr, N, kring_a + off, wave, lane);
+        if (use_v) fetch_tile<DT, D, WAVES>(Vreq, row_bytes, tbr, N, vring_a + off, wave, lane);
       }
 #endif
+      Kreq += tile_bytes;
+      Vreq += tile_bytes;
       __builtin_amdgcn_sched_barrier(0);
 
       const int tb = key0 + t * 32;
@@ -628,10 +634,13 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
     const int key0 = c0 * CH;                                        // first key of the run
     const int nt = min(nit * KT, (N - key0 + 31) / 32);              // tiles of the run that hold keys
 
+    const int64_t tile_bytes = 32 * row_bytes;
     auto request = [&](int tr) {
-      fetch_tile<DT, D, WAVES>(Kb, row_bytes, key0 + tr * 32, N, kring_a + (uint32_t)(tr & (kRing - 1)) * (TILE * 16),
-                               wave, lane);
+      fetch_tile<DT, D, WAVES>(Kb + (key0 + tr * 32) * row_bytes, row_bytes, key0 + tr * 32, N,
+                               kring_a + (uint32_t)(tr & (kRing - 1)) * (TILE * 16), wave, lane);
     };
+    // first row of the tile the next step of the loop requests (tile t + 1 + kLead at step t)
+    const char *Kreq = Kb + (key0 + (1 + kLead) * 32) * row_bytes;
     lds_barrier();                                     // the previous run is done with LDS
 #pragma unroll
     for (int j = 0; j <= kLead; ++j)
@@ -690,9 +699,10 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
       lds_barrier();                                   // every wave holds the fragments of tile t: its image is free
 #ifndef MIXKV_NODMA   // developer switch: time the arithmetic alone (results are then meaningless)
       if (t + 1 + kLead < nt)                          // tile t + kRing goes into the image of tile t
-        fetch_tile<DT, D, WAVES>(Kb, row_bytes, key0 + (t + 1 + kLead) * 32, N, kring_a + (uint32_t)SLOT * (TILE * 16), wave,
+        fetch_tile<DT, D, WAVES>(Kreq, row_bytes, key0 + (t + 1 + kLead) * 32, N, kring_a + (uint32_t)SLOT * (TILE * 16), wave,
                                  lane);
 #endif
+      Kreq += tile_bytes;
       if (t + 1 < nt) {
         const uint4 *imgn = kring + ((SLOT + 1) & (kRing - 1)) * TILE;
 #pragma unroll
