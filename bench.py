@@ -86,9 +86,16 @@ def cpu_baseline(wl, layers, budget, max_layers, variant, r_given, head_budgets,
         dt = time.perf_counter() - t0
     # scaled to the metric: tokens of the whole cache per second if every layer cost what the sample did
     tokens_per_s = wl.batch * wl.seq_len / (dt * len(layers) / n)
+    cpu_model = "unknown CPU"
+    try:
+        with open("/proc/cpuinfo") as f:
+            cpu_model = next((l.split(":", 1)[1].strip() for l in f if l.startswith("model name")), cpu_model)
+    except OSError:
+        pass
     return dict(value=tokens_per_s, unit="tokens/s", cores=workers, kind="oracle",
                 sample=f"{n} of {len(layers)} layers ({n * wl.batch * wl.n_kv_heads} units) in {dt:.2f} s, "
-                       f"process pool of {workers}, 1 BLAS thread each; scaled by {len(layers)}/{n}"), {r[0]: r for r in res}
+                       f"process pool of {workers} on {cpu_model}, 1 BLAS thread each; scaled by {len(layers)}/{n}"), \
+        {r[0]: r for r in res}
 
 
 def algorithmic_bytes(wl, budget, scores_out, reads_v=True):
