@@ -128,30 +128,59 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
   float wi, wd;
   mix_weights(s.mix, r, s.mix == MIXKV_MIX_GIVEN_R ? in.l[layer].r_given[bh] : 0.f, wi, wd);
 
-  // ---- load: EPT consecutive candidates per thread (the per-unit rows are padded past Nc)
-  float a[EPT], v[EPT], d[EPT];
-#pragma unroll
-  for (int e4 = 0; e4 < EPT; e4 += 4) {
-    const int i = base + e4;
-    float4 ar = make_float4(0.f, 0.f, 0.f, 0.f), vr = ar, kr = ar, nr = ar;
+  // ---- load.  Two ways of dealing the candidates to the threads (the per-unit rows are padded past Nc):
+  //  * up to 16 per thread, each thread owns EPT consecutive candidates from the start, and the
+  //    intrinsic score and the diversity stay in registers next to the attention;
+  //  * beyond that, three arrays of EPT no longer fit the 128 registers a 1024-thread workgroup leaves
+  //    each lane, and loads at a thread stride of EPT * 4 bytes touch one cache line per lane.  The
+  //    first phases then deal the candidates in groups of four, group g * THREADS + tid to thread tid
+  //    (consecutive lanes read consecutive 16 bytes), keep only the attention, take the statistics of
+  //    the other two as they pass, read them a second time for the mix (from L2: the kernel before
+  //    wrote them) and hand s_comp through LDS to the consecutive owners that the selection needs.
+  constexpr bool STRIDED = EPT > 8;
+  constexpr int EPT_VD = STRIDED ? 4 : EPT;
+  auto cidx = [&](int e) { return STRIDED ? (((e >> 2) * THREADS + tid) << 2) + (e & 3) : base + e; };
+  const int nvalid = Nc - base;             // consecutive ownership: candidates of this thread inside the row
+  float a[EPT], v[EPT_VD], d[EPT_VD];
+  float st[7] = {0.f, 0.f, 0.f, INFINITY, INFINITY, -INFINITY, -INFINITY};   // sums a, v, d | min v, d | max v, d
+  // intrinsic score and diversity of the four candidates from i on (zeros past the row)
+  auto load_vd = [&](int i, float4 &vr, float4 &dr) {
+    float4 kr = make_float4(0.f, 0.f, 0.f, 0.f), nr = kr;
+    vr = kr;
     if (i < Nc) {
-      ar = *reinterpret_cast<const float4 *>(araw + i);
       kr = *reinterpret_cast<const float4 *>(kdot + i);
       nr = *reinterpret_cast<const float4 *>(invn + i);
       if (knorm) vr = make_float4(neg_key_norm(nr.x), neg_key_norm(nr.y), neg_key_norm(nr.z), neg_key_norm(nr.w));
       else if (use_v) vr = *reinterpret_cast<const float4 *>(vnorm + i);
     }
-    a[e4] = ar.x; a[e4 + 1] = ar.y; a[e4 + 2] = ar.z; a[e4 + 3] = ar.w;
-    v[e4] = vr.x; v[e4 + 1] = vr.y; v[e4 + 2] = vr.z; v[e4 + 3] = vr.w;
-    d[e4] = -kr.x * nr.x; d[e4 + 1] = -kr.y * nr.y; d[e4 + 2] = -kr.z * nr.z; d[e4 + 3] = -kr.w * nr.w;   // s_div
-  }
-  // The raw attention row goes to LDS with one pad word per 32 so that the strided accesses of
-  // consecutive-range owners spread over the banks.
+    dr = make_float4(-kr.x * nr.x, -kr.y * nr.y, -kr.z * nr.z, -kr.w * nr.w);   // s_div
+  };
+  // The raw attention row goes to LDS with one pad word per 32 so that the accesses of
+  // consecutive-range owners (a thread stride of EPT words) spread over the banks.
   auto slot = [](int i) { return i + (i >> 5); };
   if (tid == 0) { sc.ur[0] = 0xffffffffu; sc.ur[1] = 0u; }   // for the key range, read after later barriers
 #pragma unroll
-  for (int e = 0; e < EPT; ++e)
-    if (base + e < Nc) a_s[slot(base + e)] = a[e];
+  for (int e4 = 0; e4 < EPT; e4 += 4) {
+    const int i = cidx(e4);
+    float4 ar = make_float4(0.f, 0.f, 0.f, 0.f), vr, dr;
+    if (i < Nc) ar = *reinterpret_cast<const float4 *>(araw + i);
+    load_vd(i, vr, dr);
+    const float a4[4] = {ar.x, ar.y, ar.z, ar.w};
+    const float v4[4] = {vr.x, vr.y, vr.z, vr.w}, d4[4] = {dr.x, dr.y, dr.z, dr.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      a[e4 + j] = a4[j];
+      if (i + j < Nc) a_s[slot(i + j)] = a4[j];
+      if constexpr (!STRIDED) {
+        v[e4 + j] = v4[j];
+        d[e4 + j] = d4[j];
+      } else if (i + j < Nc) {
+        st[1] += v4[j]; st[2] += d4[j];
+        st[3] = fminf(st[3], v4[j]); st[4] = fminf(st[4], d4[j]);
+        st[5] = fmaxf(st[5], v4[j]); st[6] = fmaxf(st[6], d4[j]);
+      }
+    }
+  }
   __syncthreads();
 
   // ---- pooled attention (candidates only) and the first round of statistics
@@ -160,41 +189,47 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
     const bool is_max = s.pool == MIXKV_POOL_MAX;
     const float fill = is_max ? -INFINITY : 0.f;        // out-of-range taps: ignored by max, zero for avg
     if (hk <= 3) {
-      // sliding window in registers: own values plus three neighbours on either side
-      float win[EPT + 6];
+      // sliding window in registers over each run of RUN consecutive candidates the thread owns: its
+      // own values plus three neighbours on either side
+      constexpr int RUN = STRIDED ? 4 : EPT;
 #pragma unroll
-      for (int j = 0; j < 3; ++j) {
-        const int il = base - 3 + j, ir = base + EPT + j;
-        win[j] = (il >= 0 && il < Nc) ? a_s[slot(il)] : fill;
-        win[EPT + 3 + j] = (ir < Nc) ? a_s[slot(ir)] : fill;
-      }
+      for (int e0 = 0; e0 < EPT; e0 += RUN) {
+        const int i0 = cidx(e0);
+        float win[RUN + 6];
 #pragma unroll
-      for (int e = 0; e < EPT; ++e) win[3 + e] = (base + e < Nc) ? a[e] : fill;
-#pragma unroll
-      for (int e = 0; e < EPT; ++e) {
-        float acc = win[3 + e];
-        if (is_max) {
-          if (hk >= 1) acc = fmaxf(acc, fmaxf(win[2 + e], win[4 + e]));
-          if (hk >= 2) acc = fmaxf(acc, fmaxf(win[1 + e], win[5 + e]));
-          if (hk >= 3) acc = fmaxf(acc, fmaxf(win[e], win[6 + e]));
-        } else {
-          // same left-to-right order as a plain loop over the taps
-          acc = 0.f;
-          if (hk >= 3) acc += win[e];
-          if (hk >= 2) acc += win[1 + e];
-          if (hk >= 1) acc += win[2 + e];
-          acc += win[3 + e];
-          if (hk >= 1) acc += win[4 + e];
-          if (hk >= 2) acc += win[5 + e];
-          if (hk >= 3) acc += win[6 + e];
-          acc = acc / (float)s.pool_k;
+        for (int j = 0; j < 3; ++j) {
+          const int il = i0 - 3 + j, ir = i0 + RUN + j;
+          win[j] = (il >= 0 && il < Nc) ? a_s[slot(il)] : fill;
+          win[RUN + 3 + j] = (ir < Nc) ? a_s[slot(ir)] : fill;
         }
-        a[e] = acc;
+#pragma unroll
+        for (int e = 0; e < RUN; ++e) win[3 + e] = (i0 + e < Nc) ? a[e0 + e] : fill;
+#pragma unroll
+        for (int e = 0; e < RUN; ++e) {
+          float acc = win[3 + e];
+          if (is_max) {
+            if (hk >= 1) acc = fmaxf(acc, fmaxf(win[2 + e], win[4 + e]));
+            if (hk >= 2) acc = fmaxf(acc, fmaxf(win[1 + e], win[5 + e]));
+            if (hk >= 3) acc = fmaxf(acc, fmaxf(win[e], win[6 + e]));
+          } else {
+            // same left-to-right order as a plain loop over the taps
+            acc = 0.f;
+            if (hk >= 3) acc += win[e];
+            if (hk >= 2) acc += win[1 + e];
+            if (hk >= 1) acc += win[2 + e];
+            acc += win[3 + e];
+            if (hk >= 1) acc += win[4 + e];
+            if (hk >= 2) acc += win[5 + e];
+            if (hk >= 3) acc += win[6 + e];
+            acc = acc / (float)s.pool_k;
+          }
+          a[e0 + e] = acc;
+        }
       }
     } else {
 #pragma unroll
       for (int e = 0; e < EPT; ++e) {
-        const int i = base + e;
+        const int i = cidx(e);
         if (i < Nc) {
           const int lo = max(0, i - hk), hi = min(Nc - 1, i + hk);
           float acc = a_s[slot(lo)];
@@ -212,13 +247,15 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
   // One round of statistics over the candidates.  The means of the min-max normalised intrinsic score
   // and diversity follow from the plain sums: sum((x - min) * c) = (sum(x) - Nc * min) * c, and
   // mean(s_imp) = mean(s_ex) + f_in * mean(s_in_norm).
-  float st[7] = {0.f, 0.f, 0.f, INFINITY, INFINITY, -INFINITY, -INFINITY};   // sums a, v, d | min v, d | max v, d
 #pragma unroll
   for (int e = 0; e < EPT; ++e)
-    if (base + e < Nc) {
-      st[0] += a[e]; st[1] += v[e]; st[2] += d[e];
-      st[3] = fminf(st[3], v[e]); st[4] = fminf(st[4], d[e]);
-      st[5] = fmaxf(st[5], v[e]); st[6] = fmaxf(st[6], d[e]);
+    if (cidx(e) < Nc) {
+      st[0] += a[e];
+      if constexpr (!STRIDED) {
+        st[1] += v[e]; st[2] += d[e];
+        st[3] = fminf(st[3], v[e]); st[4] = fminf(st[4], d[e]);
+        st[5] = fmaxf(st[5], v[e]); st[6] = fmaxf(st[6], d[e]);
+      }
     }
   block_reduce_mixed<NW, 3, 2, 2>(st, sc);
   const float mean_ex = st[0] * inv_n;
@@ -229,17 +266,36 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
   const float f_in = use_v ? mean_ex / (mean_in + s.eps) : 0.f;         // Sec. 3.2: scale VNorm to mean(s_ex)
   const float mean_imp = use_v ? mean_ex + f_in * mean_in : mean_ex;
   const float f_div = mean_imp / (mean_dn + s.eps);                      // Sec. 3.3: scale diversity to mean(s_imp)
+  auto s_comp = [&](float ai, float vi, float di) {
+    const float imp = use_v ? ai + (vi - vmin) * rvden * f_in : ai;       // Eq. 2
+    return wi * imp + wd * ((di - dmin) * rdden * f_div);                 // Eq. 5
+  };
+  if constexpr (!STRIDED) {
 #pragma unroll
-  for (int e = 0; e < EPT; ++e) {
-    const float imp = use_v ? a[e] + (v[e] - vmin) * rvden * f_in : a[e];          // Eq. 2
-    a[e] = wi * imp + wd * ((d[e] - dmin) * rdden * f_div);                        // Eq. 5: s_comp
+    for (int e = 0; e < EPT; ++e) a[e] = s_comp(a[e], v[e], d[e]);
+  } else {
+    // every thread is past the reduction's barriers, so the pooling has read all it needs of the
+    // raw row: s_comp replaces it in LDS and comes back dealt in consecutive runs of EPT
+#pragma unroll
+    for (int e4 = 0; e4 < EPT; e4 += 4) {
+      const int i = cidx(e4);
+      float4 vr, dr;
+      load_vd(i, vr, dr);
+      const float v4[4] = {vr.x, vr.y, vr.z, vr.w}, d4[4] = {dr.x, dr.y, dr.z, dr.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (i + j < Nc) a_s[slot(i + j)] = s_comp(a[e4 + j], v4[j], d4[j]);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) a[e] = e < nvalid ? a_s[slot(base + e)] : 0.f;
   }
 
   if (O.scores) {
     float *scores = O.scores + (int64_t)bh * N;
 #pragma unroll
     for (int e = 0; e < EPT; ++e)
-      if (base + e < Nc) scores[base + e] = a[e];
+      if (e < nvalid) scores[base + e] = a[e];
     for (int i = Nc + tid; i < N; i += THREADS) scores[i] = INFINITY;
   }
   if constexpr (!SELECT) return;
@@ -268,7 +324,7 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
       key[e] = order_key_u(a[e]);
-      if (base + e < Nc) { kmin = min(kmin, key[e]); kmax = max(kmax, key[e]); }
+      if (e < nvalid) { kmin = min(kmin, key[e]); kmax = max(kmax, key[e]); }
     }
     block_minmax_u32(kmin, kmax, sc);
     // bits at and above `undecided` are common to all keys; digits of up to kDigit bits from there down
@@ -282,7 +338,7 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
       __syncthreads();
 #pragma unroll
       for (int e = 0; e < EPT; ++e) {
-        const bool on = base + e < Nc && (key[e] & himask) == (prefix & himask);
+        const bool on = e < nvalid && (key[e] & himask) == (prefix & himask);
         hist_add(sc.hist, (int)((key[e] >> shift) & ((1u << wbits) - 1u)), on);
       }
       __syncthreads();
@@ -321,7 +377,7 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
     int ngt = 0, neq = 0;
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
-      const bool in = base + e < Nc;
+      const bool in = e < nvalid;
       ngt += (in && key[e] > tau) ? 1 : 0;
       neq += (in && key[e] == tau) ? 1 : 0;
     }
@@ -331,7 +387,7 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
     int pos = (packed & 0xffff) + min(seen, k);       // kept entries at smaller indices
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
-      if (base + e < Nc) {
+      if (e < nvalid) {
         bool sel = key[e] > tau;
         if (key[e] == tau) sel = seen++ < k;
         if (sel) {
