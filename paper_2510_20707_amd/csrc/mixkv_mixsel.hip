@@ -1,11 +1,14 @@
 // mixsel_kernel: score mixing and (optionally) the fixed-budget top-B' selection of one unit in a
 // single workgroup, with every per-key quantity held in registers.
 //
-// Thread t owns the EPT consecutive candidates [t*EPT, (t+1)*EPT), so the kept indices come out in
-// ascending order from a plain prefix sum.  The pooled attention needs neighbours, so the raw
-// attention row is staged once in LDS.  The selection is a most-significant-digit radix select on
-// order-preserving integer keys kept in registers; it starts at the first bit in which the keys of
-// the head differ at all, which keeps the first histogram from collapsing into one bin.
+// Loading, pooling, statistics and mixing deal the candidates to the threads in groups of four,
+// round-robin, so that every load is coalesced; the pooled attention needs neighbours, so the raw
+// attention row is staged once in LDS.  For the selection thread t owns the EPT consecutive
+// candidates [t*EPT, (t+1)*EPT) (the mixed scores change hands through the same LDS row), so the
+// kept indices come out in ascending order from a plain prefix sum.  The selection is a
+// most-significant-digit radix select on order-preserving integer keys kept in registers; it
+// starts at the first bit in which the keys of the head differ at all, which keeps the first
+// histogram from collapsing into one bin.
 //
 // Paper: Sec. 3.2 Eq. 2 (importance = attention + scaled value norm), Sec. 3.3 (min-max and mean
 // matching of the diversity, Eq. 5 mix), Sec. 3.1 / Algorithm 1 (TopB with B' = B - W); Sec. 4.3 /
@@ -128,20 +131,17 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
   float wi, wd;
   mix_weights(s.mix, r, s.mix == MIXKV_MIX_GIVEN_R ? in.l[layer].r_given[bh] : 0.f, wi, wd);
 
-  // ---- load.  Two ways of dealing the candidates to the threads (the per-unit rows are padded past Nc):
-  //  * up to 16 per thread, each thread owns EPT consecutive candidates from the start, and the
-  //    intrinsic score and the diversity stay in registers next to the attention;
-  //  * beyond that, three arrays of EPT no longer fit the 128 registers a 1024-thread workgroup leaves
-  //    each lane, and loads at a thread stride of EPT * 4 bytes touch one cache line per lane.  The
-  //    first phases then deal the candidates in groups of four, group g * THREADS + tid to thread tid
-  //    (consecutive lanes read consecutive 16 bytes), keep only the attention, take the statistics of
-  //    the other two as they pass, read them a second time for the mix (from L2: the kernel before
-  //    wrote them) and hand s_comp through LDS to the consecutive owners that the selection needs.
-  constexpr bool STRIDED = EPT > 8;
-  constexpr int EPT_VD = STRIDED ? 4 : EPT;
-  auto cidx = [&](int e) { return STRIDED ? (((e >> 2) * THREADS + tid) << 2) + (e & 3) : base + e; };
+  // ---- load.  The first phases deal the candidates to the threads in groups of four, group
+  // g * THREADS + tid to thread tid: consecutive lanes read consecutive 16 bytes (the per-unit rows
+  // are padded past Nc).  Only the attention stays in registers; the sums and extrema of the
+  // intrinsic score and the diversity are taken as they pass, and the mix reads the two a second
+  // time (from L2: the kernel before wrote them).  Three register arrays of EPT would not fit the
+  // 128 registers a 1024-thread workgroup leaves each lane at EPT = 32, and runs of EPT consecutive
+  // candidates per thread would touch one cache line per lane and load.  The selection does need
+  // consecutive runs (ascending output from one prefix sum): s_comp reaches their owners through LDS.
+  auto cidx = [&](int e) { return (((e >> 2) * THREADS + tid) << 2) + (e & 3); };
   const int nvalid = Nc - base;             // consecutive ownership: candidates of this thread inside the row
-  float a[EPT], v[EPT_VD], d[EPT_VD];
+  float a[EPT];
   float st[7] = {0.f, 0.f, 0.f, INFINITY, INFINITY, -INFINITY, -INFINITY};   // sums a, v, d | min v, d | max v, d
   // intrinsic score and diversity of the four candidates from i on (zeros past the row)
   auto load_vd = [&](int i, float4 &vr, float4 &dr) {
@@ -153,7 +153,11 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
       if (knorm) vr = make_float4(neg_key_norm(nr.x), neg_key_norm(nr.y), neg_key_norm(nr.z), neg_key_norm(nr.w));
       else if (use_v) vr = *reinterpret_cast<const float4 *>(vnorm + i);
     }
-    dr = make_float4(-kr.x * nr.x, -kr.y * nr.y, -kr.z * nr.z, -kr.w * nr.w);   // s_div
+    // s_div: a product rounded on its own.  The minimum is taken from the first reading and must
+    // cancel exactly against the second, so the compiler may not fuse the product into the
+    // subtraction that follows there (it may by default); the empty statements hide where it came from.
+    dr = make_float4(-kr.x * nr.x, -kr.y * nr.y, -kr.z * nr.z, -kr.w * nr.w);
+    asm("" : "+v"(dr.x), "+v"(dr.y), "+v"(dr.z), "+v"(dr.w));
   };
   // The raw attention row goes to LDS with one pad word per 32 so that the accesses of
   // consecutive-range owners (a thread stride of EPT words) spread over the banks.
@@ -170,11 +174,8 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       a[e4 + j] = a4[j];
-      if (i + j < Nc) a_s[slot(i + j)] = a4[j];
-      if constexpr (!STRIDED) {
-        v[e4 + j] = v4[j];
-        d[e4 + j] = d4[j];
-      } else if (i + j < Nc) {
+      if (i + j < Nc) {
+        a_s[slot(i + j)] = a4[j];
         st[1] += v4[j]; st[2] += d4[j];
         st[3] = fminf(st[3], v4[j]); st[4] = fminf(st[4], d4[j]);
         st[5] = fmaxf(st[5], v4[j]); st[6] = fmaxf(st[6], d4[j]);
@@ -189,9 +190,9 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
     const bool is_max = s.pool == MIXKV_POOL_MAX;
     const float fill = is_max ? -INFINITY : 0.f;        // out-of-range taps: ignored by max, zero for avg
     if (hk <= 3) {
-      // sliding window in registers over each run of RUN consecutive candidates the thread owns: its
-      // own values plus three neighbours on either side
-      constexpr int RUN = STRIDED ? 4 : EPT;
+      // sliding window in registers over each group of four: its own values plus three neighbours
+      // on either side
+      constexpr int RUN = 4;
 #pragma unroll
       for (int e0 = 0; e0 < EPT; e0 += RUN) {
         const int i0 = cidx(e0);
@@ -249,14 +250,7 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
   // mean(s_imp) = mean(s_ex) + f_in * mean(s_in_norm).
 #pragma unroll
   for (int e = 0; e < EPT; ++e)
-    if (cidx(e) < Nc) {
-      st[0] += a[e];
-      if constexpr (!STRIDED) {
-        st[1] += v[e]; st[2] += d[e];
-        st[3] = fminf(st[3], v[e]); st[4] = fminf(st[4], d[e]);
-        st[5] = fmaxf(st[5], v[e]); st[6] = fmaxf(st[6], d[e]);
-      }
-    }
+    if (cidx(e) < Nc) st[0] += a[e];
   block_reduce_mixed<NW, 3, 2, 2>(st, sc);
   const float mean_ex = st[0] * inv_n;
   const float vmin = st[3], dmin = st[4];
@@ -270,26 +264,21 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
     const float imp = use_v ? ai + (vi - vmin) * rvden * f_in : ai;       // Eq. 2
     return wi * imp + wd * ((di - dmin) * rdden * f_div);                 // Eq. 5
   };
-  if constexpr (!STRIDED) {
+  // every thread is past the reduction's barriers, so the pooling has read all it needs of the raw
+  // row: s_comp replaces it in LDS and comes back dealt in consecutive runs of EPT
 #pragma unroll
-    for (int e = 0; e < EPT; ++e) a[e] = s_comp(a[e], v[e], d[e]);
-  } else {
-    // every thread is past the reduction's barriers, so the pooling has read all it needs of the
-    // raw row: s_comp replaces it in LDS and comes back dealt in consecutive runs of EPT
+  for (int e4 = 0; e4 < EPT; e4 += 4) {
+    const int i = cidx(e4);
+    float4 vr, dr;
+    load_vd(i, vr, dr);
+    const float v4[4] = {vr.x, vr.y, vr.z, vr.w}, d4[4] = {dr.x, dr.y, dr.z, dr.w};
 #pragma unroll
-    for (int e4 = 0; e4 < EPT; e4 += 4) {
-      const int i = cidx(e4);
-      float4 vr, dr;
-      load_vd(i, vr, dr);
-      const float v4[4] = {vr.x, vr.y, vr.z, vr.w}, d4[4] = {dr.x, dr.y, dr.z, dr.w};
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        if (i + j < Nc) a_s[slot(i + j)] = s_comp(a[e4 + j], v4[j], d4[j]);
-    }
-    __syncthreads();
-#pragma unroll
-    for (int e = 0; e < EPT; ++e) a[e] = e < nvalid ? a_s[slot(base + e)] : 0.f;
+    for (int j = 0; j < 4; ++j)
+      if (i + j < Nc) a_s[slot(i + j)] = s_comp(a[e4 + j], v4[j], d4[j]);
   }
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) a[e] = e < nvalid ? a_s[slot(base + e)] : 0.f;
 
   if (O.scores) {
     float *scores = O.scores + (int64_t)bh * N;

@@ -78,9 +78,17 @@ def test_budget_edges():
     _run_and_check(wl, budget=wl.seq_len)         # keep everything
 
 
-def test_identical_keys_degenerate_head():
-    # r = 1, constant diversity: every mixed score is ~0 and any selection is a valid tie-break
-    wl = WL["c1"]
+@pytest.mark.parametrize("name,kw", [
+    ("c1", {}),
+    # longer rows: 16 and 32 candidates per thread in the fused mix-and-select kernel
+    ("c2", dict(seq_len=12000, batch=1, n_q_heads=4, n_kv_heads=2, text_suffix_start=11900)),
+    ("c2", dict(seq_len=20000, batch=1, n_q_heads=4, n_kv_heads=2, text_suffix_start=19900)),
+])
+def test_identical_keys_degenerate_head(name, kw):
+    # r = 1, constant diversity: every mixed score is ~0 and any selection is a valid tie-break.
+    # The constant diversity has to cancel exactly against its own minimum, or the 1/eps of the
+    # min-max normalisation blows a rounding residue up to the size of the scores.
+    wl = WL[name].with_(name="degenerate", **kw) if kw else WL[name]
     lay = synth.make_layer(wl, 0)
     lay.K[:] = lay.K[0, 0, 0]
     p, outs = H.run_compress(wl, [lay])
