@@ -265,7 +265,14 @@ __global__ __launch_bounds__(kSelectThreads) void mix_kernel(Shape s, LayerOutTa
   const float *vnorm = reinterpret_cast<const float *>(ws + w.vnorm) + unit * s.Npad;
   const float *kdot = reinterpret_cast<const float *>(ws + w.sdiv) + unit * s.Npad;
   const float *invn = reinterpret_cast<const float *>(ws + w.invnorm) + unit * s.Npad;
-  auto sdiv_at = [&](int i) { return -kdot[i] * invn[i]; };   // s_div_i = -Khat_i . Kbar
+  // s_div_i = -Khat_i . Kbar: a product rounded on its own wherever it is formed.  Its minimum has to
+  // cancel exactly against the same product further down, so the compiler may not fuse it into
+  // the subtraction there (the empty statement hides where the value came from).
+  auto sdiv_at = [&](int i) {
+    float d = -kdot[i] * invn[i];
+    asm("" : "+v"(d));
+    return d;
+  };
   const float r = reinterpret_cast<const float *>(ws + w.rbar)[unit];
   const int Nc = s.Nc;
   const bool use_v = s.intrinsic != MIXKV_INTRINSIC_NONE;

@@ -83,6 +83,8 @@ def test_budget_edges():
     # longer rows: 16 and 32 candidates per thread in the fused mix-and-select kernel
     ("c2", dict(seq_len=12000, batch=1, n_q_heads=4, n_kv_heads=2, text_suffix_start=11900)),
     ("c2", dict(seq_len=20000, batch=1, n_q_heads=4, n_kv_heads=2, text_suffix_start=19900)),
+    # beyond the fused kernel's row length: the stand-alone mix and select kernels
+    ("c2", dict(seq_len=33000, batch=1, n_q_heads=4, n_kv_heads=2, text_suffix_start=32900)),
 ])
 def test_identical_keys_degenerate_head(name, kw):
     # r = 1, constant diversity: every mixed score is ~0 and any selection is a valid tie-break.
