@@ -39,7 +39,7 @@
 extern "C" {
 #endif
 
-#define MIXKV_VERSION 7
+#define MIXKV_VERSION 8
 #define MIXKV_MAX_LAYERS 128      /* layers per call */
 #define MIXKV_MAX_WINDOW 64
 #define MIXKV_MAX_GROUP_ROWS 512  /* G * W */
@@ -252,6 +252,24 @@ mixkv_status mixkv_decode_workspace_size(const mixkv_params *params, int32_t n_l
 mixkv_status mixkv_decode_attention(const mixkv_params *params, const mixkv_decode_layer *layers, int32_t n_layers,
                                     int32_t tail_len, int32_t tail_capacity, void *workspace, size_t workspace_bytes,
                                     void *hip_stream);
+
+/*
+ * Appends one token to the tails that mixkv_decode_attention reads (Sec. 3.1: the compressed cache
+ * is what decoding continues on, so it grows again by one row per decoded token).  Per layer,
+ * batch item b and KV head h: K_tail[b][h][position][:] = K_new[b][h][:], and the same for V:
+ * verbatim copies in the dtype of params.  K_new / V_new are [batch, n_kv_heads, D] contiguous (the
+ * new token's post-RoPE key and value rows), K_tail / V_tail [batch, n_kv_heads, tail_capacity, D]
+ * contiguous; DEVICE pointers owned by the caller, 16-byte aligned; a tail may not overlap the new
+ * rows.  0 <= position < tail_capacity, else MIXKV_ERR_INVALID_ARG (nothing is launched); the rows
+ * before `position` are not touched.  After the call on the same stream,
+ * mixkv_decode_attention with tail_len = position + 1 sees the new row.  No workspace.
+ */
+typedef struct {
+  const void *K_new, *V_new;
+  void *K_tail, *V_tail;
+} mixkv_append_layer;
+mixkv_status mixkv_append(const mixkv_params *params, const mixkv_append_layer *layers, int32_t n_layers,
+                          int32_t position, int32_t tail_capacity, void *hip_stream);
 
 const char *mixkv_status_string(mixkv_status status);
 int32_t mixkv_version(void);

@@ -265,6 +265,20 @@ def decode_attention(q: np.ndarray, K_rows: List[np.ndarray], V_rows: List[np.nd
     return out
 
 
+def append_token(K_tail: np.ndarray, V_tail: np.ndarray, k_new: np.ndarray, v_new: np.ndarray, position: int):
+    """The cache grows by one token after the compression (Sec. 3.1: decoding continues on the
+    compacted cache): row `position` of every head's tail receives the new key and value row.
+
+    K_tail / V_tail [Hkv, capacity, D] are changed in place; k_new / v_new [Hkv, D].  A copy, so the
+    stored values pass through unchanged whatever their dtype.
+    """
+    if not 0 <= position < K_tail.shape[1]:
+        raise ValueError("position outside the tail")
+    for h in range(K_tail.shape[0]):
+        K_tail[h, position] = k_new[h]
+        V_tail[h, position] = v_new[h]
+
+
 # --------------------------------------------------------------------------- selection
 
 def top_indices(s: np.ndarray, b: int) -> np.ndarray:

@@ -62,6 +62,10 @@ class MixkvDecodeLayer(C.Structure):
                 ("K_tail", C.c_void_p), ("V_tail", C.c_void_p), ("Q", C.c_void_p), ("out", C.c_void_p)]
 
 
+class MixkvAppendLayer(C.Structure):
+    _fields_ = [("K_new", C.c_void_p), ("V_new", C.c_void_p), ("K_tail", C.c_void_p), ("V_tail", C.c_void_p)]
+
+
 class MixkvError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -98,6 +102,8 @@ def lib() -> C.CDLL:
         L.mixkv_decode_attention.argtypes = [pp, C.POINTER(MixkvDecodeLayer), C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                              C.c_size_t, C.c_void_p]
         L.mixkv_decode_attention.restype = C.c_int
+        L.mixkv_append.argtypes = [pp, C.POINTER(MixkvAppendLayer), C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
+        L.mixkv_append.restype = C.c_int
         L.mixkv_decode_workspace_size.argtypes = [pp, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
         L.mixkv_decode_workspace_size.restype = C.c_int
         L.mixkv_stage_name.argtypes = [C.c_int32]
@@ -318,6 +324,17 @@ def mixkv_decode_attention(p: MixkvParams, caches, tails, Qs, tail_len: int, str
     outs = [torch.empty_like(q) for q in Qs]
     PreparedDecode(p, caches, tails, Qs, outs, tail_len, workspace).run(stream)
     return outs
+
+
+def mixkv_append(p: MixkvParams, new_rows, tails, position: int, stream=None):
+    """Copies per layer the new token's (K_new, V_new) [batch, Hkv, D] into row `position` of the
+    layer's (K_tail, V_tail) [batch, Hkv, tail_capacity, D], in place."""
+    n = len(tails)
+    arr = (MixkvAppendLayer * n)()
+    for i, ((kn, vn), (kt, vt)) in enumerate(zip(new_rows, tails)):
+        assert kn.is_contiguous() and vn.is_contiguous() and kt.is_contiguous() and vt.is_contiguous()
+        arr[i] = MixkvAppendLayer(_ptr(kn), _ptr(vn), _ptr(kt), _ptr(vt))
+    _check(lib().mixkv_append(C.byref(p), arr, n, position, tails[0][0].shape[2], _stream(stream)), "mixkv_append")
 
 
 class PreparedCall:

@@ -319,3 +319,69 @@ extern "C" mixkv_status mixkv_decode_attention(const mixkv_params *params, const
   }
   return MIXKV_OK;
 }
+
+// ------------------------------------------------------------------------------------------------
+// mixkv_append: the new token's key and value rows go to row `position` of every head's tail
+// (Sec. 3.1: decoding continues on the compressed cache).  16 bytes per thread; thread p of the
+// launch copies piece p % PPR of (layer, batch item, head) p / PPR, once for K and once for V.
+// ------------------------------------------------------------------------------------------------
+namespace mixkv {
+struct AppendLayer { const char *K_new, *V_new; char *K_tail, *V_tail; };
+struct AppendTable { AppendLayer l[kLayersPerLaunch]; };
+
+__global__ __launch_bounds__(256) void append_kernel(AppendTable tab, int units_per_layer, int nunits, int ppr,
+                                                      int position, int tail_cap) {
+  const int p = blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= nunits * ppr) return;
+  const int ul = p / ppr, piece = p - ul * ppr;
+  const int layer = ul / units_per_layer, bh = ul - layer * units_per_layer;
+  const AppendLayer L = tab.l[layer];
+  const int64_t src = ((int64_t)bh * ppr + piece) * 16;
+  const int64_t dst = (((int64_t)bh * tail_cap + position) * ppr + piece) * 16;
+  const uint4 k = *reinterpret_cast<const uint4 *>(L.K_new + src);
+  const uint4 v = *reinterpret_cast<const uint4 *>(L.V_new + src);
+  *reinterpret_cast<uint4 *>(L.K_tail + dst) = k;
+  *reinterpret_cast<uint4 *>(L.V_tail + dst) = v;
+}
+}  // namespace mixkv
+
+extern "C" mixkv_status mixkv_append(const mixkv_params *params, const mixkv_append_layer *layers, int32_t n_layers,
+                                     int32_t position, int32_t tail_capacity, void *hip_stream) {
+  using namespace mixkv;
+  Shape sh;
+  mixkv_status st = make_shape(params, &sh);
+  if (st != MIXKV_OK) return st;
+  if (!layers || n_layers < 1 || n_layers > MIXKV_MAX_LAYERS) return MIXKV_ERR_INVALID_ARG;
+  if (position < 0 || position >= tail_capacity) return MIXKV_ERR_INVALID_ARG;
+  const int eb = params->dtype == MIXKV_BF16 ? 2 : 4, ppr = sh.D * eb / 16;
+  const size_t new_bytes = (size_t)sh.units_per_layer * sh.D * eb, tail_bytes = new_bytes * (size_t)tail_capacity;
+  auto bad16 = [](const void *p) { return !p || (reinterpret_cast<uintptr_t>(p) & 15u); };
+  auto overlap = [](const void *a, size_t na, const void *b, size_t nb) {
+    const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+    return x < y + nb && y < x + na;
+  };
+  for (int l = 0; l < n_layers; ++l) {
+    const mixkv_append_layer &a = layers[l];
+    if (bad16(a.K_new) || bad16(a.V_new) || bad16(a.K_tail) || bad16(a.V_tail)) return MIXKV_ERR_INVALID_ARG;
+    if (overlap(a.K_tail, tail_bytes, a.K_new, new_bytes) || overlap(a.K_tail, tail_bytes, a.V_new, new_bytes) ||
+        overlap(a.V_tail, tail_bytes, a.K_new, new_bytes) || overlap(a.V_tail, tail_bytes, a.V_new, new_bytes) ||
+        overlap(a.K_tail, tail_bytes, a.V_tail, tail_bytes))
+      return MIXKV_ERR_INVALID_ARG;
+  }
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  for (int l0 = 0; l0 < n_layers; l0 += kLayersPerLaunch) {
+    const int nl = (n_layers - l0 < kLayersPerLaunch) ? n_layers - l0 : kLayersPerLaunch;
+    AppendTable t;
+    for (int l = 0; l < kLayersPerLaunch; ++l) t.l[l] = AppendLayer{nullptr, nullptr, nullptr, nullptr};
+    for (int l = 0; l < nl; ++l) {
+      const mixkv_append_layer &a = layers[l0 + l];
+      t.l[l] = AppendLayer{static_cast<const char *>(a.K_new), static_cast<const char *>(a.V_new),
+                           static_cast<char *>(a.K_tail), static_cast<char *>(a.V_tail)};
+    }
+    const int nunits = nl * sh.units_per_layer, threads = nunits * ppr;
+    hipLaunchKernelGGL(append_kernel, dim3((threads + 255) / 256), dim3(256), 0, stream, t, sh.units_per_layer, nunits, ppr,
+                       position, tail_capacity);
+    if (hipGetLastError() != hipSuccess) return MIXKV_ERR_HIP;
+  }
+  return MIXKV_OK;
+}

@@ -140,3 +140,21 @@ def test_header_is_plain_c_and_the_library_links_from_c(tmp_path):
                     "-Wl,-rpath,/opt/rocm/lib", "-Wl,--allow-shlib-undefined"], check=True)
     r = subprocess.run([exe], capture_output=True, text=True)
     assert r.returncode == 0 and r.stdout.startswith("ok ok"), (r.returncode, r.stdout, r.stderr)
+
+
+def test_append_rejects_positions_outside_the_tail_and_bad_pointers():
+    L = B.lib()
+    p = _good()
+    lay = (B.MixkvAppendLayer * 1)()
+    lay[0] = B.MixkvAppendLayer(0x10000, 0x20000, 0x1000000, 0x2000000)     # never dereferenced: validation fails first
+    assert C.sizeof(B.MixkvAppendLayer) == 4 * 8
+    for position, cap in ((-1, 8), (8, 8), (0, 0)):
+        assert L.mixkv_append(C.byref(p), lay, 1, position, cap, None) == B.MIXKV_ERR_INVALID_ARG
+    assert L.mixkv_append(C.byref(p), None, 1, 0, 8, None) == B.MIXKV_ERR_INVALID_ARG
+    assert L.mixkv_append(C.byref(p), lay, 0, 0, 8, None) == B.MIXKV_ERR_INVALID_ARG
+    lay[0] = B.MixkvAppendLayer(0x10008, 0x20000, 0x1000000, 0x2000000)     # misaligned new key rows
+    assert L.mixkv_append(C.byref(p), lay, 1, 0, 8, None) == B.MIXKV_ERR_INVALID_ARG
+    lay[0] = B.MixkvAppendLayer(0x1000100, 0x20000, 0x1000000, 0x2000000)    # new key rows inside the key tail
+    assert L.mixkv_append(C.byref(p), lay, 1, 0, 8, None) == B.MIXKV_ERR_INVALID_ARG
+    lay[0] = B.MixkvAppendLayer(0x10000, 0x20000, 0, 0x2000000)              # no tail
+    assert L.mixkv_append(C.byref(p), lay, 1, 0, 8, None) == B.MIXKV_ERR_INVALID_ARG

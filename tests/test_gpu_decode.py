@@ -143,3 +143,47 @@ def test_window_only_cache_and_single_row():
     _decode_and_check(wl, [0], 1, budget=wl.window)
     tiny = WL["c1"].with_(name="tiny-dec", seq_len=2, window=1, budget=1, n_q_heads=1, n_kv_heads=1)
     _decode_and_check(tiny, [0], 0)                              # one row: the output is that value row
+
+
+@pytest.mark.parametrize("name,over", [("c1", {}), ("c2", {}),
+                                       ("c2", dict(seq_len=1024, text_suffix_start=960, batch=2, budget=96,
+                                                   budget_mode="adaptive", budget_floor=16))])
+def test_append_then_decode_token_by_token(name, over):
+    """Three decoding steps on a compacted cache: every step appends the new token's rows with
+    mixkv_append and attends with mixkv_decode_attention.  The tails must hold the appended rows
+    bit for bit (and nothing else may change), the outputs must match the oracle on the grown cache."""
+    wl = WL[name].with_(name="append", **over) if over else WL[name]
+    layer_ids, steps, cap = [0, 1], 3, 5
+    print(f"[case] append+decode {wl.name} dtype={wl.dtype} mode={wl.budget_mode} steps={steps} cap={cap}", flush=True)
+    layers = [synth.make_layer(wl, l) for l in layer_ids]
+    p, caches = H.run_compress(wl, layers)
+    Bt, Hq, Hkv, D = wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim
+    rng = np.random.default_rng([82, wl.cfg_id])
+    fill = 3.0                                             # what the untouched tail rows must still hold at the end
+    tails_host = [(np.full((Bt, Hkv, cap, D), fill, np.float32), np.full((Bt, Hkv, cap, D), -fill, np.float32)) for _ in layers]
+    tails = [(H.to_device(wl, k), H.to_device(wl, v)) for k, v in tails_host]
+    Bud = p.budget
+    for t in range(steps):
+        new_host = [(_quant(wl, rng.standard_normal((Bt, Hkv, D)) + 0.3), _quant(wl, rng.standard_normal((Bt, Hkv, D))))
+                    for _ in layers]
+        qs = [_quant(wl, rng.standard_normal((Bt, Hq, D)) / np.sqrt(D) * 4.0) for _ in layers]
+        B.mixkv_append(p, [(H.to_device(wl, k), H.to_device(wl, v)) for k, v in new_host], tails, t)
+        outs = B.mixkv_decode_attention(p, caches, tails, [H.to_device(wl, q) for q in qs], t + 1)
+        torch.cuda.synchronize()
+        for li, (lay, c) in enumerate(zip(layers, caches)):
+            for b in range(Bt):                            # the oracle's copy of the same append
+                O.append_token(tails_host[li][0][b], tails_host[li][1][b], new_host[li][0][b], new_host[li][1][b], t)
+            for dev_t, host_t in zip(tails[li], tails_host[li]):
+                assert np.array_equal(dev_t.float().cpu().numpy(), host_t), f"tail differs at step {t}, layer {li}"
+            got = outs[li].float().cpu().numpy().astype(np.float64)
+            idx = c.indices.cpu().numpy().reshape(Bt, Hkv * Bud)
+            cnt, off = c.counts.cpu().numpy(), c.offsets.cpu().numpy()
+            for b in range(Bt):
+                Ks = [np.concatenate([_quant(wl, lay.K[b, h][idx[b, off[b, h]:off[b, h] + cnt[b, h]]]),
+                                      tails_host[li][0][b, h, :t + 1]]) for h in range(Hkv)]
+                Vs = [np.concatenate([_quant(wl, lay.V[b, h][idx[b, off[b, h]:off[b, h] + cnt[b, h]]]),
+                                      tails_host[li][1][b, h, :t + 1]]) for h in range(Hkv)]
+                want = O.decode_attention(qs[li][b], Ks, Vs, wl.softmax_scale)
+                for g in range(Hq):
+                    err = np.abs(got[b, g] - want[g]).max() / np.abs(want[g]).max()
+                    assert err <= TOL[wl.dtype], f"step {t} layer {li} b{b} g{g}: error {err:.2e}"

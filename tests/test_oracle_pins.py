@@ -594,3 +594,26 @@ def test_decode_attention_closed_forms():
     np.testing.assert_allclose(out[0], V[4], atol=1e-9)
     out1 = O.decode_attention(q, [K[:1]], [V[:1]], 3.0)       # a single row: its value, whatever the logit
     np.testing.assert_allclose(out1, np.tile(V[0], (2, 1)), rtol=1e-14)
+
+
+def test_append_token_fills_rows_in_order_and_touches_nothing_else():
+    # appending t tokens one by one gives the tail whose first t rows are the tokens in order
+    # (numpy's stack is the independent statement of that), later rows keep what they held
+    rng = np.random.default_rng(44)
+    Hkv, cap, D, t = 3, 6, 8, 4
+    Kt, Vt = np.full((Hkv, cap, D), 7.0), np.full((Hkv, cap, D), -7.0)
+    ks, vs = rng.standard_normal((t, Hkv, D)), rng.standard_normal((t, Hkv, D))
+    for j in range(t):
+        O.append_token(Kt, Vt, ks[j], vs[j], j)
+    assert np.array_equal(Kt[:, :t], np.stack(list(ks), axis=1)) and np.array_equal(Vt[:, :t], np.stack(list(vs), axis=1))
+    assert np.all(Kt[:, t:] == 7.0) and np.all(Vt[:, t:] == -7.0)
+    with pytest.raises(ValueError):
+        O.append_token(Kt, Vt, ks[0], vs[0], cap)
+    with pytest.raises(ValueError):
+        O.append_token(Kt, Vt, ks[0], vs[0], -1)
+    # attention over the grown cache: a token appended with a very large logit takes all the weight
+    q = np.zeros((Hkv, D)); q[:, 0] = 1.0
+    big = np.zeros((Hkv, D)); big[:, 0] = 200.0
+    O.append_token(Kt, Vt, big, vs[0], t)
+    out = O.decode_attention(q, [Kt[h, :t + 1] for h in range(Hkv)], [Vt[h, :t + 1] for h in range(Hkv)], 1.0)
+    assert np.allclose(out, vs[0], atol=1e-12)
