@@ -429,23 +429,32 @@ __global__ __launch_bounds__(WAVES * 64, stats_waves_per_simd(DT, D, WAVES, TQ))
 #pragma unroll
       for (int q = 0; q < TQ; ++q) {
         if (nq == 0) break;                               // wave-uniform: this wave has no query tile
-        float tmax = fmaxf(acc[q][0], acc[q][1]);
+        // The offset m of a row only has to keep the terms inside the range of a float: exp2 of
+        // (logit - m) may be far above 1.  So the terms are formed with the offset as it stands,
+        // and only if a row's sum comes out infinite or undefined (a term or the sum overflowed, or the
+        // row has no offset yet: m = -inf gives inf or NaN for every key) does the wave take the tile's
+        // maximum, move the offset there, rescale the sum and form the terms again.  After a
+        // row's first tile that takes a logit 88 above everything the row has seen before.
+        float sum[4] = {0.f, 0.f, 0.f, 0.f};              // four chains: the adds do not wait on each other
+        {
+          const float nmu = -m[q];
 #pragma unroll
-        for (int i = 2; i < 16; i += 2) tmax = fmaxf(fmaxf(tmax, acc[q][i]), acc[q][i + 1]);
-        // The running offset m only has to be an upper bound of what was seen: it moves (and the
-        // sum is rescaled) only in the steps where some row of the wave sees a new maximum.
-        const float tm = tmax * c2;                       // c2 > 0: scaling commutes with max
-        if (__builtin_amdgcn_ballot_w64(tm > m[q]) != 0) {
-          const float mn = fmaxf(m[q], tm);
-          const float mu = (mn == -INFINITY) ? 0.f : mn;
-          l[q] = l[q] * fast_exp2(m[q] - mu);
+          for (int i = 0; i < 16; ++i) sum[i & 3] += fast_exp2(fmaf(acc[q][i], c2, nmu));
+        }
+        float lnew = l[q] + ((sum[0] + sum[1]) + (sum[2] + sum[3]));
+        if (__builtin_amdgcn_ballot_w64(!(lnew < INFINITY)) != 0) {
+          float tmax = fmaxf(acc[q][0], acc[q][1]);
+#pragma unroll
+          for (int i = 2; i < 16; i += 2) tmax = fmaxf(fmaxf(tmax, acc[q][i]), acc[q][i + 1]);
+          const float mn = fmaxf(m[q], tmax * c2);          // c2 > 0: scaling commutes with max
+          const float mu = (mn == -INFINITY) ? 0.f : mn;    // nothing visible yet: every term is exp2(-inf) = 0
+          float s2[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int i = 0; i < 16; ++i) s2[i & 3] += fast_exp2(fmaf(acc[q][i], c2, -mu));
+          lnew = l[q] * fast_exp2(m[q] - mu) + ((s2[0] + s2[1]) + (s2[2] + s2[3]));
           m[q] = mn;
         }
-        const float nmu = (m[q] == -INFINITY) ? 0.f : -m[q];
-        float sum[4] = {0.f, 0.f, 0.f, 0.f};              // four chains: the adds do not wait on each other
-#pragma unroll
-        for (int i = 0; i < 16; ++i) sum[i & 3] += fast_exp2(fmaf(acc[q][i], c2, nmu));
-        l[q] += (sum[0] + sum[1]) + (sum[2] + sum[3]);
+        l[q] = lnew;
       }
     };
     static_assert(kRing == 4, "unrolled four times below");
@@ -461,6 +470,13 @@ __global__ __launch_bounds__(WAVES * 64, stats_waves_per_simd(DT, D, WAVES, TQ))
     float2 *part_ml = reinterpret_cast<float2 *>(ws + w.part_ml) + slot * QTR;
 #pragma unroll
     for (int q = 0; q < (GIVEN_LSE ? 0 : TQ); ++q) {
+      // The sum may be far from 1 (the offset is not the maximum): bring it back to [0.5, 1) so that
+      // the merges below and in the fold cannot overflow.
+      {
+        int e;
+        l[q] = frexpf(l[q], &e);
+        m[q] += (float)e;
+      }
       ml_merge(m[q], l[q], __shfl_xor(m[q], 32), __shfl_xor(l[q], 32));
       if (q < nq && half == 0) part_ml[(wave * TQ + q) * 32 + l32] = make_float2(m[q], l[q]);
     }

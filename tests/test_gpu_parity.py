@@ -72,6 +72,16 @@ def test_ragged_shapes(dtype, D, N, W, Hq, Hkv, B):
     _run_and_check(wl, n_layers=2)
 
 
+@pytest.mark.parametrize("scale", [30.0, 150.0])
+def test_large_logits_move_the_softmax_offset_mid_run(scale):
+    # Logits with a standard deviation of 30 and 150: at 150 a row meets keys far more than 88 above
+    # everything its first key tile held, so the running softmax offset of pass 1 has to move in the middle of a
+    # run (the terms relative to the old offset overflow a float); at 30 the sums grow far beyond 1
+    # without overflowing.  Both must give the oracle's scores.
+    wl = WL["c2"].with_(name="large-logits", seq_len=2048, text_suffix_start=1984, batch=1)
+    _run_and_check(wl, softmax_scale=scale)
+
+
 def test_budget_edges():
     wl = WL["c1"]
     _run_and_check(wl, budget=wl.window)          # B' = 0: window only
