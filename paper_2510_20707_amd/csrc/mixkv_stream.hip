@@ -435,11 +435,14 @@ __global__ __launch_bounds__(WAVES * 64, stats_waves_per_simd(DT, D, WAVES, TQ))
         // row has no offset yet: m = -inf gives inf or NaN for every key) does the wave take the tile's
         // maximum, move the offset there, rescale the sum and form the terms again.  After a
         // row's first tile that takes a logit 88 above everything the row has seen before.
-        float sum[4] = {0.f, 0.f, 0.f, 0.f};              // four chains: the adds do not wait on each other
+        float sum[4];                                     // four chains: the adds do not wait on each other
         {
           const float nmu = -m[q];
 #pragma unroll
-          for (int i = 0; i < 16; ++i) sum[i & 3] += fast_exp2(fmaf(acc[q][i], c2, nmu));
+          for (int i = 0; i < 16; ++i) {
+            const float term = fast_exp2(fmaf(acc[q][i], c2, nmu));
+            sum[i & 3] = i < 4 ? term : sum[i & 3] + term;          // the first term starts its chain
+          }
         }
         float lnew = l[q] + ((sum[0] + sum[1]) + (sum[2] + sum[3]));
         if (__builtin_amdgcn_ballot_w64(!(lnew < INFINITY)) != 0) {
@@ -774,11 +777,14 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
             acc[q][i] = (key <= lim_s[row]) ? acc[q][i] : -INFINITY;
           }
       }
-      float cs4[4] = {0.f, 0.f, 0.f, 0.f};             // four chains: the adds do not wait on each other
+      float cs4[4];                                    // four chains: the adds do not wait on each other
 #pragma unroll
       for (int q = 0; q < TQ; ++q)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) cs4[i & 3] += fast_exp2(fmaf(acc[q][i], c2, nbv[q][i]));
+        for (int i = 0; i < 16; ++i) {
+          const float wgt = fast_exp2(fmaf(acc[q][i], c2, nbv[q][i]));
+          cs4[i & 3] = (q == 0 && i < 4) ? wgt : cs4[i & 3] + wgt;     // the first term starts its chain
+        }
       float colsum = (cs4[0] + cs4[1]) + (cs4[2] + cs4[3]);
       colsum += __shfl_xor(colsum, 32);
       if (half == 0) cs[k * 32 + l32] = colsum;
