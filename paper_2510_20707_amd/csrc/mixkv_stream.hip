@@ -612,7 +612,7 @@ __global__ __launch_bounds__(kFoldThreads) void fold_kernel(Shape s, LayerOutTab
 // The exponent offsets and the mean key come from fold_kernel.  The fragments of the next key tile
 // are read from LDS into a second set of registers while the current tile is being worked on.
 // ------------------------------------------------------------------------------------------------
-template <int DT, int D, int WAVES, int TQ>
+template <int DT, int D, int WAVES, int TQ, bool SPARE>
 __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTable in, LayerOutTable out, char *ws,
                                                             Workspace w, int64_t unit0, int nunits) {
   constexpr int EB = Tr<DT>::EB, EPC = Tr<DT>::EPC, NCHK = D / (2 * EPC), PPR = D * EB / 16;
@@ -629,7 +629,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
   const float c2 = s.scale_log2e;
   const int free_limit = s.causal ? Nc : N - 1;
   // the mean key rides in rows 0/1 of the first tile past the live rows, if the block has one
-  const bool spare = s.QT < WAVES * TQ;
+  // (SPARE, chosen by the launcher: QT < WAVES * TQ)
+  constexpr bool spare = SPARE;
   const int kb_wave = s.QT / TQ, kb_q = s.QT % TQ;
   const uint32_t kring_a = lds_base_of(kring);
   for (int r = tid; r < WAVES * TQ * 32; r += NT) lim_s[r] = s.causal ? Nc + r % s.W : N - 1;
@@ -705,99 +706,155 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
       }
     };
 
-    // One tile step.  At its start the images of tiles <= t + 1 are visible to every wave; the
-    // fragments of tile t are already in registers (kf), those of tile t + 1 are read into kfn
-    // under this tile's arithmetic, and tile t + 1 + kLead is requested into the image of tile t,
-    // which nobody reads any more.
+    // Where the mean key has no spare query rows, every WAVES-th key tile also meets a separate
+    // mean-key tile (the waves take turns): K_i . Kbar for the keys of the tile whose fragments are kf.
+    auto mean_key_dots = [&](const Frag (&kf)[NCHK]) {
+      f32x16 acd;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acd[i] = 0.f;
+#pragma unroll
+      for (int c = 0; c < NCHK; ++c) {
+        Frag kbf;
+        kbf.q = kbar_s[(c * 2 + half) * 2 + (l32 & 1)];
+        if (l32 >= 2) kbf.q = make_uint4(0, 0, 0, 0);
+        acd = mma<DT>(kbf, kf[c], acd);
+      }
+      return acd[0] + acd[1];
+    };
+    // Scores of the key tile in image `img` into accN: NCHK fragment reads, each feeding the TQ chains.
+    auto scores = [&](const uint4 *img, f32x16 (&accN)[TQ]) {
+#pragma unroll
+      for (int q = 0; q < TQ; ++q)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) accN[q][i] = 0.f;
+#pragma unroll
+      for (int c = 0; c < NCHK; ++c) {
+        Frag kf;
+        kf.q = read_key_frag<DT, D>(img, 0, c, l32, half);
+#pragma unroll
+        for (int q = 0; q < TQ; ++q) accN[q] = mma<DT>(qf[q][c], kf, accN[q]);
+      }
+    };
+
+    // One tile step.  At its start the images of tiles <= t + 1 are visible to every wave and the
+    // scores of tile t are in accC (their matrix instructions were issued a step ago).  The step
+    // issues the matrix instructions of tile t + 1 into accN and, in their shadow, turns the scores
+    // of tile t into weights and column sums: a wave's matrix and vector work overlap although
+    // the one feeds the other.  Tile t + 1 + kLead is requested into the image of tile t, which
+    // nobody reads any more (its fragments were read a step ago).  After the last tile of a run the
+    // "next" image holds an older tile: its scores are computed and never used.
     // The loop is unrolled over the ring, so the ring slot of a step (t mod kRing) is a constant and
     // the LDS addresses of its reads are a loop-invariant lane offset plus an immediate.
-    auto step = [&](auto slot_c, int t, Frag (&kf)[NCHK], Frag (&kfn)[NCHK]) {
+    auto step = [&](auto slot_c, int t, f32x16 (&accC)[TQ], f32x16 (&accN)[TQ], float &kdC, float &kdN) {
       constexpr int SLOT = decltype(slot_c)::value;
       __builtin_amdgcn_sched_barrier(0);
       wait_tile<KL>(t + 1, nt);
-      lds_barrier();                                   // every wave holds the fragments of tile t: its image is free
+      lds_barrier();                                   // every wave has read the fragments of tile t: its image is free
 #ifndef MIXKV_NODMA   // developer switch: time the arithmetic alone (results are then meaningless)
       if (t + 1 + kLead < nt)                          // tile t + kRing goes into the image of tile t
         fetch_tile<DT, D, WAVES>(Kreq, row_bytes, key0 + (t + 1 + kLead) * 32, N, kring_a + (uint32_t)SLOT * (TILE * 16), wave,
                                  lane);
 #endif
       Kreq += tile_bytes;
-      if (t + 1 < nt) {
-        const uint4 *imgn = kring + ((SLOT + 1) & (kRing - 1)) * TILE;
-#pragma unroll
-        for (int c = 0; c < NCHK; ++c) kfn[c].q = read_key_frag<DT, D>(imgn, 0, c, l32, half);
-      }
-      __builtin_amdgcn_sched_barrier(0);
       const int k = SLOT % KT, g = t / KT;             // tile within its chunk, chunk within the run
       if (k == 0 && g > 0) flush_colsums(c0 + g - 1, (g - 1) & 1);
       float *cs = cs_s + ((g & 1) * WAVES + wave) * CH;
       const int tb = key0 + t * 32, key = tb + l32;
+      const uint4 *imgn = kring + ((SLOT + 1) & (kRing - 1)) * TILE;
 
-      f32x16 acc[TQ];
-#pragma unroll
-      for (int q = 0; q < TQ; ++q)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[q][i] = 0.f;
-#pragma unroll
-      for (int c = 0; c < NCHK; ++c)
-#pragma unroll
-        for (int q = 0; q < TQ; ++q) acc[q] = mma<DT>(qf[q][c], kf[c], acc[q]);
-
-      // ---- K_i . Kbar: rows 0 and 1 (half 0) of the spare tile, or a separate mean-key tile that
-      // the waves apply in turn
-      float kd = 0.f;
-      bool kd_mine;
-      if (spare) {
-        kd = (kb_q == 0 ? acc[0][0] + acc[0][1] : acc[TQ - 1][0] + acc[TQ - 1][1]);
-        kd_mine = wave == kb_wave;
-      } else {
-        kd_mine = t % WAVES == wave;
-        if (kd_mine) {
-          f32x16 acd;
-#pragma unroll
-          for (int i = 0; i < 16; ++i) acd[i] = 0.f;
-#pragma unroll
-          for (int c = 0; c < NCHK; ++c) {
-            Frag kbf;
-            kbf.q = kbar_s[(c * 2 + half) * 2 + (l32 & 1)];
-            if (l32 >= 2) kbf.q = make_uint4(0, 0, 0, 0);
-            acd = mma<DT>(kbf, kf[c], acd);
-          }
-          kd = acd[0] + acd[1];
+      // straight-line body, once with and once without the mask of the tiles that reach into the
+      // window or past N, so that the scheduler sees matrix and vector work in one block
+      auto body = [&](auto mask_c) {
+        constexpr bool MASK = decltype(mask_c)::value;
+        __builtin_amdgcn_sched_barrier(0);
+        // ---- K_i . Kbar: rows 0 and 1 (half 0) of the spare tile (taken before the mask touches
+        // them), or what the separate mean-key tile left a step ago
+        float kd = kdC;
+        bool kd_mine = t % WAVES == wave;
+        if constexpr (SPARE) {
+          const float kd0 = accC[0][0] + accC[0][1], kd1 = accC[TQ - 1][0] + accC[TQ - 1][1];
+          kd = kb_q == 0 ? kd0 : kd1;
+          kd_mine = wave == kb_wave;
         }
-      }
-      if (kd_mine && half == 0 && key < Nc) kdot[key] = kd;
-
-      if (tb + 31 > free_limit) {                      // tile reaches into the window or past N: mask
+        if constexpr (MASK) {
 #pragma unroll
-        for (int q = 0; q < TQ; ++q)
+          for (int q = 0; q < TQ; ++q)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int row = (wave * TQ + q) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-            acc[q][i] = (key <= lim_s[row]) ? acc[q][i] : -INFINITY;
-          }
-      }
-      float cs4[4];                                    // four chains: the adds do not wait on each other
-#pragma unroll
-      for (int q = 0; q < TQ; ++q)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float wgt = fast_exp2(fmaf(acc[q][i], c2, nbv[q][i]));
-          cs4[i & 3] = (q == 0 && i < 4) ? wgt : cs4[i & 3] + wgt;     // the first term starts its chain
+            for (int i = 0; i < 16; ++i) {
+              const int row = (wave * TQ + q) * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+              accC[q][i] = (key <= lim_s[row]) ? accC[q][i] : -INFINITY;
+            }
         }
-      float colsum = (cs4[0] + cs4[1]) + (cs4[2] + cs4[3]);
-      colsum += __shfl_xor(colsum, 32);
-      if (half == 0) cs[k * 32 + l32] = colsum;
+        // The matrix instructions of tile t + 1 and the weights of tile t, slice by slice: one
+        // matrix instruction, then its share of the step's TQ * 16 weights (fma, exp, add), with
+        // the order of the slices fixed so that the vector work is issued while the matrix core
+        // runs.  The fragment of the next contraction chunk is read one chunk ahead.
+        constexpr int EPS = 16 / NCHK;                   // weights per slice
+        static_assert(16 % NCHK == 0, "a whole number of weights per matrix instruction");
+        // Fragments: read one contraction chunk ahead into two rotating registers sets; where a
+        // separate mean-key tile follows and registers allow (one query tile per wave), all NCHK
+        // are read up front and kept for it.
+        constexpr bool HOLD = !SPARE && TQ == 1;
+        constexpr int NF = HOLD ? NCHK : 2;
+        Frag kfr[NF];
+#pragma unroll
+        for (int c = 0; c < (HOLD ? NCHK : 1); ++c) kfr[c].q = read_key_frag<DT, D>(imgn, 0, c, l32, half);
+        float cs4[4];                                    // four chains: the adds do not wait on each other
+#pragma unroll
+        for (int c = 0; c < NCHK; ++c) {
+          if (!HOLD && c + 1 < NCHK) kfr[(c + 1) % NF].q = read_key_frag<DT, D>(imgn, 0, c + 1, l32, half);
+#pragma unroll
+          for (int q = 0; q < TQ; ++q) {
+            if (c == 0) {
+#pragma unroll
+              for (int i = 0; i < 16; ++i) accN[q][i] = 0.f;
+            }
+            accN[q] = mma<DT>(qf[q][c], kfr[c % NF], accN[q]);
+#pragma unroll
+            for (int j = 0; j < EPS; ++j) {
+              const int n = (c * TQ + q) * EPS + j, qq = n / 16, i = n % 16;
+              const float wgt = fast_exp2(fmaf(accC[qq][i], c2, nbv[qq][i]));
+              cs4[i & 3] = n < 4 ? wgt : cs4[i & 3] + wgt;        // the first term starts its chain
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+        if constexpr (HOLD) {
+          if ((t + 1) % WAVES == wave) kdN = mean_key_dots(kfr);
+        } else if constexpr (!SPARE) {
+          if ((t + 1) % WAVES == wave) {
+            Frag kfa[NCHK];
+#pragma unroll
+            for (int c = 0; c < NCHK; ++c) kfa[c].q = read_key_frag<DT, D>(imgn, 0, c, l32, half);
+            kdN = mean_key_dots(kfa);
+          }
+        }
+        float colsum = (cs4[0] + cs4[1]) + (cs4[2] + cs4[3]);
+        colsum += __shfl_xor(colsum, 32);
+        __builtin_amdgcn_sched_barrier(0);
+        if (half == 0) cs[k * 32 + l32] = colsum;
+        if (kd_mine && half == 0 && key < Nc) kdot[key] = kd;
+      };
+      if (tb + 31 > free_limit) body(std::true_type{});
+      else body(std::false_type{});
     };
 
-    Frag kfa[NCHK], kfb[NCHK];
+    f32x16 accA[TQ], accB[TQ];
+    float kdA = 0.f, kdB = 0.f;
+    scores(kring, accA);                                // tile 0
+    if constexpr (!SPARE) {
+      if (wave == 0) {
+        Frag kfa[NCHK];
 #pragma unroll
-    for (int c = 0; c < NCHK; ++c) kfa[c].q = read_key_frag<DT, D>(kring, 0, c, l32, half);   // tile 0
+        for (int c = 0; c < NCHK; ++c) kfa[c].q = read_key_frag<DT, D>(kring, 0, c, l32, half);
+        kdA = mean_key_dots(kfa);
+      }
+    }
     for (int t = 0; t < nt; t += kRing) {
-      step(std::integral_constant<int, 0>{}, t, kfa, kfb);
-      if (t + 1 < nt) step(std::integral_constant<int, 1>{}, t + 1, kfb, kfa);
-      if (t + 2 < nt) step(std::integral_constant<int, 2>{}, t + 2, kfa, kfb);
-      if (t + 3 < nt) step(std::integral_constant<int, 3>{}, t + 3, kfb, kfa);
+      step(std::integral_constant<int, 0>{}, t, accA, accB, kdA, kdB);
+      if (t + 1 < nt) step(std::integral_constant<int, 1>{}, t + 1, accB, accA, kdB, kdA);
+      if (t + 2 < nt) step(std::integral_constant<int, 2>{}, t + 2, accA, accB, kdA, kdB);
+      if (t + 3 < nt) step(std::integral_constant<int, 3>{}, t + 3, accB, accA, kdB, kdA);
     }
     lds_barrier();
     flush_colsums(c0 + (nt - 1) / KT, ((nt - 1) / KT) & 1);
@@ -848,8 +905,14 @@ static hipError_t launch_attn_c(const Shape &s, const LayerInTable &in, const La
   hipLaunchKernelGGL(fold, dim3(nunits), dim3(kFoldThreads), 0, st, s, out, lse, ws, w, unit0, nunits, grid, slot0);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  auto kern = attn_kernel<DT, D, WAVES, TQ>;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES * 64), 0, st, s, in, out, ws, w, unit0, nunits);
+  // with a spare query tile in the padded block the mean key rides in its first two rows
+  if (s.QT < WAVES * TQ) {
+    auto kern = attn_kernel<DT, D, WAVES, TQ, true>;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES * 64), 0, st, s, in, out, ws, w, unit0, nunits);
+  } else {
+    auto kern = attn_kernel<DT, D, WAVES, TQ, false>;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES * 64), 0, st, s, in, out, ws, w, unit0, nunits);
+  }
   return hipGetLastError();
 }
 
