@@ -82,6 +82,22 @@ def test_large_logits_move_the_softmax_offset_mid_run(scale):
     _run_and_check(wl, softmax_scale=scale)
 
 
+@pytest.mark.parametrize("name,over", [("c1", {}), ("c2", {}), ("c2", dict(intrinsic="knorm")), ("c1", dict(intrinsic="knorm"))])
+def test_zero_keys_are_normalised_to_the_zero_vector(name, over):
+    # a key of norm zero has no direction: its normalised key is the zero vector (it adds nothing to the mean key,
+    # its diversity score is 0, its key-norm score 0), in the window as among the candidates
+    wl = WL[name]
+    lay = synth.make_layer(wl, 0)
+    for i in (0, 5, wl.seq_len // 2, wl.seq_len - wl.window - 1, wl.seq_len - 1):
+        lay.K[:, :, i, :] = 0.0
+    lay.K[:, 0, 7, :] = 0.0
+    _say(f"[case] zero keys {wl.name} over={over}")
+    p, outs = H.run_compress(wl, [lay], **over)
+    st = H.check_layer(wl, lay, p, outs[0], **over)
+    _say(f"       checked {st['checked']} units: max score err {st['max_err']:.2e}, identical index sets {st['exact']}")
+    assert st["checked"] == wl.batch * wl.n_kv_heads
+
+
 def test_budget_edges():
     wl = WL["c1"]
     _run_and_check(wl, budget=wl.window)          # B' = 0: window only
