@@ -476,13 +476,21 @@ __global__ __launch_bounds__(kSelectThreads) void select_candidates_kernel(Shape
     pos_s[e] = cidx[(int64_t)h * kMaxCandPerHead + j];
   }
   __syncthreads();
-  // floor: rank inside the head by (key descending, position ascending)
+  // floor: rank inside the head by (key descending, position ascending).  Every list is in ascending
+  // position order, so among equal keys the entries before this one are the better ones.  No
+  // short-circuit operators: the loop body must stay free of branches (with them the loop took
+  // 52 of the kernel's 74 us on a 32K-token cache; a wave per candidate with ballots, or quarters of
+  // a list per thread with atomics, are no faster than this).
   for (int e = threadIdx.x; e < n; e += blockDim.x) {
-    const int h = e / M;
+    const int h = e / M, j = e - h * M;
     const uint32_t k = key_s[e];
-    const int p = pos_s[e];
+    const uint32_t *kh = key_s + h * M;
     int better = 0;
-    for (int o = h * M; o < (h + 1) * M; ++o) better += (key_s[o] > k || (key_s[o] == k && pos_s[o] < p)) ? 1 : 0;
+#pragma unroll 8
+    for (int o = 0; o < M; ++o) {
+      const uint32_t ko = kh[o];
+      better += (int)(ko > k) | ((int)(ko == k) & (int)(o < j));
+    }
     floor_s[e] = better < f;
   }
   __syncthreads();
