@@ -355,3 +355,45 @@ def test_very_long_video_cache_128k_tokens():
     wl = WL["c5"].with_(name="video-128k", batch=1, seq_len=64 + 256 * 510 + 64, text_suffix_start=64 + 256 * 510,
                         n_frames=256, budget_mode="fixed", budget=256)
     _run_and_check(wl, layer_ids=[0], units=[(0, 2)])
+
+
+def test_calls_on_two_streams_with_their_own_workspaces_match_the_serial_results():
+    """The library keeps no state between calls: two calls in flight on two streams of the caller
+    (default priority), each with its own workspace and outputs, give bit for bit what the same
+    calls give one after the other, and a call's results are complete once its own stream is."""
+    wl = WL["c2"].with_(name="two-streams", batch=2)
+    dev = "cuda:0"
+    sets = []
+    for first in (0, 2):
+        layers = [synth.make_layer(wl, l) for l in (first, first + 1)]
+        p = H.gpu_params(wl)
+        Ks = [H.to_device(wl, l.K, dev) for l in layers]
+        Vs = [H.to_device(wl, l.V, dev) for l in layers]
+        Qs = [H.to_device(wl, l.Q, dev) for l in layers]
+        outs = [B.alloc_layer_out(p, dev, scores=True) for _ in layers]
+        ws = B.alloc_workspace(p, len(layers), dev)
+        sets.append((B.PreparedCall(p, Ks, Vs, Qs, outs, ws), outs))
+    _say(f"[case] two streams {wl.name} dtype={wl.dtype} L=2+2 Bt={wl.batch}")
+
+    def snapshot(outs):
+        return [[t.clone() for t in (o.scores, o.redundancy, o.indices, o.counts, o.K_out, o.V_out)] for o in outs]
+
+    want = []
+    for call, outs in sets:
+        call.compress()
+        torch.cuda.synchronize()
+        want.append(snapshot(outs))
+        for o in outs:                                     # so that the concurrent run has to write everything again
+            for t in (o.scores, o.redundancy, o.indices, o.counts, o.K_out, o.V_out):
+                t.zero_()
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(3):
+        for (call, _), st in zip(sets, streams):
+            call.compress(stream=st)
+        for (call, outs), st, w in zip(sets, streams, want):
+            st.synchronize()                               # this call's stream only
+            for got_l, want_l in zip(snapshot(outs), w):
+                for g, x in zip(got_l, want_l):
+                    assert torch.equal(g, x), f"repetition {rep}: a call on its own stream differs from the serial run"
+    torch.cuda.synchronize()
