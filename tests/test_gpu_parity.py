@@ -397,3 +397,42 @@ def test_calls_on_two_streams_with_their_own_workspaces_match_the_serial_results
                 for g, x in zip(got_l, want_l):
                     assert torch.equal(g, x), f"repetition {rep}: a call on its own stream differs from the serial run"
     torch.cuda.synchronize()
+
+
+def test_a_call_captured_in_a_graph_replays_to_the_eager_results():
+    """A call allocates nothing, records no memset and never synchronises, so a caller can capture
+    it in a graph.  Three replays, with the outputs cleared by ordinary eager work and a
+    synchronisation between them, must each reproduce the eager results bit for bit."""
+    wl = WL["c2"].with_(name="graph", batch=2)
+    dev = "cuda:0"
+    layers = [synth.make_layer(wl, l) for l in (0, 1)]
+    p = H.gpu_params(wl)
+    Ks = [H.to_device(wl, l.K, dev) for l in layers]
+    Vs = [H.to_device(wl, l.V, dev) for l in layers]
+    Qs = [H.to_device(wl, l.Q, dev) for l in layers]
+    outs = [B.alloc_layer_out(p, dev, scores=True) for _ in layers]
+    ws = B.alloc_workspace(p, len(layers), dev)
+    call = B.PreparedCall(p, Ks, Vs, Qs, outs, ws)
+    _say(f"[case] graph capture {wl.name} dtype={wl.dtype} L=2 Bt={wl.batch}")
+    fields = lambda o: (o.scores, o.redundancy, o.indices, o.counts, o.K_out, o.V_out)
+    call.compress()
+    torch.cuda.synchronize()
+    want = [[t.clone() for t in fields(o)] for o in outs]
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        call.compress(side)                                # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            call.compress(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for o in outs:
+            for t in fields(o):
+                t.zero_()                                  # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for o, w in zip(outs, want):
+            for g, x in zip(fields(o), w):
+                assert torch.equal(g, x), f"replay {rep} differs from the eager call"
