@@ -33,7 +33,7 @@ MFMA_BF16_PEAK = 2.5e15
 # HBM bytes per launch (fetched + written) of the two streaming kernels on the default workload, from
 # rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this command scaled by a 1 GiB copy kernel (the summary
 # with the commands is under profiles/).  Other workloads report no measured traffic.
-MEASURED_TRAFFIC = {("c3", 28, "stats"): 513.6e6, ("c3", 28, "attn"): 289.9e6}
+MEASURED_TRAFFIC = {("c3", 28, "stats"): 513.6e6, ("c3", 28, "attn"): 278.3e6}
 
 _LAYERS = None
 _WL = None
