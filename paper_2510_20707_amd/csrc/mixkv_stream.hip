@@ -622,6 +622,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
   __shared__ uint4 kbar_s[NCHK * 4];                         // mean-key rows 0/1 x halves, 16-byte pieces
   __shared__ float cs_s[2 * WAVES * CH];                     // [2][WAVES][CH] partial column sums
   __shared__ int lim_s[WAVES * TQ * 32];                     // last key each query row attends to
+  __shared__ float kd_s[SPARE ? 1 : 2 * WAVES * CH];         // [2][WAVES][CH] partial K_i . Kbar (no spare tile)
 
   const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps its address math scalar
@@ -703,26 +704,34 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
         float a = 0.f;
         for (int wv = 0; wv < WAVES; ++wv) a += cs_s[(pb * WAVES + wv) * CH + i];
         if (key < Nc) araw[key] = a;
+        if constexpr (!SPARE) {
+          float d = 0.f;
+          for (int wv = 0; wv < WAVES; ++wv) d += kd_s[(pb * WAVES + wv) * CH + i];
+          if (key < Nc) kdot[key] = d;
+        }
       }
     };
 
-    // Where the mean key has no spare query rows, every WAVES-th key tile also meets a separate
-    // mean-key tile (the waves take turns): K_i . Kbar for the keys of the tile whose fragments are kf.
-    auto mean_key_dots = [&](const Frag (&kf)[NCHK]) {
+    // Where the mean key has no spare query rows it is a tile of its own (rows 0 and 1), and its
+    // contraction with a key tile is dealt over the waves by contraction chunk: wave w takes the
+    // NOWN chunks w, w + WAVES, ... (none if there are fewer chunks than waves: its mean-key rows
+    // are then zero), so every wave issues the same few extra matrix instructions in every step,
+    // at fixed places of the instruction stream (the chunk is a run-time index into LDS, the code
+    // has no branch), and the waves' partial dot products meet in LDS like the column sums.
+    constexpr int NOWN = NCHK >= WAVES ? NCHK / WAVES : 1;
+    auto own_chunk = [&](int j) { return (wave + j * WAVES) % NCHK; };
+    auto mean_key_frag = [&](int j) {
+      Frag kbf;
+      kbf.q = kbar_s[(own_chunk(j) * 2 + half) * 2 + (l32 & 1)];
+      if (l32 >= 2 || wave >= NCHK) kbf.q = make_uint4(0, 0, 0, 0);
+      return kbf;
+    };
+    // Scores of the key tile in image `img` into accN: NCHK fragment reads, each feeding the TQ chains
+    // (and this wave's share of the mean-key tile: kdN).
+    auto scores = [&](const uint4 *img, f32x16 (&accN)[TQ], float &kdN) {
       f32x16 acd;
 #pragma unroll
       for (int i = 0; i < 16; ++i) acd[i] = 0.f;
-#pragma unroll
-      for (int c = 0; c < NCHK; ++c) {
-        Frag kbf;
-        kbf.q = kbar_s[(c * 2 + half) * 2 + (l32 & 1)];
-        if (l32 >= 2) kbf.q = make_uint4(0, 0, 0, 0);
-        acd = mma<DT>(kbf, kf[c], acd);
-      }
-      return acd[0] + acd[1];
-    };
-    // Scores of the key tile in image `img` into accN: NCHK fragment reads, each feeding the TQ chains.
-    auto scores = [&](const uint4 *img, f32x16 (&accN)[TQ]) {
 #pragma unroll
       for (int q = 0; q < TQ; ++q)
 #pragma unroll
@@ -733,6 +742,15 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
         kf.q = read_key_frag<DT, D>(img, 0, c, l32, half);
 #pragma unroll
         for (int q = 0; q < TQ; ++q) accN[q] = mma<DT>(qf[q][c], kf, accN[q]);
+      }
+      if constexpr (!SPARE) {
+#pragma unroll
+        for (int j = 0; j < NOWN; ++j) {
+          Frag kx;
+          kx.q = read_key_frag<DT, D>(img, 0, own_chunk(j), l32, half);
+          acd = mma<DT>(mean_key_frag(j), kx, acd);
+        }
+        kdN = acd[0] + acd[1];
       }
     };
 
@@ -767,10 +785,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
       auto body = [&](auto mask_c) {
         constexpr bool MASK = decltype(mask_c)::value;
         __builtin_amdgcn_sched_barrier(0);
-        // ---- K_i . Kbar: rows 0 and 1 (half 0) of the spare tile (taken before the mask touches
-        // them), or what the separate mean-key tile left a step ago
-        float kd = kdC;
-        bool kd_mine = t % WAVES == wave;
+        // ---- K_i . Kbar: rows 0 and 1 (half 0) of the spare tile (taken before the mask touches them)
+        float kd = kdC;                                  // no spare tile: this wave's share, from a step ago
+        bool kd_mine = false;
         if constexpr (SPARE) {
           const float kd0 = accC[0][0] + accC[0][1], kd1 = accC[TQ - 1][0] + accC[TQ - 1][1];
           kd = kb_q == 0 ? kd0 : kd1;
@@ -791,25 +808,34 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
         // runs.  The fragment of the next contraction chunk is read one chunk ahead.
         constexpr int EPS = 16 / NCHK;                   // weights per slice
         static_assert(16 % NCHK == 0, "a whole number of weights per matrix instruction");
-        // Fragments: read one contraction chunk ahead into two rotating registers sets; where a
-        // separate mean-key tile follows and registers allow (one query tile per wave), all NCHK
-        // are read up front and kept for it.
-        constexpr bool HOLD = !SPARE && TQ == 1;
-        constexpr int NF = HOLD ? NCHK : 2;
-        Frag kfr[NF];
-#pragma unroll
-        for (int c = 0; c < (HOLD ? NCHK : 1); ++c) kfr[c].q = read_key_frag<DT, D>(imgn, 0, c, l32, half);
+        // Fragments are read one contraction chunk ahead into two rotating register sets.
+        Frag kfr[2];
+        kfr[0].q = read_key_frag<DT, D>(imgn, 0, 0, l32, half);
         float cs4[4];                                    // four chains: the adds do not wait on each other
+        f32x16 acd;
+        Frag kx, kbx;                                    // this wave's next chunk of the mean-key tile
+        if constexpr (!SPARE) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) acd[i] = 0.f;
+        }
 #pragma unroll
         for (int c = 0; c < NCHK; ++c) {
-          if (!HOLD && c + 1 < NCHK) kfr[(c + 1) % NF].q = read_key_frag<DT, D>(imgn, 0, c + 1, l32, half);
+          if (c + 1 < NCHK) kfr[(c + 1) & 1].q = read_key_frag<DT, D>(imgn, 0, c + 1, l32, half);
+          if constexpr (!SPARE) {
+            // own chunk j is read under slice (j + 1) * NCHK / NOWN - 2 and used one slice later
+            if ((c + 2) % (NCHK / NOWN) == 0) {
+              const int j = (c + 2) / (NCHK / NOWN) - 1;
+              kx.q = read_key_frag<DT, D>(imgn, 0, own_chunk(j), l32, half);
+              kbx = mean_key_frag(j);
+            }
+          }
 #pragma unroll
           for (int q = 0; q < TQ; ++q) {
             if (c == 0) {
 #pragma unroll
               for (int i = 0; i < 16; ++i) accN[q][i] = 0.f;
             }
-            accN[q] = mma<DT>(qf[q][c], kfr[c % NF], accN[q]);
+            accN[q] = mma<DT>(qf[q][c], kfr[c & 1], accN[q]);
 #pragma unroll
             for (int j = 0; j < EPS; ++j) {
               const int n = (c * TQ + q) * EPS + j, qq = n / 16, i = n % 16;
@@ -818,22 +844,23 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
             }
             __builtin_amdgcn_sched_barrier(0);
           }
-        }
-        if constexpr (HOLD) {
-          if ((t + 1) % WAVES == wave) kdN = mean_key_dots(kfr);
-        } else if constexpr (!SPARE) {
-          if ((t + 1) % WAVES == wave) {
-            Frag kfa[NCHK];
-#pragma unroll
-            for (int c = 0; c < NCHK; ++c) kfa[c].q = read_key_frag<DT, D>(imgn, 0, c, l32, half);
-            kdN = mean_key_dots(kfa);
+          if constexpr (!SPARE) {
+            if ((c + 1) % (NCHK / NOWN) == 0) {
+              acd = mma<DT>(kbx, kx, acd);
+              __builtin_amdgcn_sched_barrier(0);
+            }
           }
         }
+        if constexpr (!SPARE) kdN = acd[0] + acd[1];
         float colsum = (cs4[0] + cs4[1]) + (cs4[2] + cs4[3]);
         colsum += __shfl_xor(colsum, 32);
         __builtin_amdgcn_sched_barrier(0);
         if (half == 0) cs[k * 32 + l32] = colsum;
-        if (kd_mine && half == 0 && key < Nc) kdot[key] = kd;
+        if constexpr (SPARE) {
+          if (kd_mine && half == 0 && key < Nc) kdot[key] = kd;
+        } else {
+          if (half == 0) kd_s[((g & 1) * WAVES + wave) * CH + k * 32 + l32] = kd;
+        }
       };
       if (tb + 31 > free_limit) body(std::true_type{});
       else body(std::false_type{});
@@ -841,15 +868,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
 
     f32x16 accA[TQ], accB[TQ];
     float kdA = 0.f, kdB = 0.f;
-    scores(kring, accA);                                // tile 0
-    if constexpr (!SPARE) {
-      if (wave == 0) {
-        Frag kfa[NCHK];
-#pragma unroll
-        for (int c = 0; c < NCHK; ++c) kfa[c].q = read_key_frag<DT, D>(kring, 0, c, l32, half);
-        kdA = mean_key_dots(kfa);
-      }
-    }
+    scores(kring, accA, kdA);                           // tile 0
     for (int t = 0; t < nt; t += kRing) {
       step(std::integral_constant<int, 0>{}, t, accA, accB, kdA, kdB);
       if (t + 1 < nt) step(std::integral_constant<int, 1>{}, t + 1, accB, accA, kdB, kdA);
