@@ -65,6 +65,12 @@ def test_c2_variants(over):
     ("bf16", 128, 333, 32, 16, 2, 40),     # G*W = 256 rows = 8 tiles, two chunks
     ("bf16", 128, 2049, 17, 3, 1, 64),     # one key past a chunk boundary, odd window
     ("f32", 64, 64, 31, 2, 1, 40),         # window half of the sequence
+    # no spare query tile for the mean key in pass 2 (G*W a whole number of wave slots): its tile is
+    # dealt over the waves by contraction chunk, 1, 2 or 4 chunks per wave
+    ("bf16", 64, 900, 32, 4, 1, 64),       # G*W = 128: 4 tiles on 4 waves, 4 chunks
+    ("f32", 64, 700, 32, 8, 2, 80),        # the same in fp32: 8 chunks
+    ("f32", 128, 600, 32, 4, 1, 64),       # fp32, D = 128: 16 chunks
+    ("bf16", 128, 1200, 32, 16, 1, 64),    # G*W = 512: 16 tiles on 8 waves x 2
 ])
 def test_ragged_shapes(dtype, D, N, W, Hq, Hkv, B):
     wl = WL["c2"].with_(name="ragged", dtype=dtype, head_dim=D, seq_len=N, window=W, n_q_heads=Hq, n_kv_heads=Hkv,
