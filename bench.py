@@ -113,8 +113,8 @@ def algorithmic_bytes(wl, budget, scores_out, reads_v=True):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="c3", choices=sorted(synth.WORKLOADS))
     ap.add_argument("--budget", type=int, default=None)
     ap.add_argument("--layers", type=int, default=None, help="use only the first L layers (not the headline)")
