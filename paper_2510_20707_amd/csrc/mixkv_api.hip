@@ -235,7 +235,11 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
       const int64_t slot0 = (int64_t)(l0 / kLayersPerLaunch) * (kMaxStreamGrid + kLayersPerLaunch * s.units_per_layer);
       const bool given_lse = in[0].window_lse != nullptr;
       ok(timed(0, [&] { return launch_stats(s, params->dtype, ti, ws, w, unit0, nunits, grid, slot0, given_lse, stream); })) &&
-          ok(timed(1, [&] { return launch_attn(s, params->dtype, ti, to, tl, ws, w, unit0, nunits, grid, slot0, stream); })) &&
+          ok(timed(1, [&] {
+            hipError_t e = launch_fold(s, params->dtype, to, tl, ws, w, unit0, nunits, grid, s.nchunks, slot0, stream);
+            if (e != hipSuccess) return e;
+            return launch_attn(s, params->dtype, ti, to, tl, ws, w, unit0, nunits, grid, slot0, stream);
+          })) &&
           ok(timed(2, [&] {
             return fused ? launch_mixsel(s, fused_select || cand_m > 0, to, ws, w, unit0, nunits, ti,
                                          fused_gather ? eb : 0, cand_m, budgets_l0, stream)

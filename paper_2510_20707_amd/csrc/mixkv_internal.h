@@ -79,6 +79,10 @@ int stream_grid(const Shape &s, int nunits, int num_cus);
 // statistics only; `lse` then holds them per layer (all null otherwise).
 hipError_t launch_stats(const Shape &s, int dtype, const LayerInTable &in, char *ws, const Workspace &w, int64_t unit0,
                         int nunits, int grid, int64_t slot0, bool given_lse, hipStream_t st);
+// Folds the first pass's per-run partials per unit (exponent offsets, mean key, redundancy).  `grid`
+// and `items_per_unit` describe the work split of the first-pass kernel that wrote them.
+hipError_t launch_fold(const Shape &s, int dtype, const LayerOutTable &out, const LseTable &lse, char *ws, const Workspace &w,
+                       int64_t unit0, int nunits, int grid, int items_per_unit, int64_t slot0, hipStream_t st);
 hipError_t launch_attn(const Shape &s, int dtype, const LayerInTable &in, const LayerOutTable &out, const LseTable &lse,
                        char *ws, const Workspace &w, int64_t unit0, int nunits, int grid, int64_t slot0, hipStream_t st);
 hipError_t launch_mix(const Shape &s, const LayerInTable &in, const LayerOutTable &out, char *ws, const Workspace &w,
