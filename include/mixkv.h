@@ -39,7 +39,7 @@
 extern "C" {
 #endif
 
-#define MIXKV_VERSION 8
+#define MIXKV_VERSION 9
 #define MIXKV_MAX_LAYERS 128      /* layers per call */
 #define MIXKV_MAX_WINDOW 64
 #define MIXKV_MAX_GROUP_ROWS 512  /* G * W */
@@ -181,6 +181,25 @@ mixkv_status mixkv_select(const mixkv_params *params, mixkv_layer_out *out, int3
  */
 mixkv_status mixkv_compress(const mixkv_params *params, const mixkv_layer_in *in, mixkv_layer_out *out,
                             int32_t n_layers, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * mixkv_compress for callers that can neither allocate device memory nor hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * workspace is an array of MIXKV_STATIC_SCRATCH_BYTES inside the library's own device data (every
+ * GPU the library runs on holds one from load until the process ends); inputs and outputs are the
+ * caller's as in mixkv_compress, and so are the results, bit for bit.  The call allocates and
+ * frees nothing.  Shapes whose workspace (mixkv_workspace_size) exceeds the array return
+ * MIXKV_ERR_WORKSPACE_TOO_SMALL and touch nothing: 32 MiB hold the whole 28-layer 8K cache of the
+ * 28Q/4KV shape in one call; larger caches go layer group by layer group.  Nothing in the array has
+ * to start at zero (every word is written before it is read within a call) and it keeps the last
+ * call's contents.  All calls on one GPU share the array: calls that overlap in time on one GPU
+ * (different streams, or different host threads) race; serialise them or use mixkv_compress with
+ * separate workspaces.  The first call on a device looks the array's address up once
+ * (hipGetSymbolAddress); make that call outside a graph capture.
+ */
+#define MIXKV_STATIC_SCRATCH_BYTES (32u << 20)
+mixkv_status mixkv_compress_static(const mixkv_params *params, const mixkv_layer_in *in, mixkv_layer_out *out,
+                                   int32_t n_layers, void *hip_stream);
 
 /*
  * Profiling aid: mixkv_compress with every kernel launch bracketed by a pair of HIP events on

@@ -91,6 +91,8 @@ def lib() -> C.CDLL:
         L.mixkv_select.restype = C.c_int
         L.mixkv_compress.argtypes = [pp, pin, pout, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
         L.mixkv_compress.restype = C.c_int
+        L.mixkv_compress_static.argtypes = [pp, pin, pout, C.c_int32, C.c_void_p]
+        L.mixkv_compress_static.restype = C.c_int
         L.mixkv_compress_profiled.argtypes = [pp, pin, pout, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p,
                                               C.POINTER(C.c_float)]
         L.mixkv_compress_profiled.restype = C.c_int
@@ -241,6 +243,15 @@ def mixkv_compress(p: MixkvParams, Ks, Vs, Qs, outs: Sequence[LayerOut], workspa
     wp, wb = _ws(workspace)
     _check(lib().mixkv_compress(C.byref(p), _in_array(Ks, Vs, Qs, r_given, window_lse), _out_array(outs), len(outs), wp, wb,
                                 _stream(stream)), "mixkv_compress")
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def mixkv_compress_static(p: MixkvParams, Ks, Vs, Qs, outs: Sequence[LayerOut], stream=None, r_given=None, window_lse=None):
+    """mixkv_compress on the library's own static workspace (no workspace argument, no allocation)."""
+    _check(lib().mixkv_compress_static(C.byref(p), _in_array(Ks, Vs, Qs, r_given, window_lse), _out_array(outs), len(outs),
+                                       _stream(stream)), "mixkv_compress_static")
 
 
 def mixkv_similarity_workspace_size(p: MixkvParams, n_layers: int, block: int) -> int:

@@ -1,6 +1,7 @@
 // Host side of libmixkv: argument validation, workspace carve-up and the launch sequence.
 #include <cmath>
 #include <cstring>
+#include <mutex>
 
 #include "mixkv_internal.h"
 
@@ -258,6 +259,29 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
   return result != MIXKV_OK ? result : fin;
 }
 
+// The workspace of mixkv_compress_static: one array per GPU the library runs on, in the code object's
+// own data, so it exists from the moment the library is loaded until the process ends.  In host code
+// the array's name is only a handle for the symbol lookup: the device address is asked for once per
+// device (with that device current) and everything else uses the address.
+static __device__ __align__(256) unsigned char scratch[MIXKV_STATIC_SCRATCH_BYTES];
+
+static mixkv_status static_scratch(void **ptr) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void *addr[kMaxDevices] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MIXKV_ERR_HIP;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!addr[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return MIXKV_ERR_HIP;
+    if (reinterpret_cast<uintptr_t>(p) & 255u) return MIXKV_ERR_HIP;
+    addr[dev] = p;
+  }
+  *ptr = addr[dev];
+  return MIXKV_OK;
+}
+
 }  // namespace mixkv
 
 extern "C" {
@@ -295,6 +319,22 @@ mixkv_status mixkv_compress_profiled(const mixkv_params *params, const mixkv_lay
   if (!stage_ms) return MIXKV_ERR_INVALID_ARG;
   return mixkv::run(params, in, out, n_layers, workspace, workspace_bytes, hip_stream,
                     mixkv::kScore | mixkv::kSelect | mixkv::kGather, stage_ms);
+}
+
+mixkv_status mixkv_compress_static(const mixkv_params *params, const mixkv_layer_in *in, mixkv_layer_out *out,
+                                   int32_t n_layers, void *hip_stream) {
+  mixkv::Shape s;
+  mixkv_status st = mixkv::make_shape(params, &s);
+  if (st != MIXKV_OK) return st;
+  if (n_layers < 1 || n_layers > MIXKV_MAX_LAYERS) return MIXKV_ERR_INVALID_ARG;
+  mixkv::Workspace w;
+  mixkv::carve_workspace(s, (int64_t)n_layers * s.units_per_layer, &w);
+  if (w.total > (size_t)MIXKV_STATIC_SCRATCH_BYTES) return MIXKV_ERR_WORKSPACE_TOO_SMALL;
+  void *ws = nullptr;
+  st = mixkv::static_scratch(&ws);
+  if (st != MIXKV_OK) return st;
+  return mixkv::run(params, in, out, n_layers, ws, MIXKV_STATIC_SCRATCH_BYTES, hip_stream,
+                    mixkv::kScore | mixkv::kSelect | mixkv::kGather);
 }
 
 const char *mixkv_stage_name(int32_t stage) {
