@@ -5,8 +5,13 @@ One step = one mixkv_compress call over a whole synthetic cache (all layers, all
 score -> mix -> top-B -> gather.  Default workload: the Qwen2-VL-7B-shaped 28-layer, 8K-token
 cache (workload "c3"), budget 64.  Prints ONE JSON line.
 
-  value        cached tokens compressed per second (batch * N / step time); inputs resident in HBM
-  roofline     the dominant kernel's algorithmic bytes per launch / its average duration, measured
+  ms_per_step  median of the timed steps, each bracketed by HIP events on the launch stream (the
+               wall-clock mean over the same steps is reported beside it); inputs resident in HBM,
+               three copies of the cache used round-robin so that every step streams from HBM
+  value        cached tokens compressed per second: batch * N / ms_per_step
+  other_budgets_and_warm   the same figure at budgets 128 / 256 / 512 and, for the default budget, on
+               a single copy of the cache (default workload only)
+  roofline     the dominant kernel's algorithmic bytes per launch / its median duration, measured
                with HIP events on the launch stream (mixkv_compress_profiled), against 8 TB/s
   cpu_baseline the float64 oracle on the same inputs on the host cores (process pool), before the
                GPU is touched
@@ -31,9 +36,56 @@ from paper_2510_20707_amd import synth  # noqa: E402
 HBM_PEAK = 8.0e12
 MFMA_BF16_PEAK = 2.5e15
 # HBM bytes per launch (fetched + written) of the two streaming kernels on the default workload, from
-# rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this command scaled by a 1 GiB copy kernel (the summary
-# with the commands is under profiles/).  Other workloads report no measured traffic.
-MEASURED_TRAFFIC = {("c3", 28, "stats"): 513.6e6, ("c3", 28, "attn"): 278.3e6}
+# rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this command scaled by a 1 GiB copy kernel (summary and
+# commands: profiles/mixkv_compress_c3_b64_hbm_traffic.md).  A profile describes the kernels it was
+# taken on: the record carries a hash of their sources, and the bench line reports the figure only for
+# the profiled command (default workload, budget and variant, three copies) and unchanged sources.
+PROFILED_TRAFFIC = {
+    "sources": ["mixkv_stream.hip", "mixkv_stream.h"],
+    "sources_sha256": "unset",
+    "kernels": {"stats": ("stats_kernel<bf16,128,8,1>", 513.6e6), "attn": ("attn_kernel<bf16,128,4,2,spare>", 278.3e6)},
+}
+
+
+def kernel_sources_sha256(names):
+    import hashlib
+    h = hashlib.sha256()
+    for n in names:
+        with open(os.path.join(ROOT, "paper_2510_20707_amd", "csrc", n), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def profiled_traffic(args, wl, stage):
+    """The profiled HBM bytes per launch of `stage`'s kernel, or None if this run is not the profiled one."""
+    default = (args.workload == "c3" and wl.n_layers == 28 and args.budget in (None, 64) and args.copies == 3
+               and args.intrinsic == "vnorm" and args.mix == "head_adaptive" and not args.given_lse
+               and args.budgets == "config")
+    if not default or stage not in PROFILED_TRAFFIC["kernels"]:
+        return None
+    if kernel_sources_sha256(PROFILED_TRAFFIC["sources"]) != PROFILED_TRAFFIC["sources_sha256"]:
+        return None
+    name, nbytes = PROFILED_TRAFFIC["kernels"][stage]
+    return {"kernel": name, "bytes_per_launch": nbytes, "profile": "profiles/mixkv_compress_c3_b64_hbm_traffic.md"}
+
+
+def timed_steps(calls, steps, warmup, stream):
+    """`warmup` untimed steps, then `steps` steps each bracketed by HIP events on the launch stream
+    (no host synchronisation in between).  Returns (wall-clock mean, per-step event times), in ms."""
+    import torch
+    for i in range(warmup):
+        calls[i % len(calls)].compress(stream)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    evs[0].record(stream)
+    for i in range(steps):
+        calls[i % len(calls)].compress(stream)
+        evs[i + 1].record(stream)
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / steps * 1e3
+    return wall, [evs[i].elapsed_time(evs[i + 1]) for i in range(steps)]
+
 
 _LAYERS = None
 _WL = None
@@ -54,21 +106,6 @@ def _oracle_layer(l):
     out = O.compress_layer(_LAYERS[l].K, _LAYERS[l].V, _LAYERS[l].Q, p, None if _RGIVEN is None else _RGIVEN[l],
                            None if hb is None else hb[l], None if _LSE is None else _LSE[l].astype(np.float64))
     return l, [[i.astype(np.int32) for i in row] for row in out["indices"]], out["scores"].astype(np.float32)
-
-
-def window_lse(wl, lay):
-    """Stand-in for what the prefill attention kernel hands over: log-sum-exp of the window rows'
-    logits over the keys each row attends to (causal), float32 [batch, Hq, W]."""
-    n, w, g = wl.seq_len, wl.window, wl.group
-    out = np.empty((wl.batch, wl.n_q_heads, w), dtype=np.float32)
-    vis = np.arange(n)[None, :] <= (n - w + np.arange(w))[:, None]
-    for b in range(wl.batch):
-        for h in range(wl.n_q_heads):
-            s = wl.softmax_scale * (lay.Q[b, h].astype(np.float64) @ lay.K[b, h // g].astype(np.float64).T)
-            s = np.where(vis, s, -np.inf)
-            m = s.max(axis=1)
-            out[b, h] = m + np.log(np.exp(s - m[:, None]).sum(axis=1))
-    return out
 
 
 def cpu_baseline(wl, layers, budget, max_layers, variant, r_given, head_budgets, lse):
@@ -113,14 +150,16 @@ def algorithmic_bytes(wl, budget, scores_out, reads_v=True):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=500)
-    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c3", choices=sorted(synth.WORKLOADS))
     ap.add_argument("--budget", type=int, default=None)
     ap.add_argument("--layers", type=int, default=None, help="use only the first L layers (not the headline)")
     ap.add_argument("--copies", type=int, default=3, help="distinct device copies of the cache, used round-robin")
     ap.add_argument("--cpu-layers", type=int, default=28, help="layers the oracle baseline runs (0 = skip)")
     ap.add_argument("--no-parity", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true",
+                    help="skip the extra figures of the default workload (budgets 128 / 256 / 512 and the warm run)")
     ap.add_argument("--intrinsic", default="vnorm", choices=["none", "vnorm", "knorm"],
                     help="intrinsic importance; anything but vnorm is an ablation variant, not the headline")
     ap.add_argument("--mix", default="head_adaptive", choices=["head_adaptive", "sum", "div_only", "imp_only", "given_r"],
@@ -166,7 +205,7 @@ def main():
         head_budgets = np.repeat(per_layer[:, None], wl.n_kv_heads, axis=1)
     budget_mode = wl.budget_mode if head_budgets is None else "per_head"
     capacity = budget if head_budgets is None else int(head_budgets.max())      # rows per head in the output buffers
-    lse = [window_lse(wl, lay) for lay in layers] if args.given_lse else None
+    lse = [synth.window_lse(wl, lay) for lay in layers] if args.given_lse else None
     cpu, oracle_res = (None, {})
     if args.cpu_layers > 0:
         cpu, oracle_res = cpu_baseline(wl, layers, budget, args.cpu_layers, (args.intrinsic, args.mix), r_given,
@@ -204,22 +243,17 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for i in range(args.warmup):
-        calls[i % len(calls)].compress(stream)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        calls[i % len(calls)].compress(stream)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
+    wall_ms, per_step = timed_steps(calls, args.steps, args.warmup, stream)
+    ms_per_step = float(np.median(per_step))          # the headline: median of the event-timed steps
+    dt = ms_per_step * 1e-3 * args.steps                # (kept in seconds for the rates below)
 
     # per-kernel durations with HIP events on the launch stream, same inputs, same round-robin
-    stage_ms = {}
+    stage_runs = {}
     nprof = max(3, min(args.steps, 20))
     for i in range(nprof):
         for k, v in calls[i % len(calls)].compress_profiled(stream).items():
-            stage_ms[k] = stage_ms.get(k, 0.0) + v / nprof
+            stage_runs.setdefault(k, []).append(v)
+    stage_ms = {k: float(np.median(v)) for k, v in stage_runs.items()}      # median over the profiled calls
 
     parity = None
     if oracle_res and not args.no_parity:
@@ -288,6 +322,33 @@ def main():
                "achieved_GBps": sim_bytes / sim_s / 1e9, "hbm_frac": sim_bytes / sim_s / HBM_PEAK,
                "kernels": "blocksum_kernel + blockgram_kernel, HIP events on the launch stream"}
     reads_v = args.intrinsic == "vnorm"
+    # The other figures the workload definition asks for, from the same process: the fixed budgets
+    # 128 / 256 / 512 (cold: the copies of the cache used round-robin) and the default budget warm
+    # (one copy, so whatever the chip's caches keep between steps stays).  Each is the median of
+    # `steps` event-timed steps after `warmup`.
+    sweep = None
+    if (not args.no_sweep and args.workload == "c3" and not args.layers and head_budgets is None and not args.given_lse
+            and args.intrinsic == "vnorm" and args.mix == "head_adaptive" and wl.budget_mode == "fixed"):
+        sweep = {}
+        nsteps, nwarm = max(20, args.steps), max(3, args.warmup)
+
+        def figure(bud, cps):
+            pb = B.make_params(wl.dtype, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.seq_len, wl.window, bud,
+                               pool=wl.pool, pool_kernel=wl.pool_kernel, softmax_scale=wl.softmax_scale, eps=wl.eps,
+                               budget_mode="fixed", budget_floor=wl.budget_floor)
+            ob = [B.alloc_layer_out(pb, dev, scores=False, redundancy=True) for _ in layers]
+            wb = B.alloc_workspace(pb, len(layers), dev)
+            cb = [B.PreparedCall(pb, [x[0] for x in c], [x[1] for x in c], [x[2] for x in c], ob, wb) for c in cps]
+            wall, per = timed_steps(cb, nsteps, nwarm, stream)
+            med = float(np.median(per))
+            nbytes = algorithmic_bytes(wl, bud, scores_out=False, reads_v=True) * wl.n_units
+            return {"ms_per_step": med, "ms_per_step_wall_mean": wall, "tokens_per_s": wl.batch * wl.seq_len / (med * 1e-3),
+                    "hbm_frac_end_to_end": nbytes / (med * 1e-3) / HBM_PEAK, "steps": nsteps, "copies": len(cps)}
+
+        for bud in (128, 256, 512):
+            if bud != budget:
+                sweep[f"B={bud}"] = figure(bud, copies)
+        sweep[f"B={budget}, warm"] = figure(budget, copies[:1])
     bytes_step = algorithmic_bytes(wl, budget, scores_out=False, reads_v=reads_v) * units
     dom = max(("stats", "attn"), key=lambda k: stage_ms.get(k, 0.0))
     kv_bytes = wl.seq_len * wl.head_dim * e
@@ -300,6 +361,8 @@ def main():
         "value": wl.batch * wl.seq_len / (dt / args.steps),
         "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "ms_per_step_stat": "median of the steps, each timed with HIP events on the launch stream",
+        "ms_per_step_wall_mean": wall_ms, "ms_per_step_min": float(min(per_step)), "ms_per_step_max": float(max(per_step)),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.n_layers} layers x {wl.n_q_heads}Q/{wl.n_kv_heads}KV heads, D={wl.head_dim}, "
@@ -316,8 +379,10 @@ def main():
         "roofline": {"bound": "hbm", "kernel": dom + "_kernel", "achieved": dom_bytes / dom_s / 1e9,
                      "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": dom_bytes / dom_s / HBM_PEAK,
                      "algorithmic_bytes": dom_bytes, "avg_launch_us": dom_s * 1e6,
-                     "traffic": MEASURED_TRAFFIC.get((wl.name, wl.n_layers, dom)) if reads_v else None},
+                     "traffic": (profiled_traffic(args, wl, dom) or {}).get("bytes_per_launch"),
+                     "traffic_source": profiled_traffic(args, wl, dom)},
         "cpu_baseline": cpu,
+        "other_budgets_and_warm": sweep,
         "similarity": sim,
         "decode": dec,
         "parity_vs_oracle": parity,

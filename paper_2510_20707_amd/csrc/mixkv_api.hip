@@ -95,6 +95,22 @@ static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 enum Stage { kScore = 1, kSelect = 2, kGather = 4 };
 
+// Compute units of the current device (0 on failure); asked of the runtime once per device.
+static int compute_units() {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static int cus[kMaxDevices] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 0;
+  std::lock_guard<std::mutex> lock(mu);
+  if (cus[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) return 0;
+    cus[dev] = n;
+  }
+  return cus[dev];
+}
+
 // Optional per-kernel timing: each launch is bracketed by a pair of events on the call's stream.
 struct StageTimer {
   hipStream_t stream;
@@ -183,12 +199,7 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
   char *ws = reinterpret_cast<char *>(workspace);
   int num_cus = 0;
-  if (stages & kScore) {
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&num_cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || num_cus < 1)
-      return MIXKV_ERR_HIP;
-  }
+  if ((stages & kScore) && (num_cus = compute_units()) < 1) return MIXKV_ERR_HIP;
   const int32_t *budgets_dev = nullptr;
   if (stage_budgets) {
     int32_t *dst = reinterpret_cast<int32_t *>(ws + w.budgets);

@@ -13,6 +13,8 @@
 // Paper: Sec. 3.2 Eq. 2 (importance = attention + scaled value norm), Sec. 3.3 (min-max and mean
 // matching of the diversity, Eq. 5 mix), Sec. 3.1 / Algorithm 1 (TopB with B' = B - W); Sec. 4.3 /
 // Table 4 for the variants (key-norm intrinsic score, un-weighted and one-sided mixes, given weights).
+#include <mutex>
+
 #include "mixkv_internal.h"
 #include "mixkv_wave.h"
 
@@ -423,22 +425,49 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
 
 // Largest sequence the fused kernel handles: 32 candidates per thread, and the raw attention row
 // must fit in LDS next to the scratch.
-bool mixsel_supported(const Shape &s) { return s.Nc <= kMsMaxThreads * 32 && (size_t)(s.Nc + s.Nc / 32 + 1) * 4 <= 140 * 1024; }
+constexpr int kMsMaxLds = 140 * 1024;
+
+// Raises a kernel's dynamic-LDS limit to kMsMaxLds the first time it is launched on a device.
+struct LdsLimitOnce {
+  static constexpr int kMaxDevices = 64;
+  std::mutex mu;
+  bool done[kMaxDevices] = {};
+  hipError_t raise(const void *kern) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!done[dev]) {
+      e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMsMaxLds);
+      if (e != hipSuccess) return e;
+      done[dev] = true;
+    }
+    return hipSuccess;
+  }
+};
+bool mixsel_supported(const Shape &s) { return s.Nc <= kMsMaxThreads * 32 && (size_t)(s.Nc + s.Nc / 32 + 1) * 4 <= (size_t)kMsMaxLds; }
 
 template <int THREADS, int EPT>
 static hipError_t launch_mixsel_e(const Shape &s, bool select, const LayerOutTable &out, char *ws, const Workspace &w,
                                   int64_t unit0, int nunits, const LayerInTable &in, int gather_eb, int cand_m,
                                   const int32_t *budgets, hipStream_t st) {
   const size_t lds = (size_t)(s.Nc + s.Nc / 32 + 1) * 4;
+  // The kernels may use more dynamic LDS than the default limit.  The limit is a property of the
+  // kernel, shared by every stream and thread, so it is raised once, to the most mixsel_supported
+  // admits, once per device, and never touched again (a per-launch value could be lowered by another
+  // thread between this thread's call and its launch).
   if (select) {
     auto kern = mixsel_kernel<THREADS, EPT, true>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
+    static LdsLimitOnce once;
+    const hipError_t attr = once.raise(reinterpret_cast<const void *>(kern));
+    if (attr != hipSuccess) return attr;
     hipLaunchKernelGGL(kern, dim3(nunits), dim3(THREADS), lds, st, s, out, ws, w, unit0, in, gather_eb, cand_m, budgets);
   } else {
     auto kern = mixsel_kernel<THREADS, EPT, false>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
+    static LdsLimitOnce once;
+    const hipError_t attr = once.raise(reinterpret_cast<const void *>(kern));
+    if (attr != hipSuccess) return attr;
     hipLaunchKernelGGL(kern, dim3(nunits), dim3(THREADS), lds, st, s, out, ws, w, unit0, in, 0, 0, nullptr);
   }
   return hipGetLastError();

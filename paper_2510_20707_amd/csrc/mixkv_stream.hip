@@ -133,14 +133,12 @@ __global__ __launch_bounds__(WAVES * 64, stats_waves_per_simd(DT, D, WAVES, TQ))
       __builtin_amdgcn_sched_barrier(0);
       if (use_v) wait_tile<2 * KL>(t, nt); else wait_tile<KL>(t, nt);
       lds_barrier();
-#ifndef MIXKV_NODMA   // developer switch: time the arithmetic alone (results are then meaningless)
       if (t + kLead < nt) {                            // tile t + kLead goes into the image tile t - 1 has left
         constexpr uint32_t off = (uint32_t)((SLOT + kLead) & (kRing - 1)) * (TILE * 16);
         const int tbr = key0 + (t + kLead) * 32;
         fetch_tile<DT, D, WAVES>(Kreq, row_bytes, tbr, N, kring_a + off, wave, lane);
         if (use_v) fetch_tile<DT, D, WAVES>(Vreq, row_bytes, tbr, N, vring_a + off, wave, lane);
       }
-#endif
       Kreq += tile_bytes;
       Vreq += tile_bytes;
       __builtin_amdgcn_sched_barrier(0);
@@ -550,11 +548,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTab
       __builtin_amdgcn_sched_barrier(0);
       wait_tile<KL>(t + 1, nt);
       lds_barrier();                                   // every wave has read the fragments of tile t: its image is free
-#ifndef MIXKV_NODMA   // developer switch: time the arithmetic alone (results are then meaningless)
       if (t + 1 + kLead < nt)                          // tile t + kRing goes into the image of tile t
         fetch_tile<DT, D, WAVES>(Kreq, row_bytes, key0 + (t + 1 + kLead) * 32, N, kring_a + (uint32_t)SLOT * (TILE * 16), wave,
                                  lane);
-#endif
       Kreq += tile_bytes;
       const int k = SLOT % KT, g = t / KT;             // tile within its chunk, chunk within the run
       if (k == 0 && g > 0) flush_colsums(c0 + g - 1, (g - 1) & 1);

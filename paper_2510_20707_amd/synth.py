@@ -186,3 +186,20 @@ def layer_arrays(wl: Workload, lay: Layer):
     if wl.dtype == "bf16":
         return round_to_bf16_bits(lay.K), round_to_bf16_bits(lay.V), round_to_bf16_bits(lay.Q)
     return lay.K, lay.V, lay.Q
+
+
+def window_lse(wl: Workload, lay: Layer, causal: bool = True) -> np.ndarray:
+    """Stand-in for a by-product of the prefill attention kernel, an optional INPUT of the compression
+    step: for every window query row the natural logarithm of sum_i exp(softmax_scale * q.k_i) over
+    the keys the row attends to (0..Nc+w with the causal window, else all N), float32 [batch, Hq, W].
+    Computed in float64 from the layer's values; tests pin it against a library log-sum-exp."""
+    n, w, g = wl.seq_len, wl.window, wl.group
+    out = np.empty((wl.batch, wl.n_q_heads, w), dtype=np.float32)
+    vis = np.arange(n)[None, :] <= ((n - w + np.arange(w)) if causal else np.full(w, n - 1))[:, None]
+    for b in range(wl.batch):
+        for h in range(wl.n_q_heads):
+            s = wl.softmax_scale * (lay.Q[b, h].astype(np.float64) @ lay.K[b, h // g].astype(np.float64).T)
+            s = np.where(vis, s, -np.inf)
+            m = s.max(axis=1)
+            out[b, h] = m + np.log(np.exp(s - m[:, None]).sum(axis=1))
+    return out

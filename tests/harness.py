@@ -69,18 +69,9 @@ def given_weights(wl: synth.Workload, layer_id: int) -> np.ndarray:
 
 
 def window_lse(wl: synth.Workload, lay: synth.Layer, causal=True) -> np.ndarray:
-    """What a prefill attention kernel would hand over for the window rows: log-sum-exp of
-    softmax_scale * Q.K over the keys each row attends to, float32, [batch, Hq, W] (computed here in
-    float64 with a library routine from the same inputs)."""
-    from scipy.special import logsumexp
-    N, W, G, Nc = wl.seq_len, wl.window, wl.group, wl.seq_len - wl.window
-    out = np.empty((wl.batch, wl.n_q_heads, W), dtype=np.float64)
-    for b in range(wl.batch):
-        for g in range(wl.n_q_heads):
-            logits = wl.softmax_scale * (lay.Q[b, g].astype(np.float64) @ lay.K[b, g // G].astype(np.float64).T)
-            for w in range(W):
-                out[b, g, w] = logsumexp(logits[w, :Nc + w + 1 if causal else N])
-    return out.astype(np.float32)
+    """What a prefill attention kernel would hand over for the window rows (synth.window_lse, pinned
+    against a library log-sum-exp in tests/test_synth.py)."""
+    return synth.window_lse(wl, lay, causal)
 
 
 def run_compress(wl: synth.Workload, layers, device="cuda:0", want_scores=True, r_given=None, head_budgets=None,

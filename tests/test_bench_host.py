@@ -23,19 +23,3 @@ def test_algorithmic_bytes_of_the_headline_workload():
     assert bench.algorithmic_bytes(wl, 64, scores_out=True) == per_unit + 4 * 8192
     assert bench.algorithmic_bytes(wl, 64, scores_out=False, reads_v=False) == per_unit - 8192 * 128 * 2
     assert per_unit * wl.n_units == 483553280
-
-
-def test_window_lse_stand_in_matches_a_library_logsumexp():
-    sys.path.insert(0, ROOT)
-    import numpy as np
-    from scipy.special import logsumexp
-    import bench
-    from paper_2510_20707_amd import synth
-    wl = synth.WORKLOADS["c1"]
-    lay = synth.make_layer(wl, 0)
-    got = bench.window_lse(wl, lay)
-    nc = wl.seq_len - wl.window
-    for g in (0, 3):
-        for w in (0, wl.window - 1):
-            s = wl.softmax_scale * (lay.Q[0, g, w].astype(np.float64) @ lay.K[0, g // wl.group, :nc + w + 1].astype(np.float64).T)
-            assert abs(float(got[0, g, w]) - logsumexp(s)) < 1e-5

@@ -45,3 +45,18 @@ def test_redundancy_regimes():
     c3 = synth.WORKLOADS["c3"].with_(seq_len=2048, text_suffix_start=1984)
     rs = [_rbar(synth.make_layer(c3, l).K[0, h]) for l in range(3) for h in range(4)]
     assert 0.35 < min(rs) < max(rs) < 0.85 and max(rs) - min(rs) > 0.1
+
+
+def test_window_lse_stand_in_matches_a_library_logsumexp():
+    from scipy.special import logsumexp
+    wl = synth.WORKLOADS["c1"]
+    lay = synth.make_layer(wl, 0)
+    nc = wl.seq_len - wl.window
+    for causal in (True, False):
+        got = synth.window_lse(wl, lay, causal)
+        assert got.dtype == np.float32 and got.shape == (wl.batch, wl.n_q_heads, wl.window)
+        for g in (0, 3):
+            for w in (0, wl.window - 1):
+                n = nc + w + 1 if causal else wl.seq_len
+                s = wl.softmax_scale * (lay.Q[0, g, w].astype(np.float64) @ lay.K[0, g // wl.group, :n].astype(np.float64).T)
+                assert abs(float(got[0, g, w]) - logsumexp(s)) < 1e-5
