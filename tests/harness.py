@@ -22,6 +22,10 @@ from paper_2510_20707_amd import synth
 
 TOL = {"bf16": 2e-3, "f32": 1e-5}
 RTOL_R = {"bf16": 1e-5, "f32": 1e-6}
+# What the kernels achieve is far inside the contractual score tolerance (bf16 inputs are exact in
+# both paths and the arithmetic is fp32: observed errors are a few 1e-6).  A second, tighter bound
+# catches a loss of accuracy long before it reaches the contract.
+REGRESSION_TOL = {"bf16": 1e-4, "f32": 1e-5}
 
 
 def oracle_params(wl: synth.Workload, **over) -> O.Params:
@@ -99,6 +103,8 @@ def check_scores(dtype, gpu, ora, what=""):
     err = np.abs(gpu.astype(np.float64) - ora) / ref
     assert np.all(np.isfinite(gpu)), f"{what}: non-finite GPU score"
     assert err.max() <= tol, f"{what}: score error {err.max():.3e} > {tol} at {int(err.argmax())}"
+    assert err.max() <= REGRESSION_TOL[dtype], \
+        f"{what}: score error {err.max():.3e} is inside the contract ({tol}) but above what the path achieves ({REGRESSION_TOL[dtype]})"
     return float(err.max())
 
 
@@ -124,10 +130,11 @@ def check_topk_set(dtype, kept: np.ndarray, s_ora: np.ndarray, k: int, what=""):
 
 
 def check_layer(wl: synth.Workload, lay: synth.Layer, p: B.MixkvParams, out: B.LayerOut, units=None, r_given=None,
-                head_budgets=None, lse=None, **over):
+                head_budgets=None, lse=None, oracle_units=None, **over):
     """Compare one layer of GPU output with the oracle.  `units`: iterable of (b, h) to check with
     the oracle (default all); invariants are checked on every unit.  `r_given`: this layer's
-    [batch, Hkv] weights for mix "given_r"."""
+    [batch, Hkv] weights for mix "given_r".  `oracle_units`: {(b, h): {"s_comp", "r"}} computed
+    beforehand by tests/oracle_pool.py for the same inputs and parameters (else computed here)."""
     op = oracle_params(wl, **over)
     Bt, Hkv, N, D, W = wl.batch, wl.n_kv_heads, wl.seq_len, wl.head_dim, wl.window
     Bud = op.budget
@@ -168,9 +175,12 @@ def check_layer(wl: synth.Workload, lay: synth.Layer, p: B.MixkvParams, out: B.L
                 assert np.all(np.isposinf(sc_g[b, h, Nc:]))
             if (b, h) not in todo:
                 continue
-            u = O.score_unit(lay.K[b, h], lay.V[b, h], lay.Q[b, h * G:(h + 1) * G], op,
-                             None if r_given is None else float(r_given[b, h]),
-                             None if lse is None else lse[b, h * G:(h + 1) * G].astype(np.float64))
+            if oracle_units is not None:
+                u = oracle_units[(b, h)]
+            else:
+                u = O.score_unit(lay.K[b, h], lay.V[b, h], lay.Q[b, h * G:(h + 1) * G], op,
+                                 None if r_given is None else float(r_given[b, h]),
+                                 None if lse is None else lse[b, h * G:(h + 1) * G].astype(np.float64))
             s_ora_heads[h] = u["s_comp"]
             what = f"{wl.name} b{b} h{h}"
             if sc_g is not None:
@@ -196,7 +206,8 @@ def check_layer(wl: synth.Workload, lay: synth.Layer, p: B.MixkvParams, out: B.L
                 tau = np.sort(flat.reshape(-1))[::-1][rest - 1]
                 band = TOL[wl.dtype] * max(abs(tau), np.abs(s_all).mean())
                 for h in range(Hkv):
-                    slack = int(((s_all[h] >= tau - band) & (s_all[h] <= tau + band)).sum()) + 1
+                    # a head's budget can differ from the oracle's by at most its candidates inside the band
+                    slack = int(((s_all[h] >= tau - band) & (s_all[h] <= tau + band)).sum())
                     assert abs(int(cnt_g[b, h]) - W - int(bp_ora[h])) <= slack, \
                         f"{wl.name} b{b} h{h}: budget {cnt_g[b, h] - W} vs oracle {bp_ora[h]} (slack {slack})"
     return stats

@@ -134,6 +134,9 @@ def test_identical_keys_degenerate_head(name, kw):
     idx = outs[0].indices.cpu().numpy()
     for h in range(2):
         assert len(set(idx[0, h].tolist())) == wl.budget
+    # every unit through the invariants of a compacted cache: counts and offsets, kept positions
+    # unique, ascending and in range, window rows last, gathered rows bit-identical to the source
+    H.check_layer(wl, lay, p, outs[0], units=[])
 
 
 def test_c3_two_layers_all_budgets():
@@ -142,27 +145,73 @@ def test_c3_two_layers_all_budgets():
         _run_and_check(wl, layer_ids=[0, 17], units=[(0, 0), (0, 3)], budget=budget)
 
 
+def _oracle_kwargs(wl, **over):
+    op = H.oracle_params(wl, **over)
+    return {f: getattr(op, f) for f in op.__dataclass_fields__}
+
+
 def test_c3_full_cache_bench_configuration():
-    # the launch configuration bench.py times: all 28 layers in one call; oracle on sampled units,
-    # invariants (unique, ascending, window kept, rows bit-identical) on every unit
+    # the launch configuration bench.py times: all 28 layers in one call, compared with the oracle on
+    # every one of the 112 units (the oracle runs in worker processes while the GPU call is set up)
+    from tests import oracle_pool
     wl = WL["c3"]
     layers = [synth.make_layer(wl, l) for l in range(wl.n_layers)]
-    _say(f"[case] c3 full cache, {wl.n_layers} layers in one call")
+    _say(f"[case] c3 full cache, {wl.n_layers} layers in one call, oracle on all {wl.n_units} units")
+    ora = oracle_pool.score_layers("c3", {}, range(wl.n_layers), _oracle_kwargs(wl))
     p, outs = H.run_compress(wl, layers)
-    sample = {0: [(0, 1)], 9: [(0, 2)], 27: [(0, 0), (0, 3)]}
+    tot = dict(max_err=0.0, exact=0, checked=0)
     for l, (lay, out) in enumerate(zip(layers, outs)):
-        st = H.check_layer(wl, lay, p, out, units=sample.get(l, []))
-        if l in sample:
-            _say(f"       layer {l}: {st}")
+        st = H.check_layer(wl, lay, p, out, oracle_units=ora[l])
+        tot["max_err"] = max(tot["max_err"], st["max_err"])
+        tot["exact"] += st["exact"]
+        tot["checked"] += st["checked"]
+    _say(f"       {tot}")
+    assert tot["checked"] == wl.n_units
 
 
 def test_c4_llama_shaped_two_layers():
     _run_and_check(WL["c4"], layer_ids=[0, 31], units=[(0, 0), (0, 7)])
 
 
+def test_c4_llama_shaped_full_depth_one_call():
+    # all 32 layers (256 units) in one call; oracle on units of the first, middle and last layers,
+    # invariants on every unit
+    wl = WL["c4"]
+    layers = [synth.make_layer(wl, l) for l in range(wl.n_layers)]
+    _say(f"[case] c4 full depth, {wl.n_layers} layers in one call")
+    p, outs = H.run_compress(wl, layers, want_scores=True)
+    sample = {0: [(0, 0), (0, 5)], 1: [(0, 7)], 15: [(0, 2), (0, 6)], 16: [(0, 3)], 30: [(0, 1)], 31: [(0, 4), (0, 7)]}
+    checked = 0
+    for l, (lay, out) in enumerate(zip(layers, outs)):
+        st = H.check_layer(wl, lay, p, out, units=sample.get(l, []))
+        checked += st["checked"]
+        if l in sample:
+            _say(f"       layer {l}: {st}")
+    assert checked == sum(len(v) for v in sample.values()) >= 8
+
+
 def test_c5_long_video_adaptive_one_layer():
     wl = WL["c5"].with_(batch=2)
     _run_and_check(wl, layer_ids=[3], units=[(0, h) for h in range(4)])
+
+
+def test_c5_long_video_adaptive_full_depth_one_call():
+    # all 28 layers x batch 4 (448 units) in one call, head-adaptive budgets; oracle on complete
+    # (layer, batch item) groups of four heads (so the budget split is compared too) of the first,
+    # middle and last layers, every batch item covered; invariants on every unit
+    wl = WL["c5"]
+    layers = [synth.make_layer(wl, l) for l in range(wl.n_layers)]
+    _say(f"[case] c5 full depth, {wl.n_layers} layers x batch {wl.batch} in one call")
+    p, outs = H.run_compress(wl, layers, want_scores=True)
+    sample = {0: [0], 13: [1, 2], 27: [3]}                 # layer -> batch items
+    checked = 0
+    for l, (lay, out) in enumerate(zip(layers, outs)):
+        units = [(b, h) for b in sample.get(l, []) for h in range(wl.n_kv_heads)]
+        st = H.check_layer(wl, lay, p, out, units=units)
+        checked += st["checked"]
+        if l in sample:
+            _say(f"       layer {l}: {st}")
+    assert checked == 16
 
 
 def test_adaptive_small_all_units():
