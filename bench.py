@@ -227,7 +227,9 @@ def main():
 
     base = [(up(l.K), up(l.V), up(l.Q)) for l in layers]
     copies = [base] + [[(k.clone(), v.clone(), q.clone()) for k, v, q in base] for _ in range(max(0, args.copies - 1))]
-    outs = [B.alloc_layer_out(p, dev, scores=False, redundancy=True) for _ in layers]
+    # the importance-only score reads no key statistics: without a redundancy output the library skips them
+    want_r = not (args.mix == "imp_only" and args.intrinsic != "knorm")
+    outs = [B.alloc_layer_out(p, dev, scores=False, redundancy=want_r) for _ in layers]
     ws = B.alloc_workspace(p, len(layers), dev)
     rg_dev = None if r_given is None else [torch.from_numpy(r).to(dev) for r in r_given]
     lse_dev = None if lse is None else [torch.from_numpy(x).to(dev) for x in lse]

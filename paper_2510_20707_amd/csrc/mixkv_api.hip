@@ -64,6 +64,7 @@ mixkv_status make_shape(const mixkv_params *p, Shape *s) {
   s->per_head = p->budget_mode == MIXKV_BUDGET_PER_HEAD;
   s->scale_log2e = (float)((double)p->softmax_scale * 1.4426950408889634);
   s->eps = p->eps;
+  s->kstats = 1;                                    // run() clears it when nothing reads the key statistics
   return MIXKV_OK;
 }
 
@@ -196,6 +197,14 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
     }
   }
 
+  // The key statistics (1 / |K_i|, the mean normalised key, r) feed the diversity score, the head weight of
+  // Eq. 5, the key-norm intrinsic score and the redundancy output.  The importance-only score of the
+  // ablation (Table 4; the SnapKV-style base of Sec. 4.1) reads none of them unless the caller asks for r.
+  if (stages & kScore) {
+    bool wants_r = false;
+    for (int l = 0; l < n_layers; ++l) wants_r = wants_r || out[l].redundancy != nullptr;
+    s.kstats = (s.mix != MIXKV_MIX_IMP_ONLY || s.intrinsic == MIXKV_INTRINSIC_KNORM || wants_r) ? 1 : 0;
+  }
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
   char *ws = reinterpret_cast<char *>(workspace);
   int num_cus = 0;

@@ -44,6 +44,8 @@ struct Shape {
   int32_t units_per_layer;
   int32_t nb_rows;       // row length of the per-unit exponent offsets: QT*32 rounded up to 256
   int32_t pool, pool_k, causal, intrinsic, mix, adaptive, per_head, floor_;
+  int32_t kstats;        // 1 / |K_i|, the mean normalised key and r are needed (else nothing reads them: the
+                         // importance-only mix without the key-norm intrinsic score and without a redundancy output)
   float scale_log2e;     // softmax_scale * log2(e)
   float eps;
 };

@@ -150,8 +150,10 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
     float4 kr = make_float4(0.f, 0.f, 0.f, 0.f), nr = kr;
     vr = kr;
     if (i < Nc) {
-      kr = *reinterpret_cast<const float4 *>(kdot + i);
-      nr = *reinterpret_cast<const float4 *>(invn + i);
+      if (s.kstats) {                        // else nobody wrote them: the diversity is 0 and carries weight 0
+        kr = *reinterpret_cast<const float4 *>(kdot + i);
+        nr = *reinterpret_cast<const float4 *>(invn + i);
+      }
       if (knorm) vr = make_float4(neg_key_norm(nr.x), neg_key_norm(nr.y), neg_key_norm(nr.z), neg_key_norm(nr.w));
       else if (use_v) vr = *reinterpret_cast<const float4 *>(vnorm + i);
     }

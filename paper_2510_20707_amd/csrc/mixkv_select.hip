@@ -269,6 +269,7 @@ __global__ __launch_bounds__(kSelectThreads) void mix_kernel(Shape s, LayerOutTa
   // cancel exactly against the same product further down, so the compiler may not fuse it into
   // the subtraction there (the empty statement hides where the value came from).
   auto sdiv_at = [&](int i) {
+    if (!s.kstats) return 0.f;                 // nobody wrote the key statistics: diversity 0, weight 0
     float d = -kdot[i] * invn[i];
     asm("" : "+v"(d));
     return d;

@@ -60,6 +60,7 @@ __global__ __launch_bounds__(WAVES * 64, stats_waves_per_simd(DT, D, WAVES, TQ))
   const int free_limit = s.causal ? Nc : N - 1;      // keys <= this are visible to every row
   const int nq = GIVEN_LSE ? 0 : max(0, min(TQ, s.QT - wave * TQ));  // query tiles this wave owns
   const bool use_v = s.intrinsic == MIXKV_INTRINSIC_VNORM;
+  const bool use_k = s.kstats != 0;                  // key norms and the sum of normalised keys have a reader
   // Waves without a query tile (the workgroup has more tile slots than the head has tiles, or the
   // normalisers are given) run no matrix or softmax work.
   const uint32_t kring_a = lds_base_of(kring), vring_a = lds_base_of(vring);
@@ -171,6 +172,7 @@ __global__ __launch_bounds__(WAVES * 64, stats_waves_per_simd(DT, D, WAVES, TQ))
       const int lrow = lane / PPR, lq = lane % PPR;
 #pragma unroll
       for (int jj = 0; jj < (STEPS + WAVES - 1) / WAVES; ++jj) {
+        if (!use_k) break;
         const int j = jj * WAVES + wave;
         if (STEPS % WAVES != 0 && j >= STEPS) break;
         const int row = j * RPL + lrow, key = tb + row;

@@ -79,7 +79,7 @@ def window_lse(wl: synth.Workload, lay: synth.Layer, causal=True) -> np.ndarray:
 
 
 def run_compress(wl: synth.Workload, layers, device="cuda:0", want_scores=True, r_given=None, head_budgets=None,
-                 lse=None, **over):
+                 lse=None, want_redundancy=True, **over):
     """mixkv_compress on a list of synth.Layer.  `r_given`: per layer a float32 [batch, Hkv] array
     (mix "given_r"); `head_budgets`: int [len(layers), Hkv] (budget mode "per_head").
     Returns (params, list of LayerOut on device)."""
@@ -87,7 +87,7 @@ def run_compress(wl: synth.Workload, layers, device="cuda:0", want_scores=True, 
     Ks = [to_device(wl, l.K, device) for l in layers]
     Vs = [to_device(wl, l.V, device) for l in layers]
     Qs = [to_device(wl, l.Q, device) for l in layers]
-    outs = [B.alloc_layer_out(p, device, scores=want_scores) for _ in layers]
+    outs = [B.alloc_layer_out(p, device, scores=want_scores, redundancy=want_redundancy) for _ in layers]
     ws = B.alloc_workspace(p, len(layers), device)
     rg = None if r_given is None else [torch.from_numpy(np.ascontiguousarray(r, dtype=np.float32)).to(device)
                                         for r in r_given]

@@ -295,6 +295,30 @@ def test_c2_scoring_variants(over):
     _run_and_check(WL["c2"], **over)
 
 
+@pytest.mark.parametrize("name,kw,over", [
+    ("c1", {}, dict(mix="imp_only", intrinsic="none")),
+    ("c1", {}, dict(mix="imp_only", intrinsic="vnorm", pool="avg")),
+    ("c2", {}, dict(mix="imp_only", intrinsic="none")),
+    ("c2", dict(seq_len=1000, text_suffix_start=940, budget_mode="adaptive", budget_floor=8), dict(mix="imp_only")),
+    # beyond the fused mix kernel's row length: the stand-alone mix kernel
+    ("c2", dict(seq_len=33000, batch=1, n_q_heads=2, n_kv_heads=1, text_suffix_start=32900), dict(mix="imp_only", intrinsic="none")),
+])
+def test_importance_only_without_a_redundancy_output_skips_the_key_statistics(name, kw, over):
+    # The importance-only score (Table 4; the SnapKV-style base of Sec. 4.1) reads neither key norms nor
+    # the mean key nor r; when the caller does not ask for r either, the first pass does not compute
+    # them.  Results must be those of the oracle all the same, and equal to the run that does compute
+    # them (same arithmetic for everything that is read).
+    wl = WL[name].with_(name="imp-only", **kw) if kw else WL[name]
+    lay = synth.make_layer(wl, 0)
+    _say(f"[case] {wl.name} importance only, no redundancy output, {over}")
+    p, outs = H.run_compress(wl, [lay], want_redundancy=False, **over)
+    st = H.check_layer(wl, lay, p, outs[0], **over)
+    assert st["checked"] == wl.batch * wl.n_kv_heads
+    p2, ref = H.run_compress(wl, [lay], want_redundancy=True, **over)
+    assert torch.equal(outs[0].scores.view(torch.int32), ref[0].scores.view(torch.int32))
+    assert torch.equal(outs[0].indices, ref[0].indices) and torch.equal(outs[0].counts, ref[0].counts)
+
+
 def test_scoring_variants_adaptive_budgets_and_long_fallback():
     wl = WL["c2"].with_(name="adaptive-variants", seq_len=1024, text_suffix_start=960, batch=2, budget=96,
                         budget_mode="adaptive", budget_floor=16, sigma=(0.1, 0.8))
