@@ -39,7 +39,7 @@
 extern "C" {
 #endif
 
-#define MIXKV_VERSION 9
+#define MIXKV_VERSION 10
 #define MIXKV_MAX_LAYERS 128      /* layers per call */
 #define MIXKV_MAX_WINDOW 64
 #define MIXKV_MAX_GROUP_ROWS 512  /* G * W */
@@ -133,7 +133,15 @@ typedef struct {
  * Bytes of device workspace mixkv_score / mixkv_compress need for `n_layers`
  * layers of this shape.  mixkv_select needs none and accepts NULL, except in
  * per-head budget mode, where it stages the budget table there and needs
- * n_layers * n_kv_heads * 4 bytes (this function's figure is always enough).
+ * n_layers * n_kv_heads * 4 bytes.  In head-adaptive mode mixkv_select uses a
+ * workspace of n_layers * batch * n_kv_heads * 8192 bytes if it is given one
+ * (two 1024-entry candidate lists per head) and a head's candidates fit them,
+ * M = floor + n_kv_heads * (budget - window - floor) <= 1024 and n_kv_heads * M
+ * <= 4096: every head is then ranked by a
+ * workgroup of its own and a small kernel splits the pool, about ten times
+ * faster on long caches than without, where one workgroup per batch item ranks
+ * the scores of all heads; the results are the same.  This function's figure
+ * is always enough for mixkv_select.
  * Host only; touches no GPU (head_budgets is not read).  The workspace needs no
  * initialisation and 256-byte alignment.
  */

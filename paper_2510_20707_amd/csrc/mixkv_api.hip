@@ -10,6 +10,8 @@ namespace mixkv {
 int stream_chunk_keys(int dtype, int D);
 int max_adaptive_heads();
 bool mixsel_supported(const Shape &s);
+hipError_t launch_topsel(const Shape &s, const LayerOutTable &out, char *ws, const Workspace &w, int64_t unit0, int nunits,
+                         int cand_m, const int32_t *budgets, hipStream_t st);
 hipError_t launch_mixsel(const Shape &s, bool select, const LayerOutTable &out, char *ws, const Workspace &w,
                          int64_t unit0, int nunits, const LayerInTable &in, int gather_eb, int cand_m,
                          const int32_t *budgets, hipStream_t st);
@@ -68,14 +70,17 @@ mixkv_status make_shape(const mixkv_params *p, Shape *s) {
   return MIXKV_OK;
 }
 
-void carve_workspace(const Shape &s, int64_t units, Workspace *w) {
+// `select_only`: the layout of a call that only selects on the caller's scores (the budget table and
+// the candidate lists; nothing of the scoring passes).
+void carve_workspace(const Shape &s, int64_t units, Workspace *w, bool select_only) {
   size_t off = 0;
-  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + (select_only ? 0 : bytes), 256); return o; };
+  auto take_sel = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   const size_t QTR = (size_t)s.QT * 32;
   // one slot per run of the streaming kernels: each launch group owns kMaxStreamGrid + its units
   const size_t per_group = (size_t)kMaxStreamGrid + (size_t)kLayersPerLaunch * s.units_per_layer;
   const size_t groups = ((size_t)(units / s.units_per_layer) + kLayersPerLaunch - 1) / kLayersPerLaunch;
-  w->budgets = take(s.per_head ? (size_t)(units / s.units_per_layer) * s.hkv * 4 : 0);
+  w->budgets = take_sel(s.per_head ? (size_t)(units / s.units_per_layer) * s.hkv * 4 : 0);
   w->part_ml = take(groups * per_group * QTR * 8);
   w->part_ksum = take(groups * per_group * s.D * 4);
   w->rbar = take((size_t)units * 4);
@@ -86,8 +91,8 @@ void carve_workspace(const Shape &s, int64_t units, Workspace *w) {
   w->vnorm = take((size_t)units * s.Npad * 4 + 256);
   w->araw = take((size_t)units * s.Npad * 4 + 256);
   w->sdiv = take((size_t)units * s.Npad * 4 + 256);
-  w->cand_idx = take(s.adaptive ? (size_t)units * kMaxCandPerHead * 4 : 0);
-  w->cand_key = take(s.adaptive ? (size_t)units * kMaxCandPerHead * 4 : 0);
+  w->cand_idx = take_sel(s.adaptive ? (size_t)units * kMaxCandPerHead * 4 : 0);
+  w->cand_key = take_sel(s.adaptive ? (size_t)units * kMaxCandPerHead * 4 : 0);
   w->scores = take((size_t)units * s.N * 4);
   w->total = off;
 }
@@ -155,13 +160,17 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
   const int eb = params->dtype == MIXKV_BF16 ? 2 : 4;
   const int64_t units = (int64_t)n_layers * s.units_per_layer;
   Workspace w;
-  carve_workspace(s, units, &w);
-  // selection on caller-provided scores needs no workspace, except for the per-head budget table
+  const bool select_only = stages == kSelect;
+  carve_workspace(s, units, &w, select_only);
+  // Selection on caller-provided scores needs no workspace, except for the per-head budget table.
+  // Head-adaptive mode uses one for the heads' candidate lists if the caller brings it (one workgroup
+  // per head, then a small split); without it one workgroup per batch item ranks all heads' scores.
   const bool stage_budgets = s.per_head && (stages & kSelect);
   if ((stages & kScore) || stage_budgets) {
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return MIXKV_ERR_INVALID_ARG;
-    if (workspace_bytes < ((stages & kScore) ? w.total : w.part_ml)) return MIXKV_ERR_WORKSPACE_TOO_SMALL;
+    if (workspace_bytes < w.total) return MIXKV_ERR_WORKSPACE_TOO_SMALL;
   }
+  const bool lists_fit = workspace && !(reinterpret_cast<uintptr_t>(workspace) & 255u) && workspace_bytes >= w.total;
   if (stage_budgets) {
     if (!params->head_budgets) return MIXKV_ERR_INVALID_ARG;
     for (int l = 0; l < n_layers; ++l) {
@@ -235,7 +244,9 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
     const bool fused_select = fused && (stages & kSelect) && !s.adaptive;
     const bool fused_gather = fused_select && (stages & kGather);   // the selecting workgroup also copies its rows
     // head-adaptive mode: the fused kernel hands every head's best candidates to a small split kernel
-    const int cand_m = (fused && (stages & kSelect) && s.adaptive) ? adaptive_candidates(s) : 0;
+    // selection alone: the same selection code on the caller's scores, one workgroup per head
+    const bool topsel = select_only && mixsel_supported(s) && (!s.adaptive || (lists_fit && adaptive_candidates(s) > 0));
+    const int cand_m = ((fused || topsel) && (stages & kSelect) && s.adaptive) ? adaptive_candidates(s) : 0;
     for (int l = 0; l < nl; ++l) {
       if (in) {
         const mixkv_layer_in &li = in[l0 + l];
@@ -267,7 +278,9 @@ static mixkv_status run(const mixkv_params *params, const mixkv_layer_in *in, mi
                          : launch_mix(s, ti, to, ws, w, unit0, nunits, stream);
           }));
     }
-    if (result == MIXKV_OK && (stages & kSelect) && !fused_select)
+    if (result == MIXKV_OK && topsel)
+      ok(timed(3, [&] { return launch_topsel(s, to, ws, w, unit0, nunits, cand_m, budgets_l0, stream); }));
+    if (result == MIXKV_OK && (stages & kSelect) && !fused_select && !(topsel && !s.adaptive))
       ok(timed(3, [&] {
         return cand_m > 0 ? launch_select_candidates(s, to, ws, w, unit0, nl, cand_m, stream) : launch_select(s, to, nl, budgets_l0, stream);
       }));

@@ -70,7 +70,7 @@ struct Workspace {
 };
 
 mixkv_status make_shape(const mixkv_params *p, Shape *s);
-void carve_workspace(const Shape &s, int64_t units, Workspace *w);
+void carve_workspace(const Shape &s, int64_t units, Workspace *w, bool select_only = false);
 
 // Kernel launchers (one per pipeline stage).  `unit0` is the first unit of this launch group,
 // `nunits` the number of units it covers (whole layers).

@@ -29,6 +29,7 @@ struct MsScratch {
   uint32_t ur[2];
   int i[kMsMaxWaves + 1];
   int hist[kBins];
+  int hist0[kBins];                      // the first round's histogram of a head, for a second threshold on the same keys
   int bin, krem, cut;
 };
 
@@ -108,6 +109,165 @@ __device__ __forceinline__ void hist_add(int *hist, int bin, bool on) {
   const int lane = threadIdx.x & 63;
   if (lane == first) atomicAdd(&hist[b0], __popcll(same));
   if (on && bin != b0) atomicAdd(&hist[bin], 1);
+}
+
+// Threshold of the k largest of a workgroup's keys (1 <= k <= number of valid keys): every thread holds
+// EPT keys, those with their bit set in `vmask` valid, and [kmin, kmax] is the range of all valid keys.  Most-significant-digit radix select from the first
+// bit in which the keys differ.  Returns tau, the k-th largest key, and in krem how many of the
+// keys equal to tau still belong to the k (0: all of them).  Ends behind a barrier: may be called again.
+// The first round counts every valid key and does not depend on k: FIRST = 1 keeps its histogram
+// aside, FIRST = 2 takes it from there (a second threshold on the same keys), 0 does neither.
+template <int THREADS, int EPT, int FIRST = 0>
+__device__ __forceinline__ uint32_t radix_threshold(const uint32_t (&key)[EPT], uint32_t vmask, uint32_t kmin, uint32_t kmax,
+                                                    int k, MsScratch &sc, int &krem) {
+  constexpr int NW = THREADS / 64;
+  const int tid = threadIdx.x;
+  // bits at and above `undecided` are common to all keys; digits of up to kDigit bits from there down
+  int undecided = kmin == kmax ? 0 : 32 - __clz((int)(kmin ^ kmax));
+  uint32_t prefix = undecided >= 32 ? 0u : (kmax >> undecided) << undecided;
+  bool all_equal = false, first = true;
+  while (undecided > 0) {
+    const int wbits = min(kDigit, undecided), shift = undecided - wbits;
+    const uint32_t himask = undecided >= 32 ? 0u : ~0u << undecided;
+    const bool saved = FIRST == 2 && first;             // this round's histogram is already in hist0
+    int *hist = saved ? sc.hist0 : sc.hist;
+    if (!saved) {
+      for (int i = tid; i < kBins; i += THREADS) sc.hist[i] = 0;
+      __syncthreads();
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) {
+        const bool on = ((vmask >> e) & 1u) != 0 && (key[e] & himask) == (prefix & himask);
+        hist_add(sc.hist, (int)((key[e] >> shift) & ((1u << wbits) - 1u)), on);
+      }
+      __syncthreads();
+    }
+    // walk the bins from the top: thread t sums bins [kBins - (t+1)*BPT, kBins - t*BPT)
+    constexpr int BPT = (kBins + THREADS - 1) / THREADS;
+    int cnt = 0;
+#pragma unroll
+    for (int j = 0; j < BPT; ++j) {
+      const int bi = kBins - 1 - (tid * BPT + j);
+      const int c = bi >= 0 ? hist[bi] : 0;
+      if (FIRST == 1 && first && bi >= 0) sc.hist0[bi] = c;
+      cnt += c;
+    }
+    first = false;
+    int total;
+    const int excl = block_scan_excl<NW>(cnt, sc, &total);
+    if (excl < k && k <= excl + cnt) {
+      int run = excl;
+#pragma unroll
+      for (int j = 0; j < BPT; ++j) {
+        const int bi = kBins - 1 - (tid * BPT + j);
+        const int c = bi >= 0 ? hist[bi] : 0;
+        if (run < k && k <= run + c) { sc.bin = bi; sc.krem = k - run; sc.cut = c; }
+        run += c;
+      }
+    }
+    __syncthreads();
+    prefix |= (uint32_t)sc.bin << shift;
+    k = sc.krem;
+    undecided = shift;
+    const bool whole_bin = sc.cut == k && shift > 0 && prefix != 0;
+    __syncthreads();
+    // Every key of the bin is needed: the kept set is "all keys at or above the bin", whatever
+    // the lower digits are, so the remaining rounds can be skipped.
+    if (whole_bin) { prefix -= 1; all_equal = true; break; }
+  }
+  krem = all_equal ? 0 : k;
+  return prefix;
+}
+
+// Bit 31 of a candidate-list entry: the candidate is one of its head's `floor` best.
+constexpr uint32_t kFloorFlag = 0x80000000u;
+
+// TopB' of one head: the Bp >= 1 candidates with the largest scores, ties to the smaller index, out
+// of the EPT consecutive candidates base .. base + nvalid - 1 every thread holds in a[] (Sec. 3.1 /
+// Algorithm 1, TopB).  The kept positions go to idx[0, Bp) in ascending order.  With ckey not null
+// the list is a head's candidates for the head-adaptive split: the order keys go beside the
+// positions, and the head's `floor` <= Bp best carry kFloorFlag in their position word.
+// sc.ur must hold {0xffffffff, 0} from before an earlier barrier.
+template <int THREADS, int EPT>
+__device__ __forceinline__ void top_select(const float (&a)[EPT], int nvalid, int base, int Bp, int32_t *idx,
+                                           uint32_t *ckey, int floor, MsScratch &sc) {
+  constexpr int NW = THREADS / 64;
+  uint32_t key[EPT];
+  uint32_t kmin = 0xffffffffu, kmax = 0;
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    key[e] = order_key_u(a[e]);
+    if (e < nvalid) { kmin = min(kmin, key[e]); kmax = max(kmax, key[e]); }
+  }
+  block_minmax_u32(kmin, kmax, sc);
+  const uint32_t vmask = nvalid >= EPT ? (EPT >= 32 ? 0xffffffffu : (1u << (EPT & 31)) - 1u)
+                                       : (nvalid <= 0 ? 0u : (1u << nvalid) - 1u);
+  int k;                             // of the keys equal to tau, the first k (by position) are kept
+  const bool flags = ckey != nullptr && floor > 0;
+  int kf = 0;
+  uint32_t tau, tauf = 0xffffffffu;
+  if (flags) {
+    tau = radix_threshold<THREADS, EPT, 1>(key, vmask, kmin, kmax, Bp, sc, k);
+    tauf = radix_threshold<THREADS, EPT, 2>(key, vmask, kmin, kmax, floor, sc, kf);
+  } else {
+    tau = radix_threshold<THREADS, EPT>(key, vmask, kmin, kmax, Bp, sc, k);
+  }
+  // one scan carries both counts: keys above tau (low half) and keys equal to tau (high half)
+  int ngt = 0, neq = 0, neqf = 0;
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    const bool in = e < nvalid;
+    ngt += (in && key[e] > tau) ? 1 : 0;
+    neq += (in && key[e] == tau) ? 1 : 0;
+    neqf += (in && key[e] == tauf) ? 1 : 0;
+  }
+  int total;
+  const int packed = block_scan_excl<NW>(ngt | (neq << 16), sc, &total);
+  int seen = packed >> 16;                          // equal keys at smaller indices
+  int pos = (packed & 0xffff) + min(seen, k);       // kept entries at smaller indices
+  int seenf = flags ? block_scan_excl<NW>(neqf, sc, &total) : 0;
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    if (e < nvalid) {
+      bool sel = key[e] > tau;
+      if (key[e] == tau) sel = seen++ < k;
+      bool inf = flags && key[e] > tauf;
+      if (flags && key[e] == tauf) inf = seenf++ < kf;
+      if (sel) {
+        if (pos < Bp) {
+          idx[pos] = (int32_t)((uint32_t)(base + e) | (inf ? kFloorFlag : 0u));
+          if (ckey) ckey[pos] = key[e];
+        }
+        ++pos;
+      }
+    }
+  }
+}
+
+// Rows head h of a layer keeps and its first row inside the batch item: B each, or the layer's
+// row of the budget table (per-head mode), the heads packed back to back.
+__device__ __forceinline__ void head_rows(const Shape &s, const int32_t *budgets, int layer, int h, int &Bh, int &row0) {
+  Bh = s.B;
+  row0 = h * s.B;
+  if (budgets) {
+    const int32_t *bl = budgets + layer * s.hkv;
+    row0 = 0;
+    for (int j = 0; j < h; ++j) row0 += bl[j];
+    Bh = bl[h];
+  }
+}
+
+// After the candidates of a head: the W window positions, the head's count and its offsets.
+__device__ __forceinline__ void finish_head(const Shape &s, const LayerOut &O, int b, int h, int Bh, int row0,
+                                            int32_t *idx, int threads) {
+  const int tid = threadIdx.x, Bp = Bh - s.W;
+  for (int wv = tid; wv < s.W; wv += threads) idx[Bp + wv] = s.Nc + wv;
+  if (tid == 0) {
+    O.counts[b * s.hkv + h] = Bh;
+    if (O.offsets) {
+      O.offsets[b * (s.hkv + 1) + h] = row0;
+      if (h == s.hkv - 1) O.offsets[b * (s.hkv + 1) + s.hkv] = row0 + Bh;
+    }
+  }
 }
 
 template <int THREADS, int EPT, bool SELECT>
@@ -300,108 +460,15 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
   // can end up keeping more than that, so the budget split only has to look at those.
   const bool cand = cand_m > 0;
   const int h = bh % s.hkv, b = bh / s.hkv;
-  int Bh = s.B, row0 = h * s.B;                        // rows this head keeps, and its first row in the batch item
-  if (budgets) {
-    const int32_t *bl = budgets + layer * s.hkv;
-    row0 = 0;
-    for (int j = 0; j < h; ++j) row0 += bl[j];
-    Bh = bl[h];
-  }
+  int Bh, row0;                                        // rows this head keeps, and its first row in the batch item
+  head_rows(s, budgets, layer, h, Bh, row0);
   const int64_t out_row0 = (int64_t)b * s.hkv * s.B + row0;
   int32_t *idx = cand ? reinterpret_cast<int32_t *>(ws + w.cand_idx) + unit * kMaxCandPerHead : O.indices + out_row0;
   uint32_t *ckey = reinterpret_cast<uint32_t *>(ws + w.cand_key) + unit * kMaxCandPerHead;
   const int Bp = cand ? cand_m : Bh - s.W;
-  if (Bp > 0) {
-    uint32_t key[EPT];
-    uint32_t kmin = 0xffffffffu, kmax = 0;
-#pragma unroll
-    for (int e = 0; e < EPT; ++e) {
-      key[e] = order_key_u(a[e]);
-      if (e < nvalid) { kmin = min(kmin, key[e]); kmax = max(kmax, key[e]); }
-    }
-    block_minmax_u32(kmin, kmax, sc);
-    // bits at and above `undecided` are common to all keys; digits of up to kDigit bits from there down
-    int undecided = kmin == kmax ? 0 : 32 - __clz((int)(kmin ^ kmax));
-    uint32_t prefix = undecided >= 32 ? 0u : (kmax >> undecided) << undecided;
-    int k = Bp;
-    while (undecided > 0) {
-      const int wbits = min(kDigit, undecided), shift = undecided - wbits;
-      const uint32_t himask = undecided >= 32 ? 0u : ~0u << undecided;
-      for (int i = tid; i < kBins; i += THREADS) sc.hist[i] = 0;
-      __syncthreads();
-#pragma unroll
-      for (int e = 0; e < EPT; ++e) {
-        const bool on = e < nvalid && (key[e] & himask) == (prefix & himask);
-        hist_add(sc.hist, (int)((key[e] >> shift) & ((1u << wbits) - 1u)), on);
-      }
-      __syncthreads();
-      // walk the bins from the top: thread t sums bins [kBins - (t+1)*BPT, kBins - t*BPT)
-      constexpr int BPT = (kBins + THREADS - 1) / THREADS;
-      int cnt = 0;
-#pragma unroll
-      for (int j = 0; j < BPT; ++j) {
-        const int bi = kBins - 1 - (tid * BPT + j);
-        cnt += bi >= 0 ? sc.hist[bi] : 0;
-      }
-      int total;
-      const int excl = block_scan_excl<NW>(cnt, sc, &total);
-      if (excl < k && k <= excl + cnt) {
-        int run = excl;
-#pragma unroll
-        for (int j = 0; j < BPT; ++j) {
-          const int bi = kBins - 1 - (tid * BPT + j);
-          const int c = bi >= 0 ? sc.hist[bi] : 0;
-          if (run < k && k <= run + c) { sc.bin = bi; sc.krem = k - run; sc.cut = c; }
-          run += c;
-        }
-      }
-      __syncthreads();
-      prefix |= (uint32_t)sc.bin << shift;
-      k = sc.krem;
-      undecided = shift;
-      const bool whole_bin = sc.cut == k && shift > 0 && prefix != 0;
-      __syncthreads();
-      // Every key of the bin is needed: the kept set is "all keys at or above the bin", whatever
-      // the lower digits are, so the remaining rounds can be skipped.
-      if (whole_bin) { prefix -= 1; k = 0; break; }
-    }
-    const uint32_t tau = prefix;       // the B'-th largest key; k of the keys equal to it are still needed
-    // one scan carries both counts: keys above tau (low half) and keys equal to tau (high half)
-    int ngt = 0, neq = 0;
-#pragma unroll
-    for (int e = 0; e < EPT; ++e) {
-      const bool in = e < nvalid;
-      ngt += (in && key[e] > tau) ? 1 : 0;
-      neq += (in && key[e] == tau) ? 1 : 0;
-    }
-    int total;
-    const int packed = block_scan_excl<NW>(ngt | (neq << 16), sc, &total);
-    int seen = packed >> 16;                          // equal keys at smaller indices
-    int pos = (packed & 0xffff) + min(seen, k);       // kept entries at smaller indices
-#pragma unroll
-    for (int e = 0; e < EPT; ++e) {
-      if (e < nvalid) {
-        bool sel = key[e] > tau;
-        if (key[e] == tau) sel = seen++ < k;
-        if (sel) {
-          if (pos < Bp) {
-            idx[pos] = base + e;
-            if (cand) ckey[pos] = key[e];
-          }
-          ++pos;
-        }
-      }
-    }
-  }
+  if (Bp > 0) top_select<THREADS, EPT>(a, nvalid, base, Bp, idx, cand ? ckey : nullptr, s.floor_, sc);
   if (cand) return;
-  for (int wv = tid; wv < s.W; wv += THREADS) idx[Bp + wv] = Nc + wv;
-  if (tid == 0) {
-    O.counts[bh] = Bh;
-    if (O.offsets) {
-      O.offsets[b * (s.hkv + 1) + h] = row0;
-      if (h == s.hkv - 1) O.offsets[b * (s.hkv + 1) + s.hkv] = row0 + Bh;
-    }
-  }
+  finish_head(s, O, b, h, Bh, row0, idx, THREADS);
   // ---- gather of the kept rows (Sec. 3.1, the compacted cache), if asked for: gather_eb is the
   // element size in bytes, 0 to skip.  16 bytes per thread and step; the head's indices are read
   // back after a workgroup barrier (same compute unit, so they are visible).
@@ -421,6 +488,123 @@ __global__ __launch_bounds__(THREADS) void mixsel_kernel(Shape s, LayerOutTable 
       const uint4 vv = *reinterpret_cast<const uint4 *>(Vh + so);
       *reinterpret_cast<uint4 *>(Ko + (int64_t)p * 16) = kv;
       *reinterpret_cast<uint4 *>(Vo + (int64_t)p * 16) = vv;
+    }
+  }
+}
+
+// topsel_kernel: the selection half alone, on scores that are already in memory (the caller's, for
+// mixkv_select).  One workgroup per unit reads the Nc candidate scores of its head once (coalesced,
+// through the padded LDS row to their consecutive-range owners) and selects from registers as
+// above: the head's final rows in fixed and per-head mode, or with cand_m > 0 its best cand_m
+// candidates with their keys for the head-adaptive split (Sec. 3.1 / Algorithm 1, TopB).
+template <int THREADS, int EPT>
+__global__ __launch_bounds__(THREADS) void topsel_kernel(Shape s, LayerOutTable out, char *ws, Workspace w, int64_t unit0,
+                                                           int cand_m, const int32_t *budgets) {
+  extern __shared__ float a_s[];                        // [Nc] padded: the head's scores
+  __shared__ MsScratch sc;
+  const int tid = threadIdx.x, ul = blockIdx.x;
+  const int64_t unit = unit0 + ul;
+  const int layer = ul / s.units_per_layer, bh = ul - layer * s.units_per_layer;
+  const LayerOut O = out.l[layer];
+  const float *scores = O.scores + (int64_t)bh * s.N;
+  const int Nc = s.Nc, base = tid * EPT, nvalid = Nc - base;
+  auto slot = [](int i) { return i + (i >> 5); };
+  if (tid == 0) { sc.ur[0] = 0xffffffffu; sc.ur[1] = 0u; }
+  for (int i = tid; i < Nc; i += THREADS) a_s[slot(i)] = scores[i];
+  __syncthreads();
+  float a[EPT];
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) a[e] = e < nvalid ? a_s[slot(base + e)] : 0.f;
+  const bool cand = cand_m > 0;
+  const int h = bh % s.hkv, b = bh / s.hkv;
+  int Bh, row0;
+  head_rows(s, budgets, layer, h, Bh, row0);
+  int32_t *idx = cand ? reinterpret_cast<int32_t *>(ws + w.cand_idx) + unit * kMaxCandPerHead
+                      : O.indices + (int64_t)b * s.hkv * s.B + row0;
+  uint32_t *ckey = cand ? reinterpret_cast<uint32_t *>(ws + w.cand_key) + unit * kMaxCandPerHead : nullptr;
+  const int Bp = cand ? cand_m : Bh - s.W;
+  if (Bp > 0) top_select<THREADS, EPT>(a, nvalid, base, Bp, idx, ckey, s.floor_, sc);
+  if (!cand) finish_head(s, O, b, h, Bh, row0, idx, THREADS);
+}
+
+// candsplit_kernel: head-adaptive budgets from candidate lists, one workgroup per (layer, batch
+// item).  Every head brings its best M candidates (ascending positions, with keys, its f best
+// marked); a head keeps its floor, i.e. its f best, and the rest of the layer's pool goes to the
+// best remaining candidates of all heads together, ties to the smaller head, then the smaller
+// position.  A head can keep at most f + H * (B' - f) <= M candidates, so the lists hold every
+// candidate that can be kept and the result is the same as ranking all scores.  Thread t owns the
+// entries [4t, 4t + 4) of the H lists laid end to end: that order is the tie order, and the kept
+// entries of a head come out in ascending position from one prefix sum.
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void candsplit_kernel(Shape s, LayerOutTable out, char *ws, Workspace w, int64_t unit0,
+                                                              int M) {
+  constexpr int NW = THREADS / 64, EPT = 4;
+  __shared__ MsScratch sc;
+  __shared__ int hstart[65];                           // kept entries before each head's list; [H]: all
+  const int tid = threadIdx.x, lb = blockIdx.x, layer = lb / s.batch, b = lb - layer * s.batch;
+  const LayerOut O = out.l[layer];
+  const int Nc = s.Nc, H = s.hkv, n = H * M, rest = H * (s.Bp - s.floor_);
+  const int64_t unit = unit0 + (int64_t)lb * H;        // first head of this (layer, batch item)
+  const uint32_t *cidx = reinterpret_cast<const uint32_t *>(ws + w.cand_idx) + unit * kMaxCandPerHead;
+  const uint32_t *ckey = reinterpret_cast<const uint32_t *>(ws + w.cand_key) + unit * kMaxCandPerHead;
+  int32_t *idx = O.indices + (int64_t)b * H * s.B;
+  if (tid == 0) { sc.ur[0] = 0xffffffffu; sc.ur[1] = 0u; }
+  uint32_t key[EPT], pw[EPT];
+  int head[EPT];
+  uint32_t inmask = 0, vmask = 0;                       // entries inside the lists; of those, outside the floors
+  uint32_t kmin = 0xffffffffu, kmax = 0;
+#pragma unroll
+  for (int j = 0; j < EPT; ++j) {
+    const int e = tid * EPT + j;
+    head[j] = e / M;
+    key[j] = 0; pw[j] = 0;
+    if (e < n) {
+      const int at = head[j] * kMaxCandPerHead + (e - head[j] * M);
+      key[j] = ckey[at];
+      pw[j] = cidx[at];
+      inmask |= 1u << j;
+      if (!(pw[j] & kFloorFlag)) { vmask |= 1u << j; kmin = min(kmin, key[j]); kmax = max(kmax, key[j]); }
+    }
+  }
+  __syncthreads();
+  uint32_t tau = 0xffffffffu;
+  int k = 0;
+  if (rest > 0) {
+    block_minmax_u32(kmin, kmax, sc);
+    tau = radix_threshold<THREADS, EPT>(key, vmask, kmin, kmax, rest, sc, k);
+  }
+  int ngt = 0, neq = 0;
+#pragma unroll
+  for (int j = 0; j < EPT; ++j) {
+    const bool v = ((vmask >> j) & 1u) != 0 && rest > 0;
+    ngt += (((inmask & ~vmask) >> j) & 1u) + ((v && key[j] > tau) ? 1 : 0);    // floor entries are kept as they are
+    neq += (v && key[j] == tau) ? 1 : 0;
+  }
+  int total;
+  const int packed = block_scan_excl<NW>(ngt | (neq << 16), sc, &total);
+  int seen = packed >> 16;
+  int pos = (packed & 0xffff) + min(seen, k);          // kept entries before this thread's
+  const int kept = (total & 0xffff) + min(total >> 16, k);
+  bool keep[EPT];
+#pragma unroll
+  for (int j = 0; j < EPT; ++j) {
+    const bool v = ((vmask >> j) & 1u) != 0 && rest > 0;
+    keep[j] = (((inmask & ~vmask) >> j) & 1u) != 0 || (v && key[j] > tau);
+    if (v && key[j] == tau) keep[j] = seen++ < k;
+    if (((inmask >> j) & 1u) && tid * EPT + j == head[j] * M) hstart[head[j]] = pos;   // first entry of a list
+    if (keep[j]) idx[pos + head[j] * s.W] = (int32_t)(pw[j] & ~kFloorFlag);
+    pos += keep[j] ? 1 : 0;
+  }
+  if (tid == 0) hstart[H] = kept;
+  __syncthreads();
+  // per head: count, offset, and the window behind the kept candidates
+  for (int h = tid >> 6; h < H; h += NW) {
+    const int lane = tid & 63, first = hstart[h] + h * s.W, cnt = hstart[h + 1] - hstart[h];
+    for (int wv = lane; wv < s.W; wv += 64) idx[first + cnt + wv] = Nc + wv;
+    if (lane == 0) {
+      O.counts[b * H + h] = cnt + s.W;
+      O.offsets[b * (H + 1) + h] = first;
+      if (h == H - 1) O.offsets[b * (H + 1) + H] = first + cnt + s.W;
     }
   }
 }
@@ -488,6 +672,40 @@ hipError_t launch_mixsel(const Shape &s, bool select, const LayerOutTable &out, 
   if (nc <= 1024 * 8) return launch_mixsel_e<1024, 8>(s, select, out, ws, w, unit0, nunits, in, gather_eb, cand_m, budgets, st);
   if (nc <= 1024 * 16) return launch_mixsel_e<1024, 16>(s, select, out, ws, w, unit0, nunits, in, gather_eb, cand_m, budgets, st);
   return launch_mixsel_e<1024, 32>(s, select, out, ws, w, unit0, nunits, in, gather_eb, cand_m, budgets, st);
+}
+
+template <int THREADS, int EPT>
+static hipError_t launch_topsel_e(const Shape &s, const LayerOutTable &out, char *ws, const Workspace &w, int64_t unit0,
+                                  int nunits, int cand_m, const int32_t *budgets, hipStream_t st) {
+  const size_t lds = (size_t)(s.Nc + s.Nc / 32 + 1) * 4;
+  auto kern = topsel_kernel<THREADS, EPT>;
+  static LdsLimitOnce once;
+  const hipError_t attr = once.raise(reinterpret_cast<const void *>(kern));
+  if (attr != hipSuccess) return attr;
+  hipLaunchKernelGGL(kern, dim3(nunits), dim3(THREADS), lds, st, s, out, ws, w, unit0, cand_m, budgets);
+  return hipGetLastError();
+}
+
+// Selection on scores in memory for `nunits` units starting at unit0 (requires mixsel_supported):
+// final rows, or with cand_m > 0 every head's best cand_m candidates for the head-adaptive split.
+hipError_t launch_topsel(const Shape &s, const LayerOutTable &out, char *ws, const Workspace &w, int64_t unit0, int nunits,
+                         int cand_m, const int32_t *budgets, hipStream_t st) {
+  const int nc = s.Nc;
+  if (nc <= 256 * 8) return launch_topsel_e<256, 8>(s, out, ws, w, unit0, nunits, cand_m, budgets, st);
+  if (nc <= 512 * 8) return launch_topsel_e<512, 8>(s, out, ws, w, unit0, nunits, cand_m, budgets, st);
+  if (nc <= 1024 * 8) return launch_topsel_e<1024, 8>(s, out, ws, w, unit0, nunits, cand_m, budgets, st);
+  if (nc <= 1024 * 16) return launch_topsel_e<1024, 16>(s, out, ws, w, unit0, nunits, cand_m, budgets, st);
+  return launch_topsel_e<1024, 32>(s, out, ws, w, unit0, nunits, cand_m, budgets, st);
+}
+
+// The head-adaptive split of `nlayers` layers' candidate lists of M entries per head.
+hipError_t launch_select_candidates(const Shape &s, const LayerOutTable &out, char *ws, const Workspace &w, int64_t unit0,
+                                    int nlayers, int cand_m, hipStream_t st) {
+  const int n = cand_m * s.hkv, grid = nlayers * s.batch;
+  if (n <= 256 * 4) hipLaunchKernelGGL(candsplit_kernel<256>, dim3(grid), dim3(256), 0, st, s, out, ws, w, unit0, cand_m);
+  else if (n <= 512 * 4) hipLaunchKernelGGL(candsplit_kernel<512>, dim3(grid), dim3(512), 0, st, s, out, ws, w, unit0, cand_m);
+  else hipLaunchKernelGGL(candsplit_kernel<1024>, dim3(grid), dim3(1024), 0, st, s, out, ws, w, unit0, cand_m);
+  return hipGetLastError();
 }
 
 }  // namespace mixkv

@@ -451,100 +451,6 @@ __global__ __launch_bounds__(kSelectThreads) void select_adaptive_kernel(Shape s
   }
 }
 
-// Head-adaptive budgets from candidate lists: one workgroup per (layer, batch item).  Every head
-// brings its best M candidates (ascending positions, with keys); a head keeps its floor, i.e. its
-// f best, and the rest of the pool goes to the best remaining candidates of all heads together.
-// A head can keep at most f + H * (B' - f) <= M candidates, so the lists contain every candidate
-// that can be kept and the result is the same as ranking all of them.
-__global__ __launch_bounds__(kSelectThreads) void select_candidates_kernel(Shape s, LayerOutTable out, char *ws,
-                                                                          Workspace w, int64_t unit0, int M) {
-  __shared__ uint32_t key_s[kMaxCandPerGroup];
-  __shared__ int32_t pos_s[kMaxCandPerGroup];
-  __shared__ uint8_t floor_s[kMaxCandPerGroup], keep_s[kMaxCandPerGroup];
-  __shared__ int offs[kMaxAdaptiveHeads + 1];
-  __shared__ SelectScratch sc;
-  const int lb = blockIdx.x, layer = lb / s.batch, b = lb - layer * s.batch;
-  const LayerOut O = out.l[layer];
-  const int Nc = s.Nc, H = s.hkv, f = s.floor_, n = H * M;
-  const int rest = H * (s.Bp - f);
-  const int64_t unit = unit0 + (int64_t)lb * H;                 // first head of this (layer, batch item)
-  const int32_t *cidx = reinterpret_cast<const int32_t *>(ws + w.cand_idx) + unit * kMaxCandPerHead;
-  const uint32_t *ckey = reinterpret_cast<const uint32_t *>(ws + w.cand_key) + unit * kMaxCandPerHead;
-  int32_t *idx = O.indices + (int64_t)b * H * s.B;
-  for (int e = threadIdx.x; e < n; e += blockDim.x) {
-    const int h = e / M, j = e - h * M;
-    key_s[e] = ckey[(int64_t)h * kMaxCandPerHead + j];
-    pos_s[e] = cidx[(int64_t)h * kMaxCandPerHead + j];
-  }
-  __syncthreads();
-  // floor: rank inside the head by (key descending, position ascending).  Every list is in ascending
-  // position order, so among equal keys the entries before this one are the better ones.  No
-  // short-circuit operators: the loop body must stay free of branches (with them the loop took
-  // 52 of the kernel's 74 us on a 32K-token cache; a wave per candidate with ballots, or quarters of
-  // a list per thread with atomics, are no faster than this).
-  for (int e = threadIdx.x; e < n; e += blockDim.x) {
-    const int h = e / M, j = e - h * M;
-    const uint32_t k = key_s[e];
-    const uint32_t *kh = key_s + h * M;
-    int better = 0;
-#pragma unroll 8
-    for (int o = 0; o < M; ++o) {
-      const uint32_t ko = kh[o];
-      better += (int)(ko > k) | ((int)(ko == k) & (int)(o < j));
-    }
-    floor_s[e] = better < f;
-  }
-  __syncthreads();
-  // pool: the `rest` best candidates outside the floors by (key descending, head, position
-  // ascending); list order (head, entry) is that tie order, since every list is ascending
-  uint32_t tauR = 0xffffffffu;
-  int cutR = -1;
-  if (rest > 0) {
-    auto keyfn = [&](int h, int j, uint32_t &key) {
-      key = key_s[h * M + j];
-      return floor_s[h * M + j] == 0;
-    };
-    int need;
-    radix_select(H, M, rest, keyfn, sc, &tauR, &need);
-    cutR = kth_equal_index(H, M, tauR, need, keyfn, sc);
-  }
-  for (int e = threadIdx.x; e < n; e += blockDim.x)
-    keep_s[e] = floor_s[e] || (rest > 0 && (key_s[e] > tauR || (key_s[e] == tauR && e <= cutR)));
-  __syncthreads();
-  // per head: the kept candidates are already in ascending position order; then the window
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = blockDim.x >> 6;
-  for (int h = wave; h < H; h += nw) {               // one wave per head counts its kept candidates
-    int cnt = 0;
-    for (int j0 = 0; j0 < M; j0 += 64) cnt += __popcll(__ballot(j0 + lane < M && keep_s[h * M + j0 + lane]));
-    if (lane == 0) offs[h + 1] = cnt;
-  }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    int base = 0;
-    for (int h = 0; h < H; ++h) {
-      const int cnt = offs[h + 1];
-      offs[h] = base;
-      O.counts[b * H + h] = cnt + s.W;
-      O.offsets[b * (H + 1) + h] = base;
-      base += cnt + s.W;
-    }
-    offs[H] = base;
-    O.offsets[b * (H + 1) + H] = base;
-  }
-  __syncthreads();
-  for (int h = wave; h < H; h += nw) {               // one wave per head walks its list in order
-    int at = offs[h];
-    for (int j0 = 0; j0 < M; j0 += 64) {
-      const int j = j0 + lane;
-      const bool k = j < M && keep_s[h * M + j];
-      const unsigned long long m = __ballot(k);
-      if (k) idx[at + __popcll(m & ((1ull << lane) - 1ull))] = pos_s[h * M + j];
-      at += __popcll(m);
-    }
-    for (int wv = lane; wv < s.W; wv += 64) idx[at + wv] = Nc + wv;
-  }
-}
-
 // ------------------------------------------------------------------------------------------------
 // gather_kernel: K_out[p] = K[idx[p]], V_out[p] = V[idx[p]] for the packed kept rows p of one
 // (layer, batch item); 16 bytes per lane, a row is D*EB/16 consecutive lanes (Sec. 3.1, the
@@ -611,13 +517,6 @@ int adaptive_candidates(const Shape &s) {
   const int64_t M = (int64_t)s.floor_ + (int64_t)s.hkv * (s.Bp - s.floor_);
   if (M < 1 || M > s.Nc || M > kMaxCandPerHead || M * s.hkv > kMaxCandPerGroup) return 0;
   return (int)M;
-}
-
-hipError_t launch_select_candidates(const Shape &s, const LayerOutTable &out, char *ws, const Workspace &w, int64_t unit0,
-                                    int nlayers, int cand_m, hipStream_t st) {
-  hipLaunchKernelGGL(select_candidates_kernel, dim3(nlayers * s.batch), dim3(kSelectThreads), 0, st, s, out, ws, w, unit0,
-                     cand_m);
-  return hipGetLastError();
 }
 
 int max_adaptive_heads() { return kMaxAdaptiveHeads; }

@@ -50,11 +50,20 @@ def test_fixed_budget_selection_is_bit_exact(kind, N, W, Bud, Hkv):
     np.testing.assert_array_equal(out.offsets.cpu().numpy(), np.tile(np.arange(Hkv + 1) * Bud, (Bt, 1)))
 
 
+def _candidate_list_bytes(n_layers, Bt, Hkv):
+    """What the head-adaptive selection asks of a workspace: two 1024-entry lists of 4-byte words per head."""
+    return n_layers * Bt * Hkv * 1024 * 4 * 2
+
+
+# with a workspace every head's best candidates are listed by a workgroup of its own and a small
+# kernel splits the pool; without one (or with lists too long for it: the 400-row budget) one
+# workgroup per batch item ranks the scores of all heads
+@pytest.mark.parametrize("lists", [True, False])
 @pytest.mark.parametrize("kind", ["normal", "ties", "constant"])
 @pytest.mark.parametrize("N,W,Bud,Hkv,floor", [(512, 8, 64, 4, 14), (3000, 32, 128, 3, 0), (600, 4, 50, 5, 46),
-                                               (33000, 32, 128, 4, 24)])
-def test_adaptive_budget_selection_is_bit_exact(kind, N, W, Bud, Hkv, floor):
-    print(f"[case] select adaptive kind={kind} N={N} W={W} B={Bud} Hkv={Hkv} floor={floor}", flush=True)
+                                               (33000, 32, 128, 4, 24), (3000, 32, 400, 4, 10)])
+def test_adaptive_budget_selection_is_bit_exact(kind, N, W, Bud, Hkv, floor, lists):
+    print(f"[case] select adaptive kind={kind} N={N} W={W} B={Bud} Hkv={Hkv} floor={floor} lists={lists}", flush=True)
     rng = np.random.default_rng([2, N, Bud])
     Bt = 2
     s = _scores(kind, rng, Bt, Hkv, N, W)
@@ -63,7 +72,9 @@ def test_adaptive_budget_selection_is_bit_exact(kind, N, W, Bud, Hkv, floor):
     p = B.make_params("bf16", Bt, Hkv, Hkv, 128, N, W, Bud, budget_mode="adaptive", budget_floor=floor)
     out = B.alloc_layer_out(p, "cuda:0", redundancy=False, gather=False)
     out.scores = torch.from_numpy(s).to("cuda:0")
-    B.mixkv_select(p, [out])
+    out.indices.fill_(-1)
+    ws = torch.empty(_candidate_list_bytes(1, Bt, Hkv), dtype=torch.uint8, device="cuda:0") if lists else None
+    B.mixkv_select(p, [out], ws)
     torch.cuda.synchronize()
     idx = out.indices.cpu().numpy().reshape(Bt, Hkv * Bud)
     cnt, off = out.counts.cpu().numpy(), out.offsets.cpu().numpy()
@@ -74,6 +85,34 @@ def test_adaptive_budget_selection_is_bit_exact(kind, N, W, Bud, Hkv, floor):
         for h in range(Hkv):
             want = O.select_unit(s[b, h, :N - W].astype(np.float64), int(bp[h]), N, W)
             np.testing.assert_array_equal(idx[b, off[b, h]:off[b, h + 1]], want)
+        assert off[b, Hkv] == Hkv * Bud                        # the pool is used up
+
+
+def test_adaptive_selection_over_several_layers_with_candidate_lists():
+    """Layers beyond one launch group, each with its own scores, through the candidate lists."""
+    N, W, Bud, Hkv, floor, Bt, L = 2100, 16, 96, 4, 20, 2, 34
+    print(f"[case] select adaptive layers={L} N={N} W={W} B={Bud} Hkv={Hkv} floor={floor}", flush=True)
+    rng = np.random.default_rng([5, N, Bud])
+    p = B.make_params("bf16", Bt, Hkv, Hkv, 128, N, W, Bud, budget_mode="adaptive", budget_floor=floor)
+    ss, outs = [], []
+    for l in range(L):
+        s = _scores("normal" if l % 2 else "ties", rng, Bt, Hkv, N, W)
+        out = B.alloc_layer_out(p, "cuda:0", redundancy=False, gather=False)
+        out.scores = torch.from_numpy(s).to("cuda:0")
+        ss.append(s)
+        outs.append(out)
+    ws = torch.empty(_candidate_list_bytes(L, Bt, Hkv), dtype=torch.uint8, device="cuda:0")
+    B.mixkv_select(p, outs, ws)
+    torch.cuda.synchronize()
+    for l in range(L):
+        idx = outs[l].indices.cpu().numpy().reshape(Bt, Hkv * Bud)
+        cnt, off = outs[l].counts.cpu().numpy(), outs[l].offsets.cpu().numpy()
+        for b in range(Bt):
+            bp = O.adaptive_budgets(ss[l][b, :, :N - W].astype(np.float64), Bud, W, floor)
+            np.testing.assert_array_equal(cnt[b], bp + W)
+            for h in range(Hkv):
+                want = O.select_unit(ss[l][b, h, :N - W].astype(np.float64), int(bp[h]), N, W)
+                np.testing.assert_array_equal(idx[b, off[b, h]:off[b, h + 1]], want)
 
 
 @pytest.mark.parametrize("kind", ["normal", "ties"])
