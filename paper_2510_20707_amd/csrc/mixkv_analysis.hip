@@ -133,9 +133,14 @@ __global__ __launch_bounds__(256) void blockgram_kernel(AShape a, SimOutTable ou
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       const int e = tid + 256 * k, r = e >> 4, c = e & 15;
-      const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
-      const float4 va = a0 + r < a.nb ? *reinterpret_cast<const float4 *>(Su + (int64_t)(a0 + r) * D + d0 + 4 * c) : z;
-      const float4 vb = b0 + r < a.nb ? *reinterpret_cast<const float4 *>(Su + (int64_t)(b0 + r) * D + d0 + 4 * c) : z;
+      // rows past the last block read the last one (always in bounds) and are zeroed afterwards: a
+      // conditional load of either the row or a zero constant is compiled into a load from either the
+      // row or a copy of the constant in scratch memory
+      const int ra = min(a0 + r, a.nb - 1), rb = min(b0 + r, a.nb - 1);
+      float4 va = *reinterpret_cast<const float4 *>(Su + (int64_t)ra * D + d0 + 4 * c);
+      float4 vb = *reinterpret_cast<const float4 *>(Su + (int64_t)rb * D + d0 + 4 * c);
+      if (a0 + r >= a.nb) va = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (b0 + r >= a.nb) vb = make_float4(0.f, 0.f, 0.f, 0.f);
       *reinterpret_cast<float4 *>(&sa[r][4 * c]) = va;
       *reinterpret_cast<float4 *>(&sb[r][4 * c]) = vb;
     }

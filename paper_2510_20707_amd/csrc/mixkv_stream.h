@@ -40,8 +40,12 @@ __device__ __forceinline__ f32x16 mma(const Frag &a, const Frag &b, f32x16 acc) 
   if constexpr (DT == MIXKV_BF16) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.h, b.h, acc, 0, 0, 0);
   } else {
+    // the four floats are taken out of the 16-byte member the loads wrote: reading them through the
+    // union's float array instead sends whole fragment arrays through scratch memory
+    const uint32_t au[4] = {a.q.x, a.q.y, a.q.z, a.q.w}, bu[4] = {b.q.x, b.q.y, b.q.z, b.q.w};
 #pragma unroll
-    for (int i = 0; i < 4; ++i) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.f[i], b.f[i], acc, 0, 0, 0);
+    for (int i = 0; i < 4; ++i)
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(au[i]), __uint_as_float(bu[i]), acc, 0, 0, 0);
     return acc;
   }
 }
@@ -52,7 +56,8 @@ __device__ __forceinline__ float frag_elem(const Frag &f, int j) {
     uint32_t u = f.u[j >> 1];
     return __uint_as_float((j & 1) ? (u & 0xffff0000u) : (u << 16));
   } else {
-    return f.f[j];
+    const uint32_t u[4] = {f.q.x, f.q.y, f.q.z, f.q.w};
+    return __uint_as_float(u[j]);
   }
 }
 
@@ -71,7 +76,10 @@ __device__ __forceinline__ float piece_sumsq(const Frag &f) {
     }
   } else {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) ss = fmaf(f.f[j], f.f[j], ss);
+    for (int j = 0; j < 4; ++j) {
+      const float x = frag_elem<DT>(f, j);
+      ss = fmaf(x, x, ss);
+    }
   }
   return ss;
 }

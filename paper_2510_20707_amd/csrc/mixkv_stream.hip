@@ -394,8 +394,17 @@ __global__ __launch_bounds__(kFoldThreads) void fold_kernel(Shape s, LayerOutTab
 // The exponent offsets and the mean key come from fold_kernel.  The fragments of the next key tile
 // are read from LDS into a second set of registers while the current tile is being worked on.
 // ------------------------------------------------------------------------------------------------
+// Waves per SIMD the register allocation of attn_kernel aims at: two, i.e. two four-wave workgroups
+// per compute unit (an eight-wave workgroup is two per SIMD by itself).  Four waves with two query
+// tiles of 128-element f32 rows do not fit 256 registers (their fragments are twice as wide as bf16
+// ones, and the tile loop then reloads some three hundred spilled registers per step), so they run one
+// workgroup per compute unit on the full register file.
+__host__ __device__ constexpr int attn_waves_per_simd(int dtype, int D, int waves, int tq) {
+  return (dtype == MIXKV_F32 && D == 128 && waves == 4 && tq == 2) ? 1 : 2;
+}
+
 template <int DT, int D, int WAVES, int TQ, bool SPARE>
-__global__ __launch_bounds__(WAVES * 64, 2) void attn_kernel(Shape s, LayerInTable in, LayerOutTable out, char *ws,
+__global__ __launch_bounds__(WAVES * 64, attn_waves_per_simd(DT, D, WAVES, TQ)) void attn_kernel(Shape s, LayerInTable in, LayerOutTable out, char *ws,
                                                             Workspace w, int64_t unit0, int nunits) {
   constexpr int EB = Tr<DT>::EB, EPC = Tr<DT>::EPC, NCHK = D / (2 * EPC), PPR = D * EB / 16;
   constexpr int NT = WAVES * 64, KT = chunk_tiles(DT, D), CH = KT * 32, TILE = 32 * PPR;
