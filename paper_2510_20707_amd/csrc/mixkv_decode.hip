@@ -6,8 +6,12 @@
 // inside the loop except the dot-product reduction over the lanes of a row.  Long caches are
 // split over several workgroups per head (contiguous row ranges); each leaves its running softmax
 // in the workspace and decode_merge_kernel folds them in order.
-#include "mixkv_internal.h"
-#include "mixkv_wave.h"
+//
+// bf16 caches go through the matrix cores (decode_mfma_kernel): the rows travel global -> LDS in
+// 32-row tiles, the scores of a tile against all query heads of the group are one chain of MFMAs
+// with the keys on the output rows, and the weighted values a second product with the weights as
+// they stand in the accumulators.  fp32 caches take the vector path (decode_kernel).
+#include "mixkv_stream.h"
 
 namespace mixkv {
 
@@ -22,6 +26,7 @@ struct DecodeTable { DecodeLayer l[kLayersPerLaunch]; };
 
 struct DShape {
   int32_t batch, hq, hkv, G, B, tail_len, tail_cap, packed, units_per_layer, gchunks, nsplit;
+  int32_t hpw, gt;       // query heads a workgroup serves (per group chunk), and the head stride of its partials
   float scale_log2e;
 };
 
@@ -190,32 +195,253 @@ __global__ __launch_bounds__(kDecThreads) void decode_kernel(DShape s, DecodeTab
   }
 }
 
-// Folds the nsplit partial results of one (unit, query-head group) in split order and writes the output rows.
-template <int DT, int D, int GT>
+// ------------------------------------------------------------------------------------------------
+// decode_mfma_kernel (bf16): one workgroup of D/32 waves per (layer, batch item, KV head, chunk of
+// up to 32 query heads, row range).
+//   * Tiles of 32 rows of K and of V go global -> LDS through the ring of mixkv_stream.h (direct
+//     loads, requested kLead tiles ahead, bank-rotated images); the compacted rows and the appended
+//     tail are two runs of memory, so every lane picks its row's base; rows past the range re-read
+//     the last row and are masked.
+//   * Scores: keys on the MFMA output rows, query heads on the columns (heads past the chunk are
+//     zero columns), so lane (g = lane % 32, half) holds sixteen rows' scores of head g.  Every wave
+//     forms the whole score tile and its weights: the waves agree bit for bit, and nothing crosses
+//     waves inside the loop.
+//   * Weights exp2(x - m_g) with an offset m_g that only moves when a head's sum leaves the range of
+//     a float (see stats_kernel), split into a bf16 head and a bf16 remainder; the accumulator
+//     registers of one half-wave are, in order, the contraction index of the second product, so they
+//     feed it as they stand.
+//   * Weighted values: wave w owns the 32 elements [32 w, 32 w + 32) of the output rows; its A
+//     operand is that slice of V transposed, read from the tile image two bytes at a time (8 reads
+//     per fragment), its output lane (g, half) holds head g's sixteen elements of the slice.
+// Partials and outputs have the layout of decode_kernel.
+// ------------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(D * 2, 2) void decode_mfma_kernel(DShape s, DecodeTable tab, float *part) {
+  constexpr int DT = MIXKV_BF16, EB = 2, PPR = D * EB / 16, TILE = 32 * PPR, WAVES = D / 32, RPL = 64 / PPR;
+  constexpr int NCHK = D / 16;                            // MFMAs per score tile
+  constexpr int KL = (TILE / 64 + WAVES - 1) / WAVES;     // requests per wave, tile and tensor
+  static_assert(TILE / 64 == KL * WAVES, "every wave issues the same number of requests");
+  __shared__ uint4 kring[kRing * TILE], vring[kRing * TILE];
+
+  const int tid = threadIdx.x, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int sp = blockIdx.x % s.nsplit, ugc = blockIdx.x / s.nsplit;   // row split, (unit, query-head chunk)
+  const int ul = ugc / s.gchunks, gc = ugc - ul * s.gchunks;
+  const int layer = ul / s.units_per_layer, bh = ul - layer * s.units_per_layer;
+  const int b = bh / s.hkv, h = bh - b * s.hkv;
+  const DecodeLayer L = tab.l[layer];
+  const int g0 = gc * s.hpw, ng = min(s.hpw, s.G - g0);           // query heads of this workgroup
+  const float c2 = s.scale_log2e;
+
+  // rows of this head: `cnt` compacted ones, then `tail_len` appended ones
+  const int cap = s.packed ? s.hkv * s.B : s.B;                   // rows the head's slot can hold at most
+  int row0 = s.packed ? (L.offsets ? L.offsets[b * (s.hkv + 1) + h] : 0) : 0;
+  row0 = min(max(row0, 0), cap);
+  const int cnt = min(max(L.counts[bh], 0), cap - row0);          // the clamps only guard the loads
+  const int n_all = cnt + s.tail_len;
+  const int r_begin = (int)((int64_t)n_all * sp / s.nsplit), n = (int)((int64_t)n_all * (sp + 1) / s.nsplit);   // rows [r_begin, n)
+  const int nt = (n - r_begin + 31) / 32;                         // tiles of the range
+  const int64_t slot_rows = s.packed ? (int64_t)b * s.hkv * s.B + row0 : (int64_t)bh * s.B;
+  constexpr int RB = D * EB;
+  const char *Kc = reinterpret_cast<const char *>(L.Kc) + slot_rows * RB;
+  const char *Vc = reinterpret_cast<const char *>(L.Vc) + slot_rows * RB;
+  const char *Kt = reinterpret_cast<const char *>(L.Kt) + ((int64_t)bh * s.tail_cap - cnt) * RB;   // row r >= cnt at Kt + r * RB
+  const char *Vt = reinterpret_cast<const char *>(L.Vt) + ((int64_t)bh * s.tail_cap - cnt) * RB;
+
+  const uint32_t kring_a = lds_base_of(kring), vring_a = lds_base_of(vring);
+  const int lrow = lane / PPR, lq = lane % PPR;
+  // Request tile tr of the range into its ring image: load j covers slots [64 j, 64 j + 64) of the
+  // image, i.e. rows [j RPL, (j + 1) RPL) of the tile; wave w issues the loads w, w + WAVES, ...
+  auto request = [&](int tr) {
+    const int tb = r_begin + tr * 32;
+    const uint32_t off = (uint32_t)(tr & (kRing - 1)) * (TILE * 16);
+#pragma unroll
+    for (int jj = 0; jj < KL; ++jj) {
+      const int j = jj * WAVES + wave;
+      const int trow = j * RPL + lrow;
+      const int row = min(tb + trow, n - 1);                       // rows past the range repeat its last row
+      const int64_t at = (int64_t)row * RB + (lq ^ tile_swz<DT, D>(trow)) * 16;
+      const char *kp = (row < cnt ? Kc : Kt) + at, *vp = (row < cnt ? Vc : Vt) + at;
+      __builtin_amdgcn_global_load_lds((glb_void_t *)kp, (lds_void_t *)(uintptr_t)(kring_a + off + j * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_void_t *)vp, (lds_void_t *)(uintptr_t)(vring_a + off + j * 1024), 16, 0, 0);
+    }
+  };
+#pragma unroll
+  for (int j = 0; j < kLead; ++j)
+    if (j < nt) request(j);
+
+  // the query heads in fragment form: lane (g, half) holds every other 16-byte piece of head g's row
+  Frag qf[NCHK];
+  {
+    const bool live = l32 < ng;
+    const char *qrow = reinterpret_cast<const char *>(L.Q) + ((int64_t)(b * s.hq + h * s.G + g0 + (live ? l32 : 0)) * D) * EB +
+                       half * 16;
+#pragma unroll
+    for (int c = 0; c < NCHK; ++c) {
+      const uint4 v = *reinterpret_cast<const uint4 *>(qrow + c * 32);
+      qf[c].q = live ? v : make_uint4(0, 0, 0, 0);
+    }
+  }
+  // nothing may be pending when the tile loop is entered: its waits count the requests issued inside it
+  wait_vm<0>();
+
+  float m = -INFINITY, l = 0.f;      // head g's offset and this half-wave's share of the sum of weights
+  f32x16 o;                          // head g's sixteen output elements of this wave's slice, times 2^-m
+#pragma unroll
+  for (int i = 0; i < 16; ++i) o[i] = 0.f;
+  // two-byte index into a V tile image of element d = 32 wave + l32 of tile row r
+  const int vd = wave * 32 + l32;
+  auto v_at = [&](int r) { return r * (PPR * 8) + (((vd >> 3) ^ tile_swz<DT, D>(r)) << 3) + (vd & 7); };
+
+  auto tile_step = [&](auto slot_c, int t) {
+    constexpr int SLOT = decltype(slot_c)::value;
+    __builtin_amdgcn_sched_barrier(0);
+    wait_tile<2 * KL>(t, nt);
+    lds_barrier();
+    if (t + kLead < nt) request(t + kLead);              // into the image tile t - 1 has left
+    __builtin_amdgcn_sched_barrier(0);
+    const uint4 *img = kring + SLOT * TILE;
+    const uint16_t *vimg = reinterpret_cast<const uint16_t *>(vring + SLOT * TILE);
+    const int tb = r_begin + t * 32;
+
+    // ---- scores of the tile's 32 rows against the query heads
+    f32x16 acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    {
+      Frag kf[NCHK];
+#pragma unroll
+      for (int c = 0; c < NCHK; ++c) kf[c].q = read_key_frag<DT, D>(img, 0, c, l32, half);
+#pragma unroll
+      for (int c = 0; c < NCHK; ++c) acc = mma<DT>(kf[c], qf[c], acc);
+    }
+    // ---- this wave's slice of V, transposed: fragment ks holds for element d the rows of the
+    // accumulator registers [8 ks, 8 ks + 8) of this half-wave
+    Frag vf[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int j = 0; j < 8; j += 2) {
+        const int ra = 8 * (2 * ks + (j >> 2)) + 4 * half + (j & 3);
+        vf[ks].u[j >> 1] = (uint32_t)vimg[v_at(ra)] | ((uint32_t)vimg[v_at(ra + 1)] << 16);
+      }
+    if (tb + 32 > n) {                                   // the range ends inside the tile: mask
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[i] = (tb + 8 * (i >> 2) + 4 * half + (i & 3) >= n) ? -INFINITY : acc[i];
+    }
+    // ---- weights.  The terms are formed with the offset as it stands; only if the sum leaves the
+    // range (or there is no offset yet) does the wave move the offset to the tile's maximum, rescale
+    // what it has and form the terms again.  Both half-waves of a head share the offset.
+    float p[16], sum[4];
+    {
+      const float nmu = -m;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        p[i] = fast_exp2(fmaf(acc[i], c2, nmu));
+        sum[i & 3] = i < 4 ? p[i] : sum[i & 3] + p[i];
+      }
+    }
+    float lnew = l + ((sum[0] + sum[1]) + (sum[2] + sum[3]));
+    if (__builtin_amdgcn_ballot_w64(!(lnew < 1e30f)) != 0) {
+      float tmax = fmaxf(acc[0], acc[1]);
+#pragma unroll
+      for (int i = 2; i < 16; i += 2) tmax = fmaxf(fmaxf(tmax, acc[i]), acc[i + 1]);
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+      const float mn = fmaxf(m, tmax * c2);              // c2 > 0: scaling commutes with max
+      const float mu = (mn == -INFINITY) ? 0.f : mn;
+      const float f = fast_exp2(m - mu);                 // 0 while there is no offset yet
+      float s2[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        p[i] = fast_exp2(fmaf(acc[i], c2, -mu));
+        s2[i & 3] += p[i];
+      }
+      lnew = l * f + ((s2[0] + s2[1]) + (s2[2] + s2[3]));
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[i] *= f;
+      m = mn;
+    }
+    l = lnew;
+    // ---- weighted values: bf16 head and remainder of every weight
+    Frag ph[2], pl[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float x = p[8 * ks + j];
+        const __bf16 hi = (__bf16)x;
+        ph[ks].h[j] = hi;
+        pl[ks].h[j] = (__bf16)(x - (float)hi);
+      }
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      o = mma<DT>(vf[ks], ph[ks], o);
+      o = mma<DT>(vf[ks], pl[ks], o);
+    }
+  };
+  static_assert(kRing == 4, "unrolled four times below");
+  for (int t = 0; t < nt; t += kRing) {
+    tile_step(std::integral_constant<int, 0>{}, t);
+    if (t + 1 < nt) tile_step(std::integral_constant<int, 1>{}, t + 1);
+    if (t + 2 < nt) tile_step(std::integral_constant<int, 2>{}, t + 2);
+    if (t + 3 < nt) tile_step(std::integral_constant<int, 3>{}, t + 3);
+  }
+
+  // ---- the head's sum of weights from both half-waves (fixed order), then the outputs
+  const float lo = __shfl_xor(l, 32);
+  const float tot = half == 0 ? l + lo : lo + l;
+  if (l32 >= ng) return;
+  if (s.nsplit > 1) {                                    // partial: weighted values, then (offset, sum)
+    float *dst = part + ((int64_t)blockIdx.x * s.gt + l32) * (D + 2);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) dst[wave * 32 + 8 * (i >> 2) + 4 * half + (i & 3)] = o[i];
+    if (wave == 0 && half == 0) { dst[D] = m; dst[D + 1] = tot; }
+    return;
+  }
+  uint16_t *out = reinterpret_cast<uint16_t *>(L.out) + (int64_t)(b * s.hq + h * s.G + g0 + l32) * D + wave * 32;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) out[8 * (i >> 2) + 4 * half + (i & 3)] = bf16_rne(tot > 0.f ? o[i] / tot : 0.f);
+}
+
+// Folds the nsplit <= 16 partial results of one (unit, query-head chunk) in split order and writes the
+// output rows: one thread per output element (blockIdx.y walks the chunk's elements 256 at a time), every
+// split's three values requested before the first is used.
+constexpr int kDecMaxSplit = 16;
+template <int DT, int D>
 __global__ __launch_bounds__(256) void decode_merge_kernel(DShape s, DecodeTable tab, const float *part) {
   const int ugc = blockIdx.x, ul = ugc / s.gchunks, gc = ugc - ul * s.gchunks;
   const int layer = ul / s.units_per_layer, bh = ul - layer * s.units_per_layer;
   const int b = bh / s.hkv, h = bh - b * s.hkv;
-  const int g0 = gc * kDecHeads, ng = min(GT, s.G - g0);
-  void *out = tab.l[layer].out;
-  for (int idx = threadIdx.x; idx < ng * D; idx += 256) {
-    const int g = idx / D, d = idx - g * D;
-    const float *src = part + ((int64_t)ugc * s.nsplit * GT + g) * (D + 2);
-    const int64_t step = (int64_t)GT * (D + 2);                    // from one split to the next
-    float mn = -INFINITY;
-    for (int sp = 0; sp < s.nsplit; ++sp) mn = fmaxf(mn, src[sp * step + D]);
-    const float mu = mn == -INFINITY ? 0.f : mn;
-    float acc = 0.f, tot = 0.f;
-    for (int sp = 0; sp < s.nsplit; ++sp) {
-      const float f = __builtin_amdgcn_exp2f(src[sp * step + D] - mu);
-      acc = fmaf(src[sp * step + d], f, acc);
-      tot = fmaf(src[sp * step + D + 1], f, tot);
-    }
-    const float res = tot > 0.f ? acc / tot : 0.f;
-    const int64_t at = (int64_t)(b * s.hq + h * s.G + g0 + g) * D + d;
-    if constexpr (DT == MIXKV_BF16) reinterpret_cast<uint16_t *>(out)[at] = bf16_rne(res);
-    else reinterpret_cast<float *>(out)[at] = res;
+  const int g0 = gc * s.hpw, ng = min(s.hpw, s.G - g0);
+  const int idx = blockIdx.y * 256 + threadIdx.x;
+  if (idx >= ng * D) return;
+  const int g = idx / D, d = idx - g * D;
+  const float *src = part + ((int64_t)ugc * s.nsplit * s.gt + g) * (D + 2);
+  const int64_t step = (int64_t)s.gt * (D + 2);                    // from one split to the next
+  float pm[kDecMaxSplit], pa[kDecMaxSplit], pl[kDecMaxSplit];
+#pragma unroll
+  for (int sp = 0; sp < kDecMaxSplit; ++sp) {
+    const bool on = sp < s.nsplit;
+    const float *at = src + (on ? sp : 0) * step;
+    pm[sp] = on ? at[D] : -INFINITY;
+    pa[sp] = on ? at[d] : 0.f;
+    pl[sp] = on ? at[D + 1] : 0.f;
   }
+  float mn = -INFINITY;
+#pragma unroll
+  for (int sp = 0; sp < kDecMaxSplit; ++sp) mn = fmaxf(mn, pm[sp]);
+  const float mu = mn == -INFINITY ? 0.f : mn;
+  float acc = 0.f, tot = 0.f;
+#pragma unroll
+  for (int sp = 0; sp < kDecMaxSplit; ++sp) {                      // splits in order; absent ones add zeros
+    const float f = __builtin_amdgcn_exp2f(pm[sp] - mu);
+    acc = fmaf(pa[sp], f, acc);
+    tot = fmaf(pl[sp], f, tot);
+  }
+  const float res = tot > 0.f ? acc / tot : 0.f;
+  const int64_t at = (int64_t)(b * s.hq + h * s.G + g0 + g) * D + d;
+  if constexpr (DT == MIXKV_BF16) reinterpret_cast<uint16_t *>(tab.l[layer].out)[at] = bf16_rne(res);
+  else reinterpret_cast<float *>(tab.l[layer].out)[at] = res;
 }
 
 template <int DT, int D, int GT>
@@ -223,7 +449,8 @@ static void launch_decode_gt(const DShape &s, const DecodeTable &t, int nunits, 
   const dim3 grid((unsigned)(nunits * s.gchunks * s.nsplit)), block(kDecThreads);
   hipLaunchKernelGGL((decode_kernel<DT, D, GT>), grid, block, 0, st, s, t, part);
   if (s.nsplit > 1)
-    hipLaunchKernelGGL((decode_merge_kernel<DT, D, GT>), dim3((unsigned)(nunits * s.gchunks)), dim3(256), 0, st, s, t, part);
+    hipLaunchKernelGGL((decode_merge_kernel<DT, D>), dim3((unsigned)(nunits * s.gchunks), (unsigned)((s.gt * D + 255) / 256)), dim3(256), 0, st, s, t,
+                       part);
 }
 
 template <int DT, int D>
@@ -236,14 +463,43 @@ static void launch_decode_g(const DShape &s, const DecodeTable &t, int nunits, i
   }
 }
 
-// Query heads carried per workgroup and row splits per head for a shape.
-static void decode_config(const Shape &sh, int tail_len, int *gt, int *gchunks, int *nsplit) {
+template <int D>
+static void launch_decode_mfma(const DShape &s, const DecodeTable &t, int nunits, float *part, hipStream_t st) {
+  const dim3 grid((unsigned)(nunits * s.gchunks * s.nsplit)), block(D * 2);
+  hipLaunchKernelGGL((decode_mfma_kernel<D>), grid, block, 0, st, s, t, part);
+  if (s.nsplit > 1)
+    hipLaunchKernelGGL((decode_merge_kernel<MIXKV_BF16, D>), dim3((unsigned)(nunits * s.gchunks), (unsigned)((s.gt * D + 255) / 256)), dim3(256),
+                       0, st, s, t, part);
+}
+
+constexpr int kDecMfmaHeads = 32;    // query heads of one group a matrix-core workgroup serves: the columns of a tile
+constexpr int kDecTargetWgs = 512;   // two resident workgroups on each of 256 compute units
+
+// Query heads served per workgroup (hpw), their stride in the partials (gt), chunks of query heads
+// per group and row splits per head for a shape.  Host only; depends on nothing but the arguments.
+static void decode_config(const Shape &sh, int dtype, int n_layers, int tail_len, int *hpw, int *gt, int *gchunks,
+                          int *nsplit) {
+  const int rows = sh.B + tail_len;                     // per head, on average in the packed layouts
+  if (dtype == MIXKV_BF16) {
+    // Matrix-core path.  A workgroup's fixed cost (dependent loads of counts, queries and the first
+    // tiles) is a few microseconds, so rows are split only as far as it takes to put two workgroups
+    // on every compute unit, and never below 256 rows a piece (short caches: no merge launch).
+    *hpw = kDecMfmaHeads;
+    *gt = sh.G < kDecMfmaHeads ? sh.G : kDecMfmaHeads;
+    *gchunks = (sh.G + kDecMfmaHeads - 1) / kDecMfmaHeads;
+    const int64_t wgs = (int64_t)n_layers * sh.units_per_layer * *gchunks;
+    int ns = (int)(kDecTargetWgs / (wgs < 1 ? 1 : wgs));
+    const int by_rows = rows / 256;
+    if (ns > by_rows) ns = by_rows;
+    *nsplit = ns < 1 ? 1 : (ns > kDecMaxSplit ? kDecMaxSplit : ns);
+    return;
+  }
+  *hpw = kDecHeads;
   *gt = 1;
   while (*gt < sh.G && *gt < kDecHeads) *gt <<= 1;
   *gchunks = (sh.G + kDecHeads - 1) / kDecHeads;
-  const int rows = sh.B + tail_len;                     // per head, on average in the packed layouts
   int ns = (rows + 383) / 384;
-  *nsplit = ns < 1 ? 1 : (ns > 16 ? 16 : ns);
+  *nsplit = ns < 1 ? 1 : (ns > kDecMaxSplit ? kDecMaxSplit : ns);
 }
 static size_t decode_part_bytes(const Shape &sh, int n_layers, int gt, int gchunks, int nsplit) {
   if (nsplit == 1) return 0;
@@ -259,8 +515,8 @@ extern "C" mixkv_status mixkv_decode_workspace_size(const mixkv_params *params, 
   mixkv_status st = make_shape(params, &sh);
   if (st != MIXKV_OK) return st;
   if (!bytes || n_layers < 1 || n_layers > MIXKV_MAX_LAYERS || tail_len < 0) return MIXKV_ERR_INVALID_ARG;
-  int gt, gchunks, nsplit;
-  decode_config(sh, tail_len, &gt, &gchunks, &nsplit);
+  int hpw, gt, gchunks, nsplit;
+  decode_config(sh, params->dtype, n_layers, tail_len, &hpw, &gt, &gchunks, &nsplit);
   *bytes = (decode_part_bytes(sh, n_layers, gt, gchunks, nsplit) + 255) / 256 * 256;
   return MIXKV_OK;
 }
@@ -274,8 +530,8 @@ extern "C" mixkv_status mixkv_decode_attention(const mixkv_params *params, const
   if (st != MIXKV_OK) return st;
   if (!layers || n_layers < 1 || n_layers > MIXKV_MAX_LAYERS) return MIXKV_ERR_INVALID_ARG;
   if (tail_len < 0 || tail_capacity < tail_len) return MIXKV_ERR_INVALID_ARG;
-  int gt, gchunks, nsplit;
-  decode_config(sh, tail_len, &gt, &gchunks, &nsplit);
+  int hpw, gt, gchunks, nsplit;
+  decode_config(sh, params->dtype, n_layers, tail_len, &hpw, &gt, &gchunks, &nsplit);
   const size_t need = decode_part_bytes(sh, n_layers, gt, gchunks, nsplit);
   if (need > 0) {
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return MIXKV_ERR_INVALID_ARG;
@@ -292,7 +548,7 @@ extern "C" mixkv_status mixkv_decode_attention(const mixkv_params *params, const
   DShape s;
   s.batch = sh.batch; s.hq = sh.hq; s.hkv = sh.hkv; s.G = sh.G; s.B = sh.B;
   s.tail_len = tail_len; s.tail_cap = tail_capacity; s.packed = packed; s.units_per_layer = sh.units_per_layer;
-  s.gchunks = gchunks; s.nsplit = nsplit;
+  s.gchunks = gchunks; s.nsplit = nsplit; s.hpw = hpw; s.gt = gt;
   s.scale_log2e = sh.scale_log2e;
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
   for (int l0 = 0; l0 < n_layers; l0 += kLayersPerLaunch) {
@@ -309,8 +565,8 @@ extern "C" mixkv_status mixkv_decode_attention(const mixkv_params *params, const
                                  (size_t)l0 * sh.units_per_layer * gchunks * nsplit * gt * (sh.D + 2)
                            : nullptr;
     if (params->dtype == MIXKV_BF16) {
-      if (sh.D == 128) launch_decode_g<MIXKV_BF16, 128>(s, t, nunits, gt, part, stream);
-      else launch_decode_g<MIXKV_BF16, 64>(s, t, nunits, gt, part, stream);
+      if (sh.D == 128) launch_decode_mfma<128>(s, t, nunits, part, stream);
+      else launch_decode_mfma<64>(s, t, nunits, part, stream);
     } else {
       if (sh.D == 128) launch_decode_g<MIXKV_F32, 128>(s, t, nunits, gt, part, stream);
       else launch_decode_g<MIXKV_F32, 64>(s, t, nunits, gt, part, stream);

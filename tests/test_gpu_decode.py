@@ -92,6 +92,22 @@ def test_group_sizes_and_ragged_row_counts(dtype, D, Hq, Hkv, B):
     _decode_and_check(wl, [0], 7, 9)
 
 
+def test_bf16_more_query_heads_than_one_tile_of_columns():
+    # G = 40: the matrix-core path serves 32 query heads per workgroup, so a KV head takes two (32 + 8)
+    wl = WL["c2"].with_(name="wide-group-dec", seq_len=300, window=5, n_q_heads=80, n_kv_heads=2, budget=70, batch=1,
+                        text_prefix=16, text_suffix_start=260)
+    _decode_and_check(wl, [0], 3, 4)
+
+
+@pytest.mark.parametrize("budget", [90, 700])
+def test_bf16_offsets_that_have_to_move(budget):
+    # logits with a spread of a few hundred: the weights are formed against an offset that only moves
+    # when a sum leaves the range of a float, which here happens in several tiles and in every row
+    # range; the softmax is close to one-hot, so the output is a value row almost bit for bit
+    wl = WL["c2"].with_(name="steep-dec", softmax_scale=30.0)
+    _decode_and_check(wl, [0], 9, 12, budget=budget)
+
+
 def test_c3_whole_cache_and_more_layers_than_one_launch_group():
     _decode_and_check(WL["c3"], [0, 9, 27], 1, 4)
     wl = WL["c1"].with_(n_layers=35)
