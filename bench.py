@@ -42,7 +42,7 @@ MFMA_BF16_PEAK = 2.5e15
 # the profiled command (default workload, budget and variant, three copies) and unchanged sources.
 PROFILED_TRAFFIC = {
     "sources": ["mixkv_stream.hip", "mixkv_stream.h"],
-    "sources_sha256": "3222e2713fb8db05406580cde69368a02896b7cfd821298bfd24b9a6fcc15c54",
+    "sources_sha256": "f75b42fdd250bd95552541286be4fc687cbc665876eb759294aec97b0497374a",
     "kernels": {"stats": ("stats_kernel<bf16,128,8,1>", 513.6e6), "attn": ("attn_kernel<bf16,128,4,2,spare>", 278.3e6)},
 }
 
