@@ -122,6 +122,9 @@ def test_long_caches_are_split_over_workgroups():
     _decode_and_check(wl, [0], 2, 4, head_budgets=hb, budget_mode="per_head", budget=900)
     wl = WL["c1"].with_(n_layers=34)
     _decode_and_check(wl, list(range(34)), 3, 4, budget=500)          # f32, two launch groups of partials
+    # bf16 with 64-element rows (two waves per workgroup on the matrix-core path), 12 query heads per KV head, 905 rows
+    wl = WL["c2"].with_(name="d64-long", head_dim=64, n_q_heads=24, n_kv_heads=2, seq_len=2048, text_suffix_start=1900)
+    _decode_and_check(wl, [0], 5, 8, budget=900)
 
 
 def test_split_needs_its_workspace():
