@@ -287,21 +287,32 @@ def main():
                   torch.randn((wl.batch, wl.n_kv_heads, max(t, 1), wl.head_dim), generator=gen, device=dev).to(dt_))
                  for _ in layers]
         dout = [torch.empty_like(q) for q in qn]
-        dcall = B.PreparedDecode(p, outs, tails, qn, dout, t)
-        for _ in range(args.warmup):
-            dcall.run(stream)
+        rows = units * (budget + t)                                              # rows read, K and V each
+        dec_bytes = rows * wl.head_dim * e * 2 + 2 * len(layers) * wl.batch * wl.n_q_heads * wl.head_dim * e
+        # Copies of the compacted cache, used round-robin, so that a call finds as little of its rows in the
+        # chip's caches as a decoding step would (the model's weights stream through between two steps): as
+        # many as it takes to pass twice the 256 MB Infinity Cache, at most eight.
+        import types
+        ncop = max(1, min(8, -(-2 * 256 * 2 ** 20 // dec_bytes)))
+        dcalls = [B.PreparedDecode(p, outs, tails, qn, dout, t)]
+        for _ in range(ncop - 1):
+            clone = [types.SimpleNamespace(K_out=o.K_out.clone(), V_out=o.V_out.clone(), counts=o.counts, offsets=o.offsets)
+                     for o in outs]
+            dcalls.append(B.PreparedDecode(p, clone, tails, qn, dout, t))
+        for i in range(max(args.warmup, ncop)):
+            dcalls[i % ncop].run(stream)
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         ev0.record(stream)
-        for _ in range(args.steps):
-            dcall.run(stream)
+        for i in range(args.steps):
+            dcalls[i % ncop].run(stream)
         ev1.record(stream)
         torch.cuda.synchronize()
         dec_s = ev0.elapsed_time(ev1) * 1e-3 / args.steps
-        rows = units * (budget + t)                                              # rows read, K and V each
-        dec_bytes = rows * wl.head_dim * e * 2 + 2 * len(layers) * wl.batch * wl.n_q_heads * wl.head_dim * e
         dec = {"tail_len": t, "us_per_call": dec_s * 1e6, "layers_per_call": len(layers), "algorithmic_bytes": dec_bytes,
                "achieved_GBps": dec_bytes / dec_s / 1e9, "hbm_frac": dec_bytes / dec_s / HBM_PEAK,
-               "note": "same cache every call (it stays in the caches of the chip at this size)"}
+               "cache_copies_round_robin": ncop,
+               "note": ("the copies together exceed the 256 MB Infinity Cache" if ncop * dec_bytes > 256 * 2 ** 20
+                        else "the copies together still fit the 256 MB Infinity Cache (not the 32 MB of L2)")}
     sim = None
     if args.similarity_block > 0:
         blk = args.similarity_block
